@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path: multi-model paged GQA decode attention over one shared
+KV page pool (plus balloon_resize latency), one MI355X.
+
+One "step" = one decode step of the co-located models of the workload: one grouped
+decode_attention_multi call (attention kernel + split-K merge) over every active
+model's batch.  Inputs are resident in HBM before the timed region starts.  The
+default workload is cfg 2 (two co-located models, lognormal context lengths); three
+independently seeded replicas are rotated so that a step never re-reads what the
+previous step left in the 256 MB Infinity Cache.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X datasheet HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5])
+    ap.add_argument("--size", default="full", choices=["full", "small"])
+    ap.add_argument("--replicas", type=int, default=3)
+    ap.add_argument("--chunk-pages", type=int, default=0, help="force the split-K chunk size (0 = automatic)")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
+    ap.add_argument("--no-balloon", action="store_true")
+    return ap.parse_args()
+
+
+def build_replicas(gpu, cfg_id, size, n):
+    import copy
+    from workloads.scenarios import Runner, make_config
+    reps = []
+    for r in range(n):
+        cfg = copy.deepcopy(make_config(cfg_id, size))
+        cfg.seed += 17 * r
+        t0 = time.time()
+        reps.append(Runner(gpu, cfg).setup())
+        print(f"[bench] replica {r}: pool {cfg.pool_bytes >> 20} MiB, KV {reps[-1].kv_bytes_step() / 1e9:.3f} GB, "
+              f"set up in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+    return reps
+
+
+def device_inputs(torch, rep, step):
+    import numpy as np
+    mids = rep.active_models()
+    qs = [torch.from_numpy(rep.queries(step, mi).view(np.int16)).cuda() for mi in mids]
+    ctxs = [torch.from_numpy(rep.ctx[mi]).cuda() for mi in mids]
+    outs = [torch.empty((rep.cfg.models[mi].batch, rep.cfg.models[mi].q_heads, rep.cfg.models[mi].head_dim),
+                        dtype=torch.float32, device="cuda") for mi in mids]
+    return [rep.models[mi] for mi in mids], qs, ctxs, outs
+
+
+def balloon_latency(gpu, torch):
+    """Wall-clock latency of balloon_resize (launch + kernel + result read-back) on a
+    160 GB-class pool shape scaled to fit beside the benchmark pools: inflate to 176
+    frames (one cfg-3 activation), fill, release, deflate to 0; median of 50 cycles."""
+    import numpy as np
+    pool = gpu.pool_create(8 << 30, 16, 2 << 20)
+    m = gpu.model_register(pool, 32, 8, 128, 0, 32, 512)
+    seqs = np.arange(32, dtype=np.int32)
+    ctx = np.full(32, 2816, dtype=np.int32)        # 176 blocks each -> 5632 blocks = 176 frames
+    t_inf, t_def, t_res, t_rel = [], [], [], []
+    for _ in range(50):
+        t0 = time.perf_counter(); assert gpu.balloon_resize(m, 176) == 176; t1 = time.perf_counter()
+        assert gpu.seq_reserve_batch(m, seqs, ctx) == 5632; t2 = time.perf_counter()
+        for s in range(32):
+            gpu.seq_release(m, s)
+        t3 = time.perf_counter(); assert gpu.balloon_resize(m, 0) == 0; t4 = time.perf_counter()
+        t_inf.append(t1 - t0); t_res.append(t2 - t1); t_rel.append((t3 - t2) / 32); t_def.append(t4 - t3)
+    gpu.model_unregister(m)
+    gpu.pool_destroy(pool)
+    med = lambda x: float(np.median(x) * 1e6)
+    return {"inflate_176_frames_us": med(t_inf), "deflate_176_frames_us": med(t_def),
+            "reserve_batch_5632_blocks_us": med(t_res), "release_176_blocks_us": med(t_rel),
+            "kind": "host wall clock per call, median of 50"}
+
+
+def cpu_baseline(rep, seconds):
+    """The oracle, as it stands, on a bounded sample of the same workload: the same
+    bookkeeping calls, KV written only for the sampled sequences, decode attention of
+    those sequences on all host cores."""
+    import numpy as np
+    from oracle import Oracle
+    from workloads.scenarios import Runner, kv_bytes
+    orc = Oracle()
+    cfg = rep.cfg
+    # calibrate on a tiny slice, then size the sample for ~`seconds`
+    probe = Runner(orc, cfg, fill=set(), write_kv=True).setup()
+    order = sorted(((int(probe.ctx[mi][s]), mi, s) for mi in range(len(cfg.models))
+                    for s in range(cfg.models[mi].batch)), key=lambda x: x[0])
+    probe.teardown()
+    shortest = order[len(order) // 8]
+    def run(sample):
+        fill = {(mi, int(s)) for _, mi, s in sample}
+        r = Runner(orc, cfg, fill=fill).setup()
+        total_bytes, t_total = 0, 0.0
+        for mi in sorted({mi for _, mi, _ in sample}):
+            seqs = np.array([s for _, m2, s in sample if m2 == mi], dtype=np.int64)
+            rows = orc.block_table_rows(r.models[mi], cfg.models[mi].batch)[seqs]
+            q = r.queries(0, mi)[seqs]
+            ctx = r.ctx[mi][seqs]
+            t0 = time.perf_counter()
+            rc, _ = orc.decode_attention(r.models[mi], q, ctx, rows)
+            t_total += time.perf_counter() - t0
+            assert rc == 0
+            total_bytes += kv_bytes(cfg, cfg.models[mi], ctx)
+        r.teardown()
+        return total_bytes, t_total
+    b0, t0 = run([shortest])
+    rate = b0 / max(t0, 1e-6)
+    budget = rate * seconds
+    sample, acc = [], 0
+    for c, mi, s in order[::-1][len(order) // 4::3] + order:      # a spread of lengths first
+        spec = cfg.models[mi]
+        nb = kv_bytes(cfg, spec, np.array([c]))
+        if (c, mi, s) in sample or acc + nb > budget:
+            continue
+        sample.append((c, mi, s))
+        acc += nb
+    if not sample:
+        sample = [shortest]
+    b, t = run(sample)
+    return {"value": b / t / 1e9, "unit": "GB/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{len(sample)} of {len(order)} sequences of step 0 ({b / 1e6:.1f} MB of KV, "
+                      f"{t:.1f} s, fp64, {orc.num_threads()} OpenMP threads)",
+            "seconds": t}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2505_04021_amd import PrismKV
+
+    gpu = PrismKV("cuda:0")
+    gpu.set_chunk_pages(args.chunk_pages)
+    reps = build_replicas(gpu, args.config, args.size, args.replicas)
+    inputs = [device_inputs(torch, rep, 0) for rep in reps]
+    kv_per_rep = [rep.kv_bytes_step() for rep in reps]
+
+    def step(i):
+        mids, qs, ctxs, outs = inputs[i % len(reps)]
+        rc = gpu.decode_attention_multi_dev(mids, qs, ctxs, outs)
+        assert rc == 0, (rc, gpu.last_error())
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    gpu.timing_enable(True)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    n_rec, attn_ms, merge_ms = gpu.timing_read()
+    gpu.timing_enable(False)
+    assert gpu.device_errors() == 0
+    dev_ms = ev0.elapsed_time(ev1)
+
+    total_bytes = sum(kv_per_rep[i % len(reps)] for i in range(args.steps))
+    ms_per_step = wall * 1e3 / args.steps
+    gbps = total_bytes / wall / 1e9
+    attn_avg_ms = attn_ms / max(n_rec, 1)
+    rec_bytes = sum(kv_per_rep[i % len(reps)] for i in range(n_rec)) / max(n_rec, 1)
+    attn_gbps = rec_bytes / (attn_avg_ms * 1e-3) / 1e9 if n_rec else 0.0
+
+    result = {
+        "metric": "kv_read_gbps_multi_model_paged_decode",
+        "value": round(gbps, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if args.config != 5 else "fp8_e4m3",
+        "data": "synthetic",
+        "config": {"workload": reps[0].cfg.name, "cfg": args.config, "size": args.size,
+                   "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
+                   "chunk_pages": args.chunk_pages or "auto"},
+        "step_us": round(ms_per_step * 1e3, 2),
+        "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "device_ms_per_step": round(dev_ms / args.steps, 5),
+        "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
+                     "traffic": None, "avg_launch_us": round(attn_avg_ms * 1e3, 2),
+                     "merge_avg_us": round(merge_ms / max(n_rec, 1) * 1e3, 2), "launches": n_rec},
+    }
+    if not args.no_balloon:
+        result["balloon_resize"] = balloon_latency(gpu, torch)
+    if args.cpu_seconds > 0:
+        result["cpu_baseline"] = cpu_baseline(reps[0], args.cpu_seconds)
+    for rep in reps:
+        rep.teardown()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

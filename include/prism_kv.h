@@ -1,0 +1,195 @@
+/*
+ * prism_kv.h — C-ABI boundary of the MI355X (gfx950) shared-pool paged decode
+ * attention library (libprismkv.so).
+ *
+ * The library is the hot path behind GPU memory ballooning for multi-LLM
+ * co-serving: several co-located models keep their KV cache in ONE physical page
+ * pool; each model's share of the pool (its balloon) grows and shrinks between
+ * decode steps; decode attention reads K and V through per-sequence block tables.
+ *
+ * Vocabulary
+ *   frame   fixed-size physical unit of the pool (the paper's 2 MB physical page,
+ *           Sec. 4.2 D3).  Owned by at most one model (D2: models never share a
+ *           page).  balloon_resize counts frames.
+ *   block   page_tokens tokens of one model's K and V for all its KV heads (the
+ *           paper's token block / KV block, Background "KV cache and
+ *           PagedAttention").  block_bytes = 2*page_tokens*kv_heads*head_dim*e,
+ *           e = 2 for bf16 and 1 for e4m3, plus a 128-byte scale header for e4m3.
+ *   slot    place for one block inside a frame; slots = frame_bytes / block_bytes.
+ *   block id = frame * slots + slot  (what block tables hold).
+ *
+ * Conventions
+ *   - Every function returns 0 or a non-negative count on success and a negative
+ *     PKV_E_* code on error.  Nothing throws or aborts.  A failing call leaves the
+ *     bookkeeping state unchanged (balloon deflate clamps instead of failing).
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  Unless stated, buffers belong to the caller.
+ *   - Work is enqueued on the HIP stream given to pkv_set_stream (default: the
+ *     null stream).  Bookkeeping calls that return a count wait for their kernel;
+ *     kv_write and the decode_attention family only enqueue.
+ *   - All bookkeeping (free stack, ownership, frame lists, slot bitmaps, block
+ *     tables) lives in device memory and is changed only by the library's kernels.
+ *   - Calls are not thread-safe; one thread drives one library instance.
+ */
+#ifndef PRISM_KV_H
+#define PRISM_KV_H
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    PKV_OK = 0,
+    PKV_E_ARG = -1,         /* bad argument value */
+    PKV_E_HANDLE = -2,      /* unknown pool / model id */
+    PKV_E_NOMEM = -3,       /* inflate: not enough free frames; or no id / memory left */
+    PKV_E_BALLOON = -4,     /* reserve: not enough free slots in the model's balloon */
+    PKV_E_SHAPE = -5,       /* block does not fit a frame, q_heads % kv_heads != 0 */
+    PKV_E_RANGE = -6,       /* index outside a table / buffer too small */
+    PKV_E_BUSY = -7,        /* destroy / unregister while frames are still owned */
+    PKV_E_INTERNAL = -8,
+    PKV_E_DEVICE = -9,      /* a HIP call failed; see pkv_last_error() */
+    PKV_E_UNSUPPORTED = -10 /* shape the gfx950 kernels do not cover */
+};
+
+enum { PKV_BF16 = 0, PKV_E4M3 = 1 };
+
+typedef struct pkv_stats {
+    int64_t n_frames, n_free;   /* pool */
+    int64_t owned[64];          /* frames per model id (0 for ids not in this pool) */
+    int64_t used_blocks[64];    /* reserved blocks per model id */
+} pkv_stats;
+
+/* ---- library ------------------------------------------------------------ */
+
+/* Select the HIP stream (a hipStream_t, e.g. torch.cuda.current_stream().cuda_stream)
+ * all later calls enqueue on.  NULL = the null stream. */
+int pkv_set_stream(void *hip_stream);
+/* Text of the last HIP / library error on this thread (never NULL). */
+const char *pkv_last_error(void);
+/* Sticky device-side error flags raised by kernels that only enqueue (bit 0: a
+ * block id outside the pool was met in decode_attention; that page was skipped).
+ * Synchronises the stream; clears the flags. */
+int pkv_device_errors(void);
+
+/* ---- pool (paper Sec. 4.2: one physical pool for all co-located models) -- */
+
+/* Create a pool of `bytes` bytes cut into 2 MiB frames (D3: 2 MB pages);
+ * page_tokens = tokens per block.  The library allocates the device memory.
+ * Returns the pool id (lowest unused, 0..7).  The free stack starts so that
+ * frames are handed out in the order 0, 1, 2, ... */
+int pool_create(size_t bytes, int page_tokens);
+/* Same with an explicit frame size and optionally caller-owned device memory
+ * (device_base, dev, at least bytes long, 256-byte aligned; NULL = allocate). */
+int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *device_base);
+/* Fails with PKV_E_BUSY while any model is registered in the pool. */
+int pool_destroy(int pool);
+/* Set the order in which a still-untouched pool hands out frames: perm (host,
+ * n = number of frames) is a permutation of the frame ids, perm[0] first. */
+int pool_seed_free_order(int pool, const uint32_t *perm, size_t n);
+
+/* ---- models (D2: automatic token-block mapping, per-model segregation) --- */
+
+/* Register a model in the most recently created pool, with room for 256
+ * sequences of up to 2048 blocks.  dtype = PKV_BF16 | PKV_E4M3 (KV storage;
+ * queries are always bf16).  Returns the model id (lowest unused, 0..63). */
+int model_register(int q_heads, int kv_heads, int head_dim, int dtype);
+int model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
+                      int max_seqs, int max_blocks_per_seq);
+/* The model must own no frames (PKV_E_BUSY otherwise). */
+int model_unregister(int model);
+
+/* ---- balloon (D1: per-model limits that shrink and grow) ------------------ */
+
+/* Make the model own `pages` frames.
+ *   inflate: frames are popped from the pool's free stack and appended to the
+ *            model's frame list; PKV_E_NOMEM if the pool has too few (no change).
+ *   deflate: empty frames are returned to the free stack, newest first, until
+ *            the target is met; frames that still hold blocks stay.
+ * Returns the number of frames owned afterwards (>= pages on a clamped deflate). */
+long balloon_resize(int model, long pages);
+
+/* Grow sequence `seq`'s block-table row to ceil(ctx_len / page_tokens) blocks,
+ * taking the lowest free slots of the model's frames in frame-list order.
+ * Returns the number of blocks added; PKV_E_BALLOON if the balloon has too few
+ * free slots (no change); PKV_E_RANGE beyond max_blocks_per_seq. */
+int seq_reserve(int model, int seq, int ctx_len);
+/* Same effect as seq_reserve for (seqs[i], ctx_lens[i]), i = 0..n-1 in order, in
+ * one kernel launch; refused as a whole when the total does not fit.
+ * seqs, ctx_lens: host, n <= 2048. */
+int seq_reserve_batch(int model, int n, const int32_t *seqs, const int32_t *ctx_lens);
+/* Free all blocks of the row; returns how many (0 for an empty row). */
+int seq_release(int model, int seq);
+
+/* Device pointer to the model's block table, int32 [max_seqs][*row_stride],
+ * owned by the library, valid until model_unregister. */
+const int32_t *model_block_table(int model, int *row_stride);
+
+/* ---- KV data -------------------------------------------------------------- */
+
+/* Scatter tokens [tok_begin, tok_begin + n_tok) of sequence `seq` from logical
+ * layout into its reserved blocks.  k, v: dev, [n_tok][kv_heads][head_dim] bf16
+ * values or e4m3 codes.  e4m3 only: k_scale, v_scale: dev, fp32
+ * [blocks touched][kv_heads], row 0 = the block holding tok_begin; the value of an
+ * element is decode(code) * scale.  Enqueues only. */
+int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const void *v,
+             const float *k_scale, const float *v_scale);
+
+/* ---- decode attention (Background: paged attention over the block table) -- */
+
+/* Batch shape used by decode_attention: `batch` sequences, caller block tables
+ * with `row_stride` int32 entries per row. */
+int model_set_batch(int model, int batch, int row_stride);
+
+/* out[s][h][:] = softmax_t( q[s][h] . K[t][h/g] / sqrt(head_dim) ) V[t][h/g][:]
+ * over t < ctx_lens[s], g = q_heads / kv_heads, K/V read through the block table.
+ *   q           dev, bf16 [batch][q_heads][head_dim]
+ *   block_table dev, int32 [batch][row_stride] block ids; NULL = the library's own
+ *               table, rows 0..batch-1
+ *   ctx_lens    dev, int32 [batch]; 0 gives a zero output row
+ *   out         dev, fp32 [batch][q_heads][head_dim]
+ * fp32 accumulation.  Enqueues only. */
+int decode_attention(int model, const void *q, const int32_t *block_table,
+                     const int32_t *ctx_lens, float *out);
+int decode_attention_ex(int model, int batch, const void *q, const int32_t *block_table,
+                        int row_stride, const int32_t *ctx_lens, float *out);
+/* One grouped launch over several models of one pool (the multi-model decode
+ * step); each uses the library's own block table rows 0..batches[i]-1.
+ * models, batches, q, ctx_lens, out: host arrays of n_models entries holding
+ * ids / sizes / dev pointers. */
+int decode_attention_multi(int n_models, const int *models, const int *batches,
+                           const void *const *q, const int32_t *const *ctx_lens,
+                           float *const *out);
+
+/* ---- observation ----------------------------------------------------------- */
+
+/* Canonical image of the bookkeeping state as little-endian int32 words:
+ *   "PKVS", version 1, n_frames, page_tokens, n_free, free stack bottom..top,
+ *   owner[n_frames] (-1 = free), n_models, then per model in id order:
+ *   id, q_heads, kv_heads, head_dim, dtype, slots, owned, frames[owned], nbits,
+ *   ceil(nbits/32) words of slot bits (bit j = slot j%slots of frame j/slots),
+ *   max_seqs, n_rows, then per non-empty row: seq, len, block ids.
+ * host_buf: host.  Returns the byte size needed; writes only if cap suffices.
+ * Synchronises the stream. */
+long pool_export_state(int pool, void *host_buf, size_t cap);
+int pool_stats(int pool, pkv_stats *out);
+
+/* Per-kernel timing for measurements: while enabled, every decode_attention* call
+ * brackets its attention kernel and its merge kernel with HIP events on the
+ * library's stream (at most 8192 calls are recorded).  pkv_timing_read waits for
+ * the stream, returns the number of recorded calls and the summed kernel times in
+ * milliseconds, and clears the record. */
+int pkv_timing_enable(int on);
+long pkv_timing_read(double *attention_ms, double *merge_ms);
+/* Tuning knob for measurements: pages per split-K chunk (0 = automatic). */
+int pkv_set_chunk_pages(int pages);
+/* Host-side check of the multiply-shift division the kernels use to split a block
+ * id into (frame, slot): returns n / d computed that way. */
+uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,240 @@
+"""ctypes binding of libprismkv.so: argument marshalling only.
+
+Every method has the name of the C entry point it calls.  Device buffers are torch
+tensors on the GPU (torch is used for device memory and streams, nothing else);
+numpy inputs are copied to the device first.  No step of the path runs in Python.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+PKV_BF16, PKV_E4M3 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def lib_path():
+    return os.path.join(_HERE, "libprismkv.so")
+
+
+def _load():
+    path = lib_path()
+    if not os.path.exists(path):
+        from . import build as _build
+        _build.build()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with paper_2505_04021_amd/build.py (no CPU fallback exists)")
+    lib = C.CDLL(path)
+    i, l, sz, vp, u32 = C.c_int, C.c_long, C.c_size_t, C.c_void_p, C.c_uint32
+    sig = {
+        "pkv_set_stream": (i, [vp]),
+        "pkv_last_error": (C.c_char_p, []),
+        "pkv_device_errors": (i, []),
+        "pkv_set_chunk_pages": (i, [i]),
+        "pkv_debug_fastdiv": (u32, [u32, u32]),
+        "pkv_timing_enable": (i, [i]),
+        "pkv_timing_read": (l, [C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "pool_create": (i, [sz, i]),
+        "pool_create_ex": (i, [sz, i, sz, vp]),
+        "pool_destroy": (i, [i]),
+        "pool_seed_free_order": (i, [i, vp, sz]),
+        "model_register": (i, [i, i, i, i]),
+        "model_register_ex": (i, [i, i, i, i, i, i, i]),
+        "model_unregister": (i, [i]),
+        "balloon_resize": (l, [i, l]),
+        "seq_reserve": (i, [i, i, i]),
+        "seq_reserve_batch": (i, [i, i, vp, vp]),
+        "seq_release": (i, [i, i]),
+        "model_block_table": (vp, [i, C.POINTER(i)]),
+        "kv_write": (i, [i, i, i, i, vp, vp, vp, vp]),
+        "model_set_batch": (i, [i, i, i]),
+        "decode_attention": (i, [i, vp, vp, vp, vp]),
+        "decode_attention_ex": (i, [i, i, vp, vp, i, vp, vp]),
+        "decode_attention_multi": (i, [i, vp, vp, vp, vp, vp]),
+        "pool_export_state": (l, [i, vp, sz]),
+        "pool_stats": (i, [i, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    return lib
+
+
+EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_chunk_pages", "pkv_debug_fastdiv",
+           "pkv_timing_enable", "pkv_timing_read",
+           "pool_create", "pool_create_ex", "pool_destroy", "pool_seed_free_order", "model_register",
+           "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
+           "seq_release", "model_block_table", "kv_write", "model_set_batch", "decode_attention",
+           "decode_attention_ex", "decode_attention_multi", "pool_export_state", "pool_stats"]
+
+
+class PrismKV:
+    """One per process; the library holds global pool / model tables."""
+
+    name = "gpu"
+
+    def __init__(self, device="cuda:0"):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("PrismKV needs a GPU: the HIP path has no CPU fallback")
+        self.torch = torch
+        self.device = torch.device(device)
+        self.lib = _load()
+        self._shape = {}
+        self._keep = {}
+        self.use_current_stream()
+
+    # ---- plumbing
+    def use_current_stream(self):
+        s = self.torch.cuda.current_stream(self.device)
+        return self.lib.pkv_set_stream(C.c_void_p(s.cuda_stream))
+
+    def last_error(self):
+        return self.lib.pkv_last_error().decode()
+
+    def device_errors(self):
+        return self.lib.pkv_device_errors()
+
+    def set_chunk_pages(self, pages):
+        return self.lib.pkv_set_chunk_pages(pages)
+
+    def timing_enable(self, on=True):
+        return self.lib.pkv_timing_enable(1 if on else 0)
+
+    def timing_read(self):
+        """(recorded calls, attention kernel ms, merge kernel ms), summed since the last read."""
+        a, m = C.c_double(0), C.c_double(0)
+        n = self.lib.pkv_timing_read(C.byref(a), C.byref(m))
+        return n, a.value, m.value
+
+    def _dev(self, a, dtype=None):
+        """torch device tensor for a numpy array / tensor; dtype is a torch dtype to view as."""
+        t = self.torch
+        if a is None:
+            return None
+        if isinstance(a, np.ndarray):
+            if a.dtype == np.uint16:
+                a = t.from_numpy(np.ascontiguousarray(a).view(np.int16))
+            else:
+                a = t.from_numpy(np.ascontiguousarray(a))
+        a = a.to(self.device).contiguous()
+        return a
+
+    @staticmethod
+    def _p(tensor):
+        return None if tensor is None else C.c_void_p(tensor.data_ptr())
+
+    # ---- pool
+    def pool_create(self, nbytes, page_tokens, frame_bytes=None, storage=None):
+        """storage: optional torch uint8 device tensor to use as the pool memory."""
+        if frame_bytes is None and storage is None:
+            return self.lib.pool_create(nbytes, page_tokens)
+        base = None
+        if storage is not None:
+            assert storage.is_cuda and storage.numel() * storage.element_size() >= nbytes
+            base = C.c_void_p(storage.data_ptr())
+        pool = self.lib.pool_create_ex(nbytes, page_tokens, frame_bytes or (2 << 20), base)
+        if pool >= 0 and storage is not None:
+            self._keep[("pool", pool)] = storage
+        return pool
+
+    def pool_destroy(self, pool):
+        rc = self.lib.pool_destroy(pool)
+        if rc == 0:
+            self._keep.pop(("pool", pool), None)
+        return rc
+
+    def pool_seed_free_order(self, pool, perm):
+        perm = np.ascontiguousarray(perm, dtype=np.uint32)
+        return self.lib.pool_seed_free_order(pool, perm.ctypes.data_as(C.c_void_p), perm.size)
+
+    # ---- models
+    def model_register(self, pool, q_heads, kv_heads, head_dim, dtype, max_seqs=None, max_blocks=None):
+        m = self.lib.model_register_ex(pool, q_heads, kv_heads, head_dim, dtype, max_seqs or 256, max_blocks or 2048)
+        if m >= 0:
+            self._shape[m] = (q_heads, kv_heads, head_dim, dtype)
+        return m
+
+    def model_unregister(self, model):
+        return self.lib.model_unregister(model)
+
+    def balloon_resize(self, model, frames):
+        return self.lib.balloon_resize(model, frames)
+
+    def seq_reserve(self, model, seq, ctx_len):
+        return self.lib.seq_reserve(model, seq, ctx_len)
+
+    def seq_reserve_batch(self, model, seqs, ctx_lens):
+        seqs = np.ascontiguousarray(seqs, dtype=np.int32)
+        ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        assert seqs.size == ctx_lens.size
+        return self.lib.seq_reserve_batch(model, seqs.size, seqs.ctypes.data_as(C.c_void_p),
+                                          ctx_lens.ctypes.data_as(C.c_void_p))
+
+    def seq_release(self, model, seq):
+        return self.lib.seq_release(model, seq)
+
+    def model_block_table(self, model):
+        """(device pointer, row stride) of the library-owned block table."""
+        stride = C.c_int(0)
+        p = self.lib.model_block_table(model, C.byref(stride))
+        return p, stride.value
+
+    # ---- data
+    def kv_write(self, model, seq, tok_begin, k, v, k_scale=None, v_scale=None):
+        _, hkv, d, _ = self._shape[model]
+        k, v = self._dev(k), self._dev(v)
+        assert tuple(k.shape[1:]) == (hkv, d) and k.shape == v.shape
+        ks, vs = self._dev(k_scale), self._dev(v_scale)
+        rc = self.lib.kv_write(model, seq, tok_begin, k.shape[0], self._p(k), self._p(v), self._p(ks), self._p(vs))
+        # the call only enqueues: keep the staging tensors alive until the stream has used them
+        self.torch.cuda.current_stream(self.device).synchronize()
+        return rc
+
+    def model_set_batch(self, model, batch, row_stride):
+        return self.lib.model_set_batch(model, batch, row_stride)
+
+    def decode_attention_dev(self, model, q, ctx_lens, out, block_table=None):
+        """All arguments are device tensors; only enqueues.  Returns the library's code."""
+        b = ctx_lens.numel()
+        if block_table is None:
+            return self.lib.decode_attention_ex(model, b, self._p(q), None, 0, self._p(ctx_lens), self._p(out))
+        return self.lib.decode_attention_ex(model, b, self._p(q), self._p(block_table), block_table.shape[1],
+                                            self._p(ctx_lens), self._p(out))
+
+    def decode_attention(self, model, q, ctx_lens, block_table=None):
+        """Convenience for tests: host or device inputs -> (code, out as numpy fp32 [B][Hq][D])."""
+        t = self.torch
+        hq, _, d, _ = self._shape[model]
+        q = self._dev(q)
+        ctx = self._dev(np.ascontiguousarray(ctx_lens, dtype=np.int32) if isinstance(ctx_lens, np.ndarray) else ctx_lens)
+        bt = None
+        if block_table is not None:
+            bt = self._dev(np.ascontiguousarray(block_table, dtype=np.int32)
+                           if isinstance(block_table, np.ndarray) else block_table)
+        out = t.empty((ctx.numel(), hq, d), dtype=t.float32, device=self.device)
+        rc = self.decode_attention_dev(model, q, ctx, out, bt)
+        t.cuda.current_stream(self.device).synchronize()
+        return rc, out.cpu().numpy()
+
+    def decode_attention_multi_dev(self, models, qs, ctxs, outs):
+        """One grouped launch; lists of device tensors.  Only enqueues."""
+        n = len(models)
+        ids = (C.c_int * n)(*models)
+        bs = (C.c_int * n)(*[c.numel() for c in ctxs])
+        qp = (C.c_void_p * n)(*[q.data_ptr() for q in qs])
+        cp = (C.c_void_p * n)(*[c.data_ptr() for c in ctxs])
+        op = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
+        return self.lib.decode_attention_multi(n, ids, bs, qp, cp, op)
+
+    # ---- state
+    def pool_export_state(self, pool):
+        n = self.lib.pool_export_state(pool, None, 0)
+        if n < 0:
+            raise RuntimeError(f"pool_export_state failed: {n} {self.last_error()}")
+        buf = np.empty(n // 4, dtype=np.int32)
+        n2 = self.lib.pool_export_state(pool, buf.ctypes.data_as(C.c_void_p), buf.nbytes)
+        assert n2 == n
+        return buf

@@ -1,0 +1,615 @@
+// Host side of libprismkv: the C-ABI of include/prism_kv.h.
+//
+// Handles argument checks, device allocations and kernel launches.  It never
+// computes bookkeeping or attention results itself: the page-pool state lives in
+// HBM and changes only through the kernels in pool_kernels.hip; the host keeps just
+// the shapes and a shadow of each row's length (a deterministic function of the
+// successful calls) for argument validation.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <vector>
+
+#include "pkv_internal.h"
+
+namespace {
+
+struct Pool {
+    bool live = false;
+    size_t bytes = 0, frame_bytes = 0;
+    int T = 0;
+    int64_t n_frames = 0;
+    uint8_t *base = nullptr;
+    bool own_base = false;
+    PoolDev dev{};
+};
+
+struct Model {
+    bool live = false;
+    int pool = -1;
+    int Hq = 0, Hkv = 0, D = 0, dtype = 0, g = 0;
+    size_t block_bytes = 0;
+    int slots = 0;
+    int batch = 0, row_stride = 0;          // model_set_batch
+    int64_t owned = 0;                      // shadow of the device counter
+    int64_t used_blocks = 0;
+    std::vector<int32_t> row_len;           // shadow
+    ModelDev dev{};
+    float *ws = nullptr;                    // split-K partials
+    size_t ws_floats = 0;
+};
+
+Pool g_pools[PKV_MAX_POOLS];
+Model g_models[PKV_MAX_MODELS];
+int g_last_pool = -1;
+hipStream_t g_stream = nullptr;
+BookResult *g_res = nullptr;       // pinned host
+int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
+uint32_t *g_err = nullptr;         // device error flags
+int g_chunk_pages = 0;
+bool g_timing = false;
+std::vector<hipEvent_t> g_events;   // triples: before attention, after attention, after merge
+size_t g_events_used = 0;
+constexpr size_t kMaxTimedLaunches = 8192;
+thread_local char g_errbuf[256] = "";
+
+int fail_hip(hipError_t e, const char *what) {
+    snprintf(g_errbuf, sizeof g_errbuf, "%s: %s", what, hipGetErrorString(e));
+    return PKV_E_DEVICE;
+}
+#define HIP_TRY(call)                                   \
+    do {                                                \
+        hipError_t e_ = (call);                         \
+        if (e_ != hipSuccess) return fail_hip(e_, #call); \
+    } while (0)
+
+int lib_init() {
+    if (g_res) return PKV_OK;
+    HIP_TRY(hipHostMalloc((void **)&g_res, sizeof(BookResult), hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc((void **)&g_ops, sizeof(int32_t) * 2 * PKV_MAX_BATCH_OPS, hipHostMallocDefault));
+    HIP_TRY(hipMalloc((void **)&g_err, sizeof(uint32_t)));
+    HIP_TRY(hipMemset(g_err, 0, sizeof(uint32_t)));
+    return PKV_OK;
+}
+
+Pool *get_pool(int id) { return (id >= 0 && id < PKV_MAX_POOLS && g_pools[id].live) ? &g_pools[id] : nullptr; }
+Model *get_model(int id) { return (id >= 0 && id < PKV_MAX_MODELS && g_models[id].live) ? &g_models[id] : nullptr; }
+
+// run one bookkeeping kernel and wait for its result
+template <class F>
+int64_t book_call(F launch) {
+    g_res->value = PKV_E_INTERNAL;
+    g_res->aux0 = g_res->aux1 = 0;
+    hipError_t e = launch();
+    if (e != hipSuccess) return fail_hip(e, "bookkeeping launch");
+    e = hipStreamSynchronize(g_stream);
+    if (e != hipSuccess) return fail_hip(e, "bookkeeping sync");
+    return g_res->value;
+}
+
+void free_model_dev(Model &m) {
+    (void)hipFree(m.dev.frames); (void)hipFree(m.dev.bits); (void)hipFree(m.dev.mark); (void)hipFree(m.dev.rows);
+    (void)hipFree(m.dev.row_len); (void)hipFree(m.dev.counters); (void)hipFree(m.ws);
+    m.dev = ModelDev{};
+    m.ws = nullptr;
+    m.ws_floats = 0;
+}
+
+int pick_chunk_pages(const Model &m, bool own_table) {
+    if (g_chunk_pages > 0) return g_chunk_pages;
+    // Aim for several waves per SIMD over the whole chip while keeping the split-K
+    // partials a few percent of the KV bytes; the host knows how many blocks the
+    // model has reserved when the library's own table is used.
+    if (!own_table) return 16;
+    const int64_t page_items = m.used_blocks * m.Hkv;
+    int c = 32;
+    while (c > 4 && page_items / c < 3 * 4096) c >>= 1;
+    return c;
+}
+
+int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *table, int row_stride,
+              const int32_t *ctx_lens, float *out) {
+    Pool &p = g_pools[m.pool];
+    const bool own = table == nullptr;
+    d.pool_base = p.base;
+    d.q = (const uint16_t *)q;
+    d.table = own ? m.dev.rows : table;
+    d.row_stride = own ? m.dev.max_blocks : row_stride;
+    d.ctx_lens = ctx_lens;
+    d.out = out;
+    d.err = g_err;
+    d.frame_bytes = p.frame_bytes;
+    d.block_bytes = m.block_bytes;
+    d.slots_div = fastdiv_make((uint32_t)m.slots);
+    d.max_block_id = (uint32_t)(p.n_frames * m.slots);
+    d.batch = batch;
+    d.Hq = m.Hq; d.Hkv = m.Hkv; d.g = m.g; d.D = m.D; d.dtype = m.dtype;
+    d.chunk_pages = pick_chunk_pages(m, own);
+    d.max_chunks = (d.row_stride + d.chunk_pages - 1) / d.chunk_pages;
+    d.n_items = batch * m.Hkv * d.max_chunks;
+    d.item_begin = 0;
+    d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m.D));
+    const size_t need = d.max_chunks > 1 ? (size_t)d.n_items * m.g * (m.D + 2) : 0;
+    if (need > m.ws_floats) {
+        HIP_TRY(hipStreamSynchronize(g_stream));
+        (void)hipFree(m.ws);
+        m.ws = nullptr;
+        m.ws_floats = 0;
+        HIP_TRY(hipMalloc((void **)&m.ws, need * sizeof(float)));
+        m.ws_floats = need;
+    }
+    d.ws = m.ws;
+    return PKV_OK;
+}
+
+hipEvent_t *next_events() {
+    if (!g_timing || g_events_used + 3 > 3 * kMaxTimedLaunches) return nullptr;
+    while (g_events.size() < g_events_used + 3) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        g_events.push_back(e);
+    }
+    hipEvent_t *p = &g_events[g_events_used];
+    g_events_used += 3;
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pkv_timing_enable(int on) {
+    g_timing = on != 0;
+    g_events_used = 0;
+    return PKV_OK;
+}
+
+long pkv_timing_read(double *attention_ms, double *merge_ms) {
+    HIP_TRY(hipStreamSynchronize(g_stream));
+    double a = 0.0, m = 0.0;
+    for (size_t i = 0; i + 3 <= g_events_used; i += 3) {
+        float t = 0.f;
+        HIP_TRY(hipEventElapsedTime(&t, g_events[i], g_events[i + 1]));
+        a += t;
+        HIP_TRY(hipEventElapsedTime(&t, g_events[i + 1], g_events[i + 2]));
+        m += t;
+    }
+    if (attention_ms) *attention_ms = a;
+    if (merge_ms) *merge_ms = m;
+    const long n = (long)(g_events_used / 3);
+    g_events_used = 0;
+    return n;
+}
+
+int pkv_set_stream(void *hip_stream) {
+    g_stream = (hipStream_t)hip_stream;
+    return PKV_OK;
+}
+
+const char *pkv_last_error(void) { return g_errbuf; }
+
+int pkv_device_errors(void) {
+    int rc = lib_init();
+    if (rc) return rc;
+    uint32_t v = 0;
+    HIP_TRY(hipStreamSynchronize(g_stream));
+    HIP_TRY(hipMemcpy(&v, g_err, sizeof v, hipMemcpyDeviceToHost));
+    if (v) HIP_TRY(hipMemset(g_err, 0, sizeof v));
+    return (int)v;
+}
+
+int pkv_set_chunk_pages(int pages) {
+    if (pages < 0 || pages > 4096) return PKV_E_ARG;
+    g_chunk_pages = pages;
+    return PKV_OK;
+}
+
+uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d) {
+    if (d == 0) return 0;
+    return fastdiv_div(n, fastdiv_make(d));
+}
+
+/* ------------------------------------------------------------------ pool */
+
+int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *device_base) {
+    if (page_tokens <= 0 || frame_bytes == 0 || bytes < frame_bytes) return PKV_E_ARG;
+    if (frame_bytes % 256 != 0 || ((uintptr_t)device_base & 255) != 0) return PKV_E_ARG;
+    const int64_t n_frames = (int64_t)(bytes / frame_bytes);
+    if (n_frames > 0x7fffffffLL / 4) return PKV_E_ARG;
+    int rc = lib_init();
+    if (rc) return rc;
+    int id = -1;
+    for (int i = 0; i < PKV_MAX_POOLS; ++i)
+        if (!g_pools[i].live) { id = i; break; }
+    if (id < 0) return PKV_E_NOMEM;
+    Pool p;
+    p.bytes = bytes; p.frame_bytes = frame_bytes; p.T = page_tokens; p.n_frames = n_frames;
+    if (device_base) {
+        p.base = (uint8_t *)device_base;
+    } else {
+        hipError_t e = hipMalloc((void **)&p.base, (size_t)n_frames * frame_bytes);
+        if (e != hipSuccess) { fail_hip(e, "hipMalloc(pool)"); return PKV_E_NOMEM; }
+        p.own_base = true;
+    }
+    p.dev.n_frames = n_frames;
+    hipError_t e = hipMalloc((void **)&p.dev.owner, sizeof(int32_t) * n_frames);
+    if (e == hipSuccess) e = hipMalloc((void **)&p.dev.free_stack, sizeof(uint32_t) * n_frames);
+    if (e == hipSuccess) e = hipMalloc((void **)&p.dev.pos, sizeof(int32_t) * n_frames);
+    if (e == hipSuccess) e = hipMalloc((void **)&p.dev.n_free, sizeof(int64_t));
+    if (e == hipSuccess) e = pkv_launch_pool_init(p.dev, nullptr, g_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(g_stream);
+    if (e != hipSuccess) {
+        (void)hipFree(p.dev.owner); (void)hipFree(p.dev.free_stack); (void)hipFree(p.dev.pos); (void)hipFree(p.dev.n_free);
+        if (p.own_base) (void)hipFree(p.base);
+        return fail_hip(e, "pool_create");
+    }
+    p.live = true;
+    g_pools[id] = p;
+    g_last_pool = id;
+    return id;
+}
+
+int pool_create(size_t bytes, int page_tokens) {
+    return pool_create_ex(bytes, page_tokens, (size_t)2 << 20, nullptr);
+}
+
+int pool_destroy(int pool) {
+    Pool *p = get_pool(pool);
+    if (!p) return PKV_E_HANDLE;
+    for (int m = 0; m < PKV_MAX_MODELS; ++m)
+        if (g_models[m].live && g_models[m].pool == pool) return PKV_E_BUSY;
+    HIP_TRY(hipStreamSynchronize(g_stream));
+    (void)hipFree(p->dev.owner); (void)hipFree(p->dev.free_stack); (void)hipFree(p->dev.pos); (void)hipFree(p->dev.n_free);
+    if (p->own_base) (void)hipFree(p->base);
+    *p = Pool{};
+    if (g_last_pool == pool) g_last_pool = -1;
+    return PKV_OK;
+}
+
+int pool_seed_free_order(int pool, const uint32_t *perm, size_t n) {
+    Pool *p = get_pool(pool);
+    if (!p) return PKV_E_HANDLE;
+    if (!perm || (int64_t)n != p->n_frames) return PKV_E_ARG;
+    for (int m = 0; m < PKV_MAX_MODELS; ++m)      // only while every frame is still free
+        if (g_models[m].live && g_models[m].pool == pool && g_models[m].owned != 0) return PKV_E_ARG;
+    std::vector<uint8_t> seen(n, 0);
+    for (size_t i = 0; i < n; ++i) {
+        if (perm[i] >= n || seen[perm[i]]) return PKV_E_ARG;
+        seen[perm[i]] = 1;
+    }
+    uint32_t *dperm = nullptr;
+    HIP_TRY(hipMalloc((void **)&dperm, sizeof(uint32_t) * n));
+    hipError_t e = hipMemcpyAsync(dperm, perm, sizeof(uint32_t) * n, hipMemcpyHostToDevice, g_stream);
+    if (e == hipSuccess) e = pkv_launch_pool_init(p->dev, dperm, g_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(g_stream);
+    (void)hipFree(dperm);
+    if (e != hipSuccess) return fail_hip(e, "pool_seed_free_order");
+    return PKV_OK;
+}
+
+/* ----------------------------------------------------------------- model */
+
+int model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dtype, int max_seqs,
+                      int max_blocks_per_seq) {
+    Pool *p = get_pool(pool);
+    if (!p) return PKV_E_HANDLE;
+    if (q_heads <= 0 || kv_heads <= 0 || head_dim <= 0 || max_seqs <= 0 || max_blocks_per_seq <= 0)
+        return PKV_E_ARG;
+    if (dtype != PKV_BF16 && dtype != PKV_E4M3) return PKV_E_ARG;
+    if (max_seqs > PKV_MAX_SEQS) return PKV_E_ARG;
+    if (q_heads % kv_heads != 0) return PKV_E_SHAPE;
+    const size_t e = dtype == PKV_BF16 ? 2 : 1;
+    size_t block_bytes = (size_t)2 * p->T * kv_heads * head_dim * e;
+    if (dtype == PKV_E4M3) {
+        if ((size_t)kv_heads * 2 * sizeof(float) > PKV_FP8_HEADER) return PKV_E_SHAPE;
+        block_bytes += PKV_FP8_HEADER;
+    }
+    const size_t slots = p->frame_bytes / block_bytes;
+    if (slots == 0) return PKV_E_SHAPE;
+    // what the gfx950 kernels are built for
+    if (p->T != 16 || (head_dim != 64 && head_dim != 128) || q_heads / kv_heads > 16) return PKV_E_UNSUPPORTED;
+    int id = -1;
+    for (int i = 0; i < PKV_MAX_MODELS; ++i)
+        if (!g_models[i].live) { id = i; break; }
+    if (id < 0) return PKV_E_NOMEM;
+    Model m;
+    m.pool = pool;
+    m.Hq = q_heads; m.Hkv = kv_heads; m.D = head_dim; m.dtype = dtype; m.g = q_heads / kv_heads;
+    m.block_bytes = block_bytes;
+    m.slots = (int)slots;
+    m.row_len.assign(max_seqs, 0);
+    ModelDev &d = m.dev;
+    d.model_id = id;
+    d.slots = (int)slots;
+    d.wpf = (int)((slots + 31) / 32);
+    d.max_seqs = max_seqs;
+    d.max_blocks = max_blocks_per_seq;
+    d.page_tokens = p->T;
+    const int64_t nf = p->n_frames;
+    hipError_t err = hipMalloc((void **)&d.frames, sizeof(uint32_t) * nf);
+    if (err == hipSuccess) err = hipMalloc((void **)&d.bits, sizeof(uint32_t) * nf * d.wpf);
+    if (err == hipSuccess) err = hipMalloc((void **)&d.mark, (size_t)nf);
+    if (err == hipSuccess) err = hipMalloc((void **)&d.rows, sizeof(int32_t) * (size_t)max_seqs * max_blocks_per_seq);
+    if (err == hipSuccess) err = hipMalloc((void **)&d.row_len, sizeof(int32_t) * max_seqs);
+    if (err == hipSuccess) err = hipMalloc((void **)&d.counters, sizeof(int64_t) * 2);
+    if (err == hipSuccess) err = hipMemsetAsync(d.rows, 0, sizeof(int32_t) * (size_t)max_seqs * max_blocks_per_seq, g_stream);
+    if (err == hipSuccess) err = hipMemsetAsync(d.row_len, 0, sizeof(int32_t) * max_seqs, g_stream);
+    if (err == hipSuccess) err = hipMemsetAsync(d.counters, 0, sizeof(int64_t) * 2, g_stream);
+    if (err == hipSuccess) err = hipStreamSynchronize(g_stream);
+    if (err != hipSuccess) {
+        free_model_dev(m);
+        fail_hip(err, "model_register");
+        return PKV_E_NOMEM;
+    }
+    m.live = true;
+    g_models[id] = m;
+    return id;
+}
+
+int model_register(int q_heads, int kv_heads, int head_dim, int dtype) {
+    if (g_last_pool < 0) return PKV_E_HANDLE;
+    return model_register_ex(g_last_pool, q_heads, kv_heads, head_dim, dtype, 256, 2048);
+}
+
+int model_unregister(int model) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (m->owned != 0) return PKV_E_BUSY;
+    HIP_TRY(hipStreamSynchronize(g_stream));
+    free_model_dev(*m);
+    *m = Model{};
+    return PKV_OK;
+}
+
+/* --------------------------------------------------------------- balloon */
+
+long balloon_resize(int model, long pages) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (pages < 0) return PKV_E_ARG;
+    Pool &p = g_pools[m->pool];
+    if (pages > p.n_frames) return PKV_E_NOMEM;
+    int64_t r;
+    if (pages > m->owned) {
+        r = book_call([&] { return pkv_launch_inflate(p.dev, m->dev, pages, g_res, g_stream); });
+    } else if (pages < m->owned) {
+        r = book_call([&] { return pkv_launch_deflate(p.dev, m->dev, pages, g_res, g_stream); });
+    } else {
+        return (long)m->owned;
+    }
+    if (r >= 0) m->owned = r;
+    return (long)r;
+}
+
+int seq_reserve_batch(int model, int n, const int32_t *seqs, const int32_t *ctx_lens) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (n < 0 || n > PKV_MAX_BATCH_OPS || (n > 0 && (!seqs || !ctx_lens))) return PKV_E_ARG;
+    if (n == 0) return 0;
+    Pool &p = g_pools[m->pool];
+    memcpy(g_ops, seqs, sizeof(int32_t) * n);
+    memcpy(g_ops + n, ctx_lens, sizeof(int32_t) * n);
+    const int64_t r = book_call([&] { return pkv_launch_reserve(p.dev, m->dev, n, g_ops, g_res, g_stream); });
+    if (r >= 0) {   // the call succeeded as a whole: replay its effect on the shadow lengths
+        for (int i = 0; i < n; ++i) {
+            const int want = (int)(((int64_t)ctx_lens[i] + p.T - 1) / p.T);
+            if (want > m->row_len[seqs[i]]) m->row_len[seqs[i]] = want;
+        }
+        m->used_blocks += r;
+    }
+    return (int)r;
+}
+
+int seq_reserve(int model, int seq, int ctx_len) {
+    const int32_t s = seq, c = ctx_len;
+    return seq_reserve_batch(model, 1, &s, &c);
+}
+
+int seq_release(int model, int seq) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (seq < 0 || seq >= m->dev.max_seqs) return PKV_E_ARG;
+    if (m->row_len[seq] == 0) return 0;
+    Pool &p = g_pools[m->pool];
+    const int64_t r = book_call([&] { return pkv_launch_release(p.dev, m->dev, seq, g_res, g_stream); });
+    if (r >= 0) {
+        m->row_len[seq] = 0;
+        m->used_blocks -= r;
+    }
+    return (int)r;
+}
+
+const int32_t *model_block_table(int model, int *row_stride) {
+    Model *m = get_model(model);
+    if (!m) return nullptr;
+    if (row_stride) *row_stride = m->dev.max_blocks;
+    return m->dev.rows;
+}
+
+/* ---------------------------------------------------------------- KV data */
+
+int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const void *v, const float *k_scale,
+             const float *v_scale) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (seq < 0 || seq >= m->dev.max_seqs || tok_begin < 0 || n_tok < 0) return PKV_E_ARG;
+    if (n_tok == 0) return 0;
+    if (!k || !v) return PKV_E_ARG;
+    if (m->dtype == PKV_E4M3 && (!k_scale || !v_scale)) return PKV_E_ARG;
+    Pool &p = g_pools[m->pool];
+    if (((int64_t)tok_begin + n_tok + p.T - 1) / p.T > m->row_len[seq]) return PKV_E_RANGE;
+    AttnDesc d{};
+    d.pool_base = p.base;
+    d.table = m->dev.rows;
+    d.row_stride = m->dev.max_blocks;
+    d.frame_bytes = p.frame_bytes;
+    d.block_bytes = m->block_bytes;
+    d.slots_div = fastdiv_make((uint32_t)m->slots);
+    d.Hq = m->Hq; d.Hkv = m->Hkv; d.g = m->g; d.D = m->D; d.dtype = m->dtype;
+    HIP_TRY(pkv_launch_kv_write(d, seq, tok_begin, n_tok, k, v, k_scale, v_scale, p.T, g_stream));
+    return n_tok;
+}
+
+/* -------------------------------------------------------- decode attention */
+
+int model_set_batch(int model, int batch, int row_stride) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (batch < 0 || row_stride < 0) return PKV_E_ARG;
+    m->batch = batch;
+    m->row_stride = row_stride;
+    return PKV_OK;
+}
+
+int decode_attention_ex(int model, int batch, const void *q, const int32_t *block_table, int row_stride,
+                        const int32_t *ctx_lens, float *out) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (batch < 0) return PKV_E_ARG;
+    if (batch == 0) return PKV_OK;
+    if (!q || !ctx_lens || !out) return PKV_E_ARG;
+    if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return PKV_E_ARG;
+    if (block_table) {
+        if (row_stride <= 0) return PKV_E_ARG;
+    } else if (batch > m->dev.max_seqs) {
+        return PKV_E_RANGE;
+    }
+    AttnGroup grp;
+    grp.n = 1;
+    int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out);
+    if (rc) return rc;
+    HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
+    return PKV_OK;
+}
+
+int decode_attention(int model, const void *q, const int32_t *block_table, const int32_t *ctx_lens, float *out) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (m->batch <= 0) return PKV_E_ARG;   // model_set_batch first
+    return decode_attention_ex(model, m->batch, q, block_table, m->row_stride, ctx_lens, out);
+}
+
+int decode_attention_multi(int n_models, const int *models, const int *batches, const void *const *q,
+                           const int32_t *const *ctx_lens, float *const *out) {
+    if (n_models < 0 || n_models > PKV_MAX_GROUP) return PKV_E_ARG;
+    if (n_models == 0) return PKV_OK;
+    if (!models || !batches || !q || !ctx_lens || !out) return PKV_E_ARG;
+    AttnGroup grp;
+    grp.n = 0;
+    int items = 0, pool = -1;
+    for (int i = 0; i < n_models; ++i) {
+        Model *m = get_model(models[i]);
+        if (!m) return PKV_E_HANDLE;
+        for (int j = 0; j < i; ++j)
+            if (models[j] == models[i]) return PKV_E_ARG;   // one partials buffer per model
+        if (pool < 0) pool = m->pool;
+        if (m->pool != pool) return PKV_E_ARG;
+        if (batches[i] < 0 || batches[i] > m->dev.max_seqs) return PKV_E_RANGE;
+        if (batches[i] == 0) continue;
+        if (!q[i] || !ctx_lens[i] || !out[i]) return PKV_E_ARG;
+        if (((uintptr_t)q[i] & 15) || ((uintptr_t)out[i] & 15)) return PKV_E_ARG;
+        AttnDesc &d = grp.m[grp.n];
+        int rc = fill_desc(d, *m, batches[i], q[i], nullptr, 0, ctx_lens[i], out[i]);
+        if (rc) return rc;
+        d.item_begin = items;
+        items += d.n_items;
+        grp.n++;
+    }
+    if (grp.n == 0) return PKV_OK;
+    HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
+    return PKV_OK;
+}
+
+/* ------------------------------------------------------------ observation */
+
+long pool_export_state(int pool, void *host_buf, size_t cap) {
+    Pool *p = get_pool(pool);
+    if (!p) return PKV_E_HANDLE;
+    HIP_TRY(hipStreamSynchronize(g_stream));
+    const int64_t nf = p->n_frames;
+    std::vector<int32_t> img;
+    int64_t n_free = 0;
+    HIP_TRY(hipMemcpy(&n_free, p->dev.n_free, sizeof n_free, hipMemcpyDeviceToHost));
+    std::vector<uint32_t> stack(nf);
+    std::vector<int32_t> owner(nf);
+    HIP_TRY(hipMemcpy(stack.data(), p->dev.free_stack, sizeof(uint32_t) * nf, hipMemcpyDeviceToHost));
+    HIP_TRY(hipMemcpy(owner.data(), p->dev.owner, sizeof(int32_t) * nf, hipMemcpyDeviceToHost));
+    img.push_back(0x53564B50);
+    img.push_back(1);
+    img.push_back((int32_t)nf);
+    img.push_back(p->T);
+    img.push_back((int32_t)n_free);
+    for (int64_t i = 0; i < n_free; ++i) img.push_back((int32_t)stack[i]);
+    img.insert(img.end(), owner.begin(), owner.end());
+    int n_models = 0;
+    for (int id = 0; id < PKV_MAX_MODELS; ++id)
+        if (g_models[id].live && g_models[id].pool == pool) n_models++;
+    img.push_back(n_models);
+    for (int id = 0; id < PKV_MAX_MODELS; ++id) {
+        Model &m = g_models[id];
+        if (!m.live || m.pool != pool) continue;
+        int64_t cnt[2];
+        HIP_TRY(hipMemcpy(cnt, m.dev.counters, sizeof cnt, hipMemcpyDeviceToHost));
+        const int64_t owned = cnt[0];
+        std::vector<uint32_t> frames(owned), bits((size_t)owned * m.dev.wpf);
+        if (owned) {
+            HIP_TRY(hipMemcpy(frames.data(), m.dev.frames, sizeof(uint32_t) * owned, hipMemcpyDeviceToHost));
+            HIP_TRY(hipMemcpy(bits.data(), m.dev.bits, sizeof(uint32_t) * bits.size(), hipMemcpyDeviceToHost));
+        }
+        img.push_back(id); img.push_back(m.Hq); img.push_back(m.Hkv); img.push_back(m.D); img.push_back(m.dtype);
+        img.push_back(m.slots); img.push_back((int32_t)owned);
+        for (int64_t i = 0; i < owned; ++i) img.push_back((int32_t)frames[i]);
+        const int64_t nbits = owned * m.slots;
+        img.push_back((int32_t)nbits);
+        std::vector<uint32_t> packed((size_t)((nbits + 31) / 32), 0u);
+        for (int64_t i = 0; i < owned; ++i)          // per-frame words -> one contiguous bit string
+            for (int s = 0; s < m.slots; ++s)
+                if (bits[(size_t)i * m.dev.wpf + (s >> 5)] >> (s & 31) & 1u) {
+                    const int64_t j = i * m.slots + s;
+                    packed[(size_t)(j >> 5)] |= 1u << (j & 31);
+                }
+        for (uint32_t w : packed) img.push_back((int32_t)w);
+        img.push_back(m.dev.max_seqs);
+        std::vector<int32_t> len(m.dev.max_seqs);
+        HIP_TRY(hipMemcpy(len.data(), m.dev.row_len, sizeof(int32_t) * len.size(), hipMemcpyDeviceToHost));
+        int n_rows = 0;
+        for (int32_t l : len) n_rows += l > 0;
+        img.push_back(n_rows);
+        std::vector<int32_t> row(m.dev.max_blocks);
+        for (int s = 0; s < m.dev.max_seqs; ++s) {
+            if (len[s] == 0) continue;
+            HIP_TRY(hipMemcpy(row.data(), m.dev.rows + (size_t)s * m.dev.max_blocks, sizeof(int32_t) * len[s],
+                              hipMemcpyDeviceToHost));
+            img.push_back(s);
+            img.push_back(len[s]);
+            img.insert(img.end(), row.begin(), row.begin() + len[s]);
+        }
+    }
+    const size_t need = img.size() * sizeof(int32_t);
+    if (host_buf && cap >= need) memcpy(host_buf, img.data(), need);
+    return (long)need;
+}
+
+int pool_stats(int pool, pkv_stats *out) {
+    Pool *p = get_pool(pool);
+    if (!p) return PKV_E_HANDLE;
+    if (!out) return PKV_E_ARG;
+    memset(out, 0, sizeof *out);
+    HIP_TRY(hipStreamSynchronize(g_stream));
+    int64_t n_free = 0;
+    HIP_TRY(hipMemcpy(&n_free, p->dev.n_free, sizeof n_free, hipMemcpyDeviceToHost));
+    out->n_frames = p->n_frames;
+    out->n_free = n_free;
+    for (int id = 0; id < PKV_MAX_MODELS; ++id) {
+        Model &m = g_models[id];
+        if (!m.live || m.pool != pool) continue;
+        int64_t cnt[2];
+        HIP_TRY(hipMemcpy(cnt, m.dev.counters, sizeof cnt, hipMemcpyDeviceToHost));
+        out->owned[id] = cnt[0];
+        out->used_blocks[id] = cnt[0] * m.slots - cnt[1];
+    }
+    return PKV_OK;
+}
+
+}  // extern "C"

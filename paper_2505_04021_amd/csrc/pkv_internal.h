@@ -1,0 +1,108 @@
+// Internal declarations shared by the host API and the HIP kernels of libprismkv.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/prism_kv.h"
+
+#define PKV_MAX_POOLS 8
+#define PKV_MAX_MODELS 64
+#define PKV_FP8_HEADER 128   // bytes in front of an e4m3 block: fp32 sK[Hkv], fp32 sV[Hkv]
+#define PKV_MAX_BATCH_OPS 2048
+#define PKV_MAX_SEQS 4096
+#define PKV_BOOK_THREADS 1024
+
+// Unsigned division by an invariant divisor with one multiply-high and two shifts
+// (Granlund & Montgomery, "Division by invariant integers using multiplication").
+// Exact for every 32-bit numerator.
+struct FastDiv {
+    uint32_t d, mul, sh1, sh2;
+};
+
+static inline FastDiv fastdiv_make(uint32_t d) {
+    FastDiv f;
+    f.d = d;
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;                   // l = ceil(log2 d)
+    f.mul = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+    f.sh1 = l < 1 ? l : 1;
+    f.sh2 = l < 1 ? 0 : l - 1;
+    return f;
+}
+
+__host__ __device__ static inline uint32_t fastdiv_div(uint32_t n, const FastDiv &f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t t = __umulhi(n, f.mul);
+#else
+    uint32_t t = (uint32_t)(((uint64_t)n * f.mul) >> 32);
+#endif
+    return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
+// Result slot in pinned host memory, written by the bookkeeping kernels.
+struct BookResult {
+    int64_t value;     // count or negative PKV_E_* code
+    int64_t aux0, aux1;
+};
+
+// Device-resident pool state.
+struct PoolDev {
+    int32_t *owner;        // [n_frames] model id or -1
+    uint32_t *free_stack;  // [n_frames], [0] bottom .. [n_free-1] top
+    int32_t *pos;          // [n_frames] position of the frame in its owner's list
+    int64_t *n_free;       // [1]
+    int64_t n_frames;
+};
+
+// Device-resident per-model bookkeeping state.
+struct ModelDev {
+    uint32_t *frames;      // [n_frames] acquisition order
+    uint32_t *bits;        // [n_frames][wpf] slot bits of the frame at that position
+    uint8_t *mark;         // [n_frames] scratch for deflate
+    int32_t *rows;         // [max_seqs][max_blocks] block ids
+    int32_t *row_len;      // [max_seqs]
+    int64_t *counters;     // [0] owned frames, [1] free slots
+    int32_t model_id;
+    int32_t slots, wpf;    // slots per frame, 32-bit words per frame in `bits`
+    int32_t max_seqs, max_blocks, page_tokens;
+};
+
+// What one attention work-group needs to know about its model.
+struct AttnDesc {
+    const uint8_t *pool_base;
+    const uint16_t *q;          // bf16 [B][Hq][D]
+    const int32_t *table;       // [B][row_stride]
+    const int32_t *ctx_lens;    // [B]
+    float *out;                 // [B][Hq][D]
+    float *ws;                  // split-K partials of this model
+    uint32_t *err;              // device error flags
+    uint64_t frame_bytes, block_bytes;
+    FastDiv slots_div;
+    uint32_t max_block_id;      // n_frames * slots
+    int32_t batch, row_stride;
+    int32_t Hq, Hkv, g, D, dtype;
+    int32_t chunk_pages, max_chunks;
+    int32_t item_begin;         // first work item of this model in a grouped launch
+    int32_t n_items;            // batch * Hkv * max_chunks
+    float scale_log2;           // log2(e) / sqrt(D)
+};
+
+#define PKV_MAX_GROUP 16
+
+struct AttnGroup {
+    AttnDesc m[PKV_MAX_GROUP];
+    int32_t n;
+};
+
+// ---- launch wrappers implemented in the .hip files ----------------------------
+hipError_t pkv_launch_pool_init(const PoolDev &p, const uint32_t *perm_dev, hipStream_t s);
+hipError_t pkv_launch_inflate(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, hipStream_t s);
+hipError_t pkv_launch_deflate(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, hipStream_t s);
+hipError_t pkv_launch_reserve(const PoolDev &p, const ModelDev &m, int n, const int32_t *seqs_ctx /*pinned host: n seqs then n ctx*/,
+                              BookResult *res, hipStream_t s);
+hipError_t pkv_launch_release(const PoolDev &p, const ModelDev &m, int seq, BookResult *res, hipStream_t s);
+
+hipError_t pkv_launch_kv_write(const AttnDesc &d, int seq, int tok_begin, int n_tok, const void *k, const void *v,
+                               const float *ks, const float *vs, int page_tokens, hipStream_t s);
+// ev: NULL or three events recorded before the attention kernel, after it, and after the merge
+hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t *ev);
