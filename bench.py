@@ -31,9 +31,11 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5])
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--replicas", type=int, default=3)
-    ap.add_argument("--chunk-pages", type=int, default=0, help="force the split-K chunk size (0 = automatic)")
+    ap.add_argument("--items", type=int, default=0, help="work items (waves) per attention launch (0 = automatic)")
+    ap.add_argument("--min-share", type=int, default=0, help="smallest share of pages per wave (0 = automatic)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     ap.add_argument("--no-balloon", action="store_true")
+    ap.add_argument("--sweep-items", default="", help="comma list of work-item counts to time before the main run (stderr)")
     return ap.parse_args()
 
 
@@ -87,54 +89,29 @@ def balloon_latency(gpu, torch):
 
 
 def cpu_baseline(rep, seconds):
-    """The oracle, as it stands, on a bounded sample of the same workload: the same
-    bookkeeping calls, KV written only for the sampled sequences, decode attention of
-    those sequences on all host cores."""
+    """The oracle, as it stands, on the same workload: the same bookkeeping calls and
+    KV, decode attention of every model's batch on all host cores, repeated with the
+    queries of successive steps until about `seconds` of CPU time have been spent."""
     import numpy as np
     from oracle import Oracle
-    from workloads.scenarios import Runner, kv_bytes
+    from workloads.scenarios import Runner
     orc = Oracle()
-    cfg = rep.cfg
-    # calibrate on a tiny slice, then size the sample for ~`seconds`
-    probe = Runner(orc, cfg, fill=set(), write_kv=True).setup()
-    order = sorted(((int(probe.ctx[mi][s]), mi, s) for mi in range(len(cfg.models))
-                    for s in range(cfg.models[mi].batch)), key=lambda x: x[0])
-    probe.teardown()
-    shortest = order[len(order) // 8]
-    def run(sample):
-        fill = {(mi, int(s)) for _, mi, s in sample}
-        r = Runner(orc, cfg, fill=fill).setup()
-        total_bytes, t_total = 0, 0.0
-        for mi in sorted({mi for _, mi, _ in sample}):
-            seqs = np.array([s for _, m2, s in sample if m2 == mi], dtype=np.int64)
-            rows = orc.block_table_rows(r.models[mi], cfg.models[mi].batch)[seqs]
-            q = r.queries(0, mi)[seqs]
-            ctx = r.ctx[mi][seqs]
+    r = Runner(orc, rep.cfg).setup()
+    step_bytes = r.kv_bytes_step()
+    t_total, n = 0.0, 0
+    while t_total < seconds and n < 1000:
+        for mi in r.active_models():
+            q = r.queries(n, mi)
             t0 = time.perf_counter()
-            rc, _ = orc.decode_attention(r.models[mi], q, ctx, rows)
+            rc, _ = orc.decode_attention(r.models[mi], q, r.ctx[mi])
             t_total += time.perf_counter() - t0
             assert rc == 0
-            total_bytes += kv_bytes(cfg, cfg.models[mi], ctx)
-        r.teardown()
-        return total_bytes, t_total
-    b0, t0 = run([shortest])
-    rate = b0 / max(t0, 1e-6)
-    budget = rate * seconds
-    sample, acc = [], 0
-    for c, mi, s in order[::-1][len(order) // 4::3] + order:      # a spread of lengths first
-        spec = cfg.models[mi]
-        nb = kv_bytes(cfg, spec, np.array([c]))
-        if (c, mi, s) in sample or acc + nb > budget:
-            continue
-        sample.append((c, mi, s))
-        acc += nb
-    if not sample:
-        sample = [shortest]
-    b, t = run(sample)
-    return {"value": b / t / 1e9, "unit": "GB/s", "cores": orc.num_threads(), "kind": "oracle",
-            "sample": f"{len(sample)} of {len(order)} sequences of step 0 ({b / 1e6:.1f} MB of KV, "
-                      f"{t:.1f} s, fp64, {orc.num_threads()} OpenMP threads)",
-            "seconds": t}
+        n += 1
+    r.teardown()
+    return {"value": round(step_bytes * n / t_total / 1e9, 3), "unit": "GB/s", "cores": orc.num_threads(),
+            "kind": "oracle", "step_us": round(t_total / n * 1e6, 1),
+            "sample": f"{n} full decode steps of replica 0 ({step_bytes / 1e6:.1f} MB of KV each, "
+                      f"{t_total:.1f} s in total, fp64, {orc.num_threads()} OpenMP threads)"}
 
 
 def main():
@@ -147,7 +124,7 @@ def main():
     from paper_2505_04021_amd import PrismKV
 
     gpu = PrismKV("cuda:0")
-    gpu.set_chunk_pages(args.chunk_pages)
+    gpu.set_split(args.items, args.min_share)
     reps = build_replicas(gpu, args.config, args.size, args.replicas)
     inputs = [device_inputs(torch, rep, 0) for rep in reps]
     kv_per_rep = [rep.kv_bytes_step() for rep in reps]
@@ -156,6 +133,23 @@ def main():
         mids, qs, ctxs, outs = inputs[i % len(reps)]
         rc = gpu.decode_attention_multi_dev(mids, qs, ctxs, outs)
         assert rc == 0, (rc, gpu.last_error())
+
+    for c in [int(x) for x in args.sweep_items.split(",") if x]:
+        gpu.set_split(c, args.min_share)
+        for i in range(10):
+            step(i)
+        torch.cuda.synchronize()
+        gpu.timing_enable(True)
+        t0 = time.perf_counter()
+        for i in range(60):
+            step(i)
+        torch.cuda.synchronize()
+        w = (time.perf_counter() - t0) / 60
+        n_rec, a_ms = gpu.timing_read()
+        gpu.timing_enable(False)
+        print(f"[sweep] items {c:6d}: step {w * 1e6:7.1f} us  attention kernel {a_ms / n_rec * 1e3:7.1f} us",
+              file=sys.stderr, flush=True)
+    gpu.set_split(args.items, args.min_share)
 
     for i in range(args.warmup):
         step(i)
@@ -170,7 +164,7 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    n_rec, attn_ms, merge_ms = gpu.timing_read()
+    n_rec, attn_ms = gpu.timing_read()
     gpu.timing_enable(False)
     assert gpu.device_errors() == 0
     dev_ms = ev0.elapsed_time(ev1)
@@ -197,15 +191,17 @@ def main():
         "data": "synthetic",
         "config": {"workload": reps[0].cfg.name, "cfg": args.config, "size": args.size,
                    "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
-                   "chunk_pages": args.chunk_pages or "auto"},
+                   "work_items": args.items or "auto"},
         "step_us": round(ms_per_step * 1e3, 2),
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "device_ms_per_step": round(dev_ms / args.steps, 5),
         "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None, "avg_launch_us": round(attn_avg_ms * 1e3, 2),
-                     "merge_avg_us": round(merge_ms / max(n_rec, 1) * 1e3, 2), "launches": n_rec},
+                     "traffic": None, "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": n_rec},
     }
+    result["read_ceiling_gbps"] = {"stream": round(gpu.stream_read_probe(4 << 30, 0, 10), 1),
+                                   "scattered_8KiB": round(gpu.stream_read_probe(4 << 30, 8 << 10, 10), 1),
+                                   "scattered_64KiB": round(gpu.stream_read_probe(4 << 30, 64 << 10, 10), 1)}
     if not args.no_balloon:
         result["balloon_resize"] = balloon_latency(gpu, torch)
     if args.cpu_seconds > 0:

@@ -177,14 +177,22 @@ long pool_export_state(int pool, void *host_buf, size_t cap);
 int pool_stats(int pool, pkv_stats *out);
 
 /* Per-kernel timing for measurements: while enabled, every decode_attention* call
- * brackets its attention kernel and its merge kernel with HIP events on the
- * library's stream (at most 8192 calls are recorded).  pkv_timing_read waits for
- * the stream, returns the number of recorded calls and the summed kernel times in
- * milliseconds, and clears the record. */
+ * brackets its attention kernel with HIP events on the library's stream (at most
+ * 8192 calls are recorded).  pkv_timing_read waits for the stream, returns the
+ * number of recorded calls and the summed kernel time in milliseconds, and clears
+ * the record. */
 int pkv_timing_enable(int on);
-long pkv_timing_read(double *attention_ms, double *merge_ms);
-/* Tuning knob for measurements: pages per split-K chunk (0 = automatic). */
-int pkv_set_chunk_pages(int pages);
+long pkv_timing_read(double *attention_ms);
+/* Measured ceilings for comparison: reads a freshly allocated buffer of `bytes` bytes
+ * (a power of two) `iters` times with a kernel that does no arithmetic and reports
+ * the read bandwidth in GB/s.  granule_bytes = 0: plain streaming read; otherwise a
+ * power of two >= 8192: whole granules of that size are read in a scrambled order,
+ * the access pattern of paged KV tiles.  Allocates and frees its buffer; synchronises. */
+int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double *gbps);
+/* Measurement / test knobs of the attention work split: `items` = work items (waves)
+ * per launch, `min_share` = smallest number of pages a wave may be given; 0 selects
+ * the automatic value of either. */
+int pkv_set_split(int items, int min_share);
 /* Host-side check of the multiply-shift division the kernels use to split a block
  * id into (frame, slot): returns n / d computed that way. */
 uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d);

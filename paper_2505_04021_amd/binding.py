@@ -15,7 +15,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 
 def lib_path():
-    return os.path.join(_HERE, "libprismkv.so")
+    # PRISMKV_LIB selects another build of the same library (kernel tuning experiments)
+    return os.environ.get("PRISMKV_LIB") or os.path.join(_HERE, "libprismkv.so")
 
 
 def _load():
@@ -31,10 +32,11 @@ def _load():
         "pkv_set_stream": (i, [vp]),
         "pkv_last_error": (C.c_char_p, []),
         "pkv_device_errors": (i, []),
-        "pkv_set_chunk_pages": (i, [i]),
+        "pkv_set_split": (i, [i, i]),
         "pkv_debug_fastdiv": (u32, [u32, u32]),
+        "pkv_stream_read_probe": (i, [sz, sz, i, C.POINTER(C.c_double)]),
         "pkv_timing_enable": (i, [i]),
-        "pkv_timing_read": (l, [C.POINTER(C.c_double), C.POINTER(C.c_double)]),
+        "pkv_timing_read": (l, [C.POINTER(C.c_double)]),
         "pool_create": (i, [sz, i]),
         "pool_create_ex": (i, [sz, i, sz, vp]),
         "pool_destroy": (i, [i]),
@@ -62,8 +64,8 @@ def _load():
     return lib
 
 
-EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_chunk_pages", "pkv_debug_fastdiv",
-           "pkv_timing_enable", "pkv_timing_read",
+EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_debug_fastdiv",
+           "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
            "seq_release", "model_block_table", "kv_write", "model_set_batch", "decode_attention",
@@ -97,17 +99,24 @@ class PrismKV:
     def device_errors(self):
         return self.lib.pkv_device_errors()
 
-    def set_chunk_pages(self, pages):
-        return self.lib.pkv_set_chunk_pages(pages)
+    def set_split(self, items=0, min_share=0):
+        return self.lib.pkv_set_split(items, min_share)
+
+    def stream_read_probe(self, nbytes=4 << 30, granule_bytes=0, iters=10):
+        g = C.c_double(0)
+        rc = self.lib.pkv_stream_read_probe(nbytes, granule_bytes, iters, C.byref(g))
+        if rc != 0:
+            raise RuntimeError(f"pkv_stream_read_probe failed: {rc} {self.last_error()}")
+        return g.value
 
     def timing_enable(self, on=True):
         return self.lib.pkv_timing_enable(1 if on else 0)
 
     def timing_read(self):
-        """(recorded calls, attention kernel ms, merge kernel ms), summed since the last read."""
-        a, m = C.c_double(0), C.c_double(0)
-        n = self.lib.pkv_timing_read(C.byref(a), C.byref(m))
-        return n, a.value, m.value
+        """(recorded calls, attention kernel ms summed since the last read)."""
+        a = C.c_double(0)
+        n = self.lib.pkv_timing_read(C.byref(a))
+        return n, a.value
 
     def _dev(self, a, dtype=None):
         """torch device tensor for a numpy array / tensor; dtype is a torch dtype to view as."""

@@ -19,11 +19,13 @@ def newest_source_mtime():
     return t
 
 
-def build(force: bool = True, verbose: bool = False) -> str:
-    if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= newest_source_mtime():
-        return LIB
+def build(force: bool = True, verbose: bool = False, defines=(), out: str = LIB) -> str:
+    """defines / out: build a variant with other compile-time kernel knobs beside the default library."""
+    if not force and os.path.exists(out) and os.path.getmtime(out) >= newest_source_mtime():
+        return out
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + [f for f in FLAGS if f] + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd = [hipcc] + [f for f in FLAGS if f] + [f"-D{d}" for d in defines] + ["-o", out] + \
+          [os.path.join(CSRC, s) for s in SOURCES]
     if verbose:
         print(" ".join(cmd))
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -33,7 +35,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err:
         print(err)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

@@ -38,7 +38,37 @@ struct Model {
     ModelDev dev{};
     float *ws = nullptr;                    // split-K partials
     size_t ws_floats = 0;
+    uint32_t *cnt = nullptr;                // arrival counters, zero between launches
+    size_t cnt_cap = 0;
 };
+
+// Uncached device memory for split-K partials and arrival counters.  Blocks are
+// recycled between models but never returned to the driver while the process lives.
+struct UcBlock {
+    void *p;
+    size_t bytes;
+    bool used;
+};
+std::vector<UcBlock> g_uc;
+
+void *uc_alloc(size_t bytes) {
+    int best = -1;
+    for (size_t i = 0; i < g_uc.size(); ++i)
+        if (!g_uc[i].used && g_uc[i].bytes >= bytes && (best < 0 || g_uc[i].bytes < g_uc[best].bytes)) best = (int)i;
+    if (best < 0) {
+        void *p = nullptr;
+        if (hipExtMallocWithFlags(&p, bytes, hipDeviceMallocUncached) != hipSuccess) return nullptr;
+        g_uc.push_back(UcBlock{p, bytes, false});
+        best = (int)g_uc.size() - 1;
+    }
+    g_uc[best].used = true;
+    return g_uc[best].p;
+}
+
+void uc_release(void *p) {
+    for (auto &b : g_uc)
+        if (b.p == p) b.used = false;
+}
 
 Pool g_pools[PKV_MAX_POOLS];
 Model g_models[PKV_MAX_MODELS];
@@ -47,9 +77,9 @@ hipStream_t g_stream = nullptr;
 BookResult *g_res = nullptr;       // pinned host
 int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
 uint32_t *g_err = nullptr;         // device error flags
-int g_chunk_pages = 0;
+int g_items = 0, g_min_share = 0;   // measurement knobs (0 = automatic)
 bool g_timing = false;
-std::vector<hipEvent_t> g_events;   // triples: before attention, after attention, after merge
+std::vector<hipEvent_t> g_events;   // pairs: before and after the attention kernel
 size_t g_events_used = 0;
 constexpr size_t kMaxTimedLaunches = 8192;
 thread_local char g_errbuf[256] = "";
@@ -90,26 +120,29 @@ int64_t book_call(F launch) {
 
 void free_model_dev(Model &m) {
     (void)hipFree(m.dev.frames); (void)hipFree(m.dev.bits); (void)hipFree(m.dev.mark); (void)hipFree(m.dev.rows);
-    (void)hipFree(m.dev.row_len); (void)hipFree(m.dev.counters); (void)hipFree(m.ws);
+    (void)hipFree(m.dev.row_len); (void)hipFree(m.dev.counters);
+    uc_release(m.ws);
+    uc_release(m.cnt);
     m.dev = ModelDev{};
     m.ws = nullptr;
-    m.ws_floats = 0;
+    m.cnt = nullptr;
+    m.ws_floats = m.cnt_cap = 0;
 }
 
-int pick_chunk_pages(const Model &m, bool own_table) {
-    if (g_chunk_pages > 0) return g_chunk_pages;
-    // Aim for several waves per SIMD over the whole chip while keeping the split-K
-    // partials a few percent of the KV bytes; the host knows how many blocks the
-    // model has reserved when the library's own table is used.
-    if (!own_table) return 16;
-    const int64_t page_items = m.used_blocks * m.Hkv;
-    int c = 32;
-    while (c > 4 && page_items / c < 3 * 4096) c >>= 1;
-    return c;
+// Work items (waves) per attention launch.  The chip holds 256 CUs x 4 SIMDs x 2
+// resident waves of this kernel; twice that many items lets the dispatcher even out
+// CUs that run ahead.  Each model of a grouped launch gets items in proportion to the
+// KV bytes it is expected to read.
+constexpr int kDefaultItems = 4096;
+constexpr int kDefaultMinShare = 4;
+
+double est_bytes(const Model &m, bool own, int batch, int row_stride) {
+    const double blocks = own ? (double)m.used_blocks : (double)batch * row_stride;
+    return blocks * (double)m.block_bytes;
 }
 
 int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *table, int row_stride,
-              const int32_t *ctx_lens, float *out) {
+              const int32_t *ctx_lens, float *out, double share_of_launch) {
     Pool &p = g_pools[m.pool];
     const bool own = table == nullptr;
     d.pool_base = p.base;
@@ -117,6 +150,7 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.table = own ? m.dev.rows : table;
     d.row_stride = own ? m.dev.max_blocks : row_stride;
     d.ctx_lens = ctx_lens;
+    d.row_len = own ? m.dev.row_len : nullptr;
     d.out = out;
     d.err = g_err;
     d.frame_bytes = p.frame_bytes;
@@ -125,33 +159,47 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.max_block_id = (uint32_t)(p.n_frames * m.slots);
     d.batch = batch;
     d.Hq = m.Hq; d.Hkv = m.Hkv; d.g = m.g; d.D = m.D; d.dtype = m.dtype;
-    d.chunk_pages = pick_chunk_pages(m, own);
-    d.max_chunks = (d.row_stride + d.chunk_pages - 1) / d.chunk_pages;
-    d.n_items = batch * m.Hkv * d.max_chunks;
     d.item_begin = 0;
     d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m.D));
-    const size_t need = d.max_chunks > 1 ? (size_t)d.n_items * m.g * (m.D + 2) : 0;
+    d.min_share = g_min_share > 0 ? g_min_share : kDefaultMinShare;
+    // no more items than there can be shares of min_share pages (an empty row counts as one page)
+    const double units = ((own ? (double)m.used_blocks : (double)batch * d.row_stride) + batch) * m.Hkv;
+    double items = (g_items > 0 ? g_items : kDefaultItems) * share_of_launch;
+    if (items > units / d.min_share) items = units / d.min_share;
+    d.n_items = items < 1.0 ? 1 : (int)(items + 0.5);
+    const size_t need = (size_t)2 * d.n_items * m.g * (m.D + 2);
     if (need > m.ws_floats) {
         HIP_TRY(hipStreamSynchronize(g_stream));
-        (void)hipFree(m.ws);
-        m.ws = nullptr;
+        uc_release(m.ws);
         m.ws_floats = 0;
-        HIP_TRY(hipMalloc((void **)&m.ws, need * sizeof(float)));
-        m.ws_floats = need;
+        m.ws = (float *)uc_alloc(need * sizeof(float) * 2);
+        if (!m.ws) return PKV_E_NOMEM;
+        m.ws_floats = need * 2;
     }
     d.ws = m.ws;
+    const size_t n_cnt = (size_t)batch * m.Hkv;
+    if (n_cnt > m.cnt_cap) {
+        HIP_TRY(hipStreamSynchronize(g_stream));
+        uc_release(m.cnt);
+        m.cnt_cap = 0;
+        m.cnt = (uint32_t *)uc_alloc(n_cnt * 2 * sizeof(uint32_t));
+        if (!m.cnt) return PKV_E_NOMEM;
+        HIP_TRY(hipMemset(m.cnt, 0, n_cnt * 2 * sizeof(uint32_t)));
+        m.cnt_cap = n_cnt * 2;
+    }
+    d.cnt = m.cnt;
     return PKV_OK;
 }
 
 hipEvent_t *next_events() {
-    if (!g_timing || g_events_used + 3 > 3 * kMaxTimedLaunches) return nullptr;
-    while (g_events.size() < g_events_used + 3) {
+    if (!g_timing || g_events_used + 2 > 2 * kMaxTimedLaunches) return nullptr;
+    while (g_events.size() < g_events_used + 2) {
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return nullptr;
         g_events.push_back(e);
     }
     hipEvent_t *p = &g_events[g_events_used];
-    g_events_used += 3;
+    g_events_used += 2;
     return p;
 }
 
@@ -165,19 +213,16 @@ int pkv_timing_enable(int on) {
     return PKV_OK;
 }
 
-long pkv_timing_read(double *attention_ms, double *merge_ms) {
+long pkv_timing_read(double *attention_ms) {
     HIP_TRY(hipStreamSynchronize(g_stream));
-    double a = 0.0, m = 0.0;
-    for (size_t i = 0; i + 3 <= g_events_used; i += 3) {
+    double a = 0.0;
+    for (size_t i = 0; i + 2 <= g_events_used; i += 2) {
         float t = 0.f;
         HIP_TRY(hipEventElapsedTime(&t, g_events[i], g_events[i + 1]));
         a += t;
-        HIP_TRY(hipEventElapsedTime(&t, g_events[i + 1], g_events[i + 2]));
-        m += t;
     }
     if (attention_ms) *attention_ms = a;
-    if (merge_ms) *merge_ms = m;
-    const long n = (long)(g_events_used / 3);
+    const long n = (long)(g_events_used / 2);
     g_events_used = 0;
     return n;
 }
@@ -199,9 +244,37 @@ int pkv_device_errors(void) {
     return (int)v;
 }
 
-int pkv_set_chunk_pages(int pages) {
-    if (pages < 0 || pages > 4096) return PKV_E_ARG;
-    g_chunk_pages = pages;
+int pkv_set_split(int items, int min_share) {
+    if (items < 0 || items > (1 << 20) || min_share < 0 || min_share > 4096) return PKV_E_ARG;
+    g_items = items;
+    g_min_share = min_share;
+    return PKV_OK;
+}
+
+int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double *gbps) {
+    if (bytes < (1u << 20) || iters <= 0 || !gbps) return PKV_E_ARG;
+    if ((bytes & (bytes - 1)) != 0) return PKV_E_ARG;
+    if (granule_bytes != 0 && (granule_bytes < 8192 || (granule_bytes & (granule_bytes - 1)) != 0 || granule_bytes > bytes))
+        return PKV_E_ARG;
+    int rc = lib_init();
+    if (rc) return rc;
+    void *buf = nullptr;
+    if (hipMalloc(&buf, bytes) != hipSuccess) return PKV_E_NOMEM;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    HIP_TRY(hipMemsetAsync(buf, 1, bytes, g_stream));
+    HIP_TRY(pkv_launch_stream_read(buf, bytes, granule_bytes, g_err, g_stream));       // warm-up
+    HIP_TRY(hipEventRecord(e0, g_stream));
+    for (int i = 0; i < iters; ++i) HIP_TRY(pkv_launch_stream_read(buf, bytes, granule_bytes, g_err, g_stream));
+    HIP_TRY(hipEventRecord(e1, g_stream));
+    HIP_TRY(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    *gbps = (double)bytes * iters / (ms * 1e-3) / 1e9;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipFree(buf);
     return PKV_OK;
 }
 
@@ -477,7 +550,7 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     }
     AttnGroup grp;
     grp.n = 1;
-    int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out);
+    int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
     if (rc) return rc;
     HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
     return PKV_OK;
@@ -498,6 +571,7 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
     AttnGroup grp;
     grp.n = 0;
     int items = 0, pool = -1;
+    double total_bytes = 0.0;
     for (int i = 0; i < n_models; ++i) {
         Model *m = get_model(models[i]);
         if (!m) return PKV_E_HANDLE;
@@ -509,8 +583,14 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
         if (batches[i] == 0) continue;
         if (!q[i] || !ctx_lens[i] || !out[i]) return PKV_E_ARG;
         if (((uintptr_t)q[i] & 15) || ((uintptr_t)out[i] & 15)) return PKV_E_ARG;
+        total_bytes += est_bytes(*m, true, batches[i], 0) + 1.0;
+    }
+    for (int i = 0; i < n_models; ++i) {
+        if (batches[i] == 0) continue;
+        Model *m = get_model(models[i]);
         AttnDesc &d = grp.m[grp.n];
-        int rc = fill_desc(d, *m, batches[i], q[i], nullptr, 0, ctx_lens[i], out[i]);
+        const double frac = (est_bytes(*m, true, batches[i], 0) + 1.0) / total_bytes;
+        int rc = fill_desc(d, *m, batches[i], q[i], nullptr, 0, ctx_lens[i], out[i], frac);
         if (rc) return rc;
         d.item_begin = items;
         items += d.n_items;

@@ -6,8 +6,12 @@
 // R4/D4).  The path is bound by HBM reads of K and V, each byte exactly once.
 //
 // Mapping to the hardware
-//   * one wavefront (64 lanes) per work item = (sequence, kv head, chunk of pages):
-//     split-K over pages, merged afterwards with the online-softmax rule;
+//   * one wavefront (64 lanes) per work item; the pages of all (sequence, kv head)
+//     pairs are laid end to end and cut into equal shares, so every wave reads the
+//     same number of bytes whatever the mix of context lengths; where a share boundary
+//     cuts a sequence, the wave that finishes it last merges the pieces with the
+//     online-softmax rule inside the same kernel (partials and arrival counters sit in
+//     uncached memory: no cache flush, no second launch);
 //   * K and V tiles are stored inside a block in the lane order of the MFMA operands,
 //     so each 16-byte global load is fully coalesced (64 lanes x 16 B = 1 KiB
 //     contiguous) and lands directly in operand registers — no LDS round trip, no
@@ -42,6 +46,12 @@ __device__ __forceinline__ u32x4 mk4(uint32_t a, uint32_t b, uint32_t c, uint32_
 __device__ __forceinline__ u32x2 mk2(uint32_t a, uint32_t b) { return u32x2{a, b}; }
 
 constexpr int T = 16;   // tokens per block the kernels are built for
+
+// Wave-uniform reads of data this kernel never writes (block tables, context
+// lengths, the work plan, e4m3 scales): going through the constant address space
+// makes them scalar loads, which are counted apart from the vector loads of K and V
+// and so never force the KV pipeline to drain.
+#define PKV_CONST(T_, p_) ((const T_ __attribute__((address_space(4))) *)(p_))
 
 __device__ __forceinline__ uint32_t pack_bf16_trunc(float lo, float hi) {
     // two fp32 -> packed bf16 by taking the upper halves (exact for values that
@@ -79,12 +89,21 @@ struct PageRegs {
     float sk, sv;
 };
 
+// Issue the loads of one page (K tile, V tile) of one kv head.  Buffer loads with a
+// per-page resource descriptor: a page beyond the chunk (live == false) gets a
+// descriptor of zero records, so its loads return zeros without touching memory.
+// That keeps every load of the software pipeline unconditional, which lets the
+// compiler count outstanding loads exactly (s_waitcnt vmcnt(N) with N > 0) instead of
+// draining the queue at each control-flow join.
 template <int D, int DT>
 __device__ __forceinline__ void load_page(PageRegs<D, DT> &r, const AttnDesc &d, const int32_t *row, int page,
-                                          int kvh, int lane) {
-    uint32_t id = (uint32_t)row[page];
+                                          bool live, int kvh, int lane, uint32_t &bad) {
+    using TL = Tile<D, DT>;
+    const int idx = page < d.row_stride ? page : d.row_stride - 1;
+    // wave-uniform by construction; say so, so that it lives in scalar registers
+    uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[idx]);
     if (id >= d.max_block_id) {          // never dereference an id outside the pool
-        if (lane == 0) atomicOr(d.err, 1u);
+        bad |= live ? 1u : 0u;           // reported once, after the last load (no store inside the loop)
         id = 0;
     }
     const uint32_t f = fastdiv_div(id, d.slots_div);
@@ -92,16 +111,20 @@ __device__ __forceinline__ void load_page(PageRegs<D, DT> &r, const AttnDesc &d,
     const uint8_t *blk = d.pool_base + (uint64_t)f * d.frame_bytes + (uint64_t)s * d.block_bytes;
     if (DT == PKV_E4M3) {
         const float *hdr = reinterpret_cast<const float *>(blk);
-        r.sk = hdr[kvh];
-        r.sv = hdr[d.Hkv + kvh];
+        r.sk = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[kvh])));
+        r.sv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[d.Hkv + kvh])));
         blk += PKV_FP8_HEADER;
     }
-    const u32x4 *kp = reinterpret_cast<const u32x4 *>(blk + (size_t)kvh * 2 * Tile<D, DT>::TILE_BYTES) + lane;
-    const u32x4 *vp = kp + Tile<D, DT>::TILE_BYTES / 16;
+    const uint8_t *tiles = blk + (size_t)kvh * 2 * TL::TILE_BYTES;
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(tiles), 0, live ? 2 * TL::TILE_BYTES : 0, 0x00020000);
+    const int voff = lane * 16;
 #pragma unroll
-    for (int j = 0; j < Tile<D, DT>::NL; ++j) r.k[j] = __builtin_nontemporal_load(kp + j * 64);
+    for (int j = 0; j < TL::NL; ++j)
+        r.k[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff + j * 1024, 0, 2 /* non-temporal */);
 #pragma unroll
-    for (int j = 0; j < Tile<D, DT>::NL; ++j) r.v[j] = __builtin_nontemporal_load(vp + j * 64);
+    for (int j = 0; j < TL::NL; ++j)
+        r.v[j] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff + j * 1024, TL::TILE_BYTES, 2);
 }
 
 template <int D, int DT>
@@ -110,10 +133,29 @@ struct State {
     float m, l;                   // running max (log2 domain) and this lane's share of the sum
 };
 
-template <int D, int DT, bool TAIL>
+// A operand of the PV product for output tile jt: V[4G..4G+3][16jt + (lane & 15)]
+template <int D, int DT>
+__device__ __forceinline__ s16x4 v_operand(const PageRegs<D, DT> &r, int jt, uint32_t m01, uint32_t m23) {
+    u32x2 a;
+    if (DT == PKV_BF16) {
+        const u32x4 vv = r.v[jt >> 1];
+        a = (jt & 1) ? mk2(vv.z, vv.w) : mk2(vv.x, vv.y);
+    } else {
+        const u32x4 vv = r.v[jt >> 2];
+        const uint32_t w = (jt & 3) == 0 ? vv.x : (jt & 3) == 1 ? vv.y : (jt & 3) == 2 ? vv.z : vv.w;
+        a = fp8x4_to_bf16x4(w);
+    }
+    a.x &= m01;
+    a.y &= m23;
+    return *reinterpret_cast<s16x4 *>(&a);
+}
+
+template <int D, int DT>
 __device__ __forceinline__ void process_page(State<D, DT> &st, const PageRegs<D, DT> &r, const bf16x8 *qf,
-                                             float scale_log2, int valid /*tokens valid in this page*/, int G) {
+                                             float scale_log2, int valid /*tokens valid in this page, 1..16*/,
+                                             int G) {
     using TL = Tile<D, DT>;
+    const bool tail = valid < T;          // wave-uniform
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
     if (DT == PKV_BF16) {
 #pragma unroll
@@ -137,7 +179,7 @@ __device__ __forceinline__ void process_page(State<D, DT> &st, const PageRegs<D,
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         s[i] *= sc;
-        if (TAIL && 4 * G + i >= valid) s[i] = -INFINITY;
+        if (tail && 4 * G + i >= valid) s[i] = -INFINITY;   // select, so a NaN logit of a dead token cannot leak
     }
     float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
     mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -165,71 +207,68 @@ __device__ __forceinline__ void process_page(State<D, DT> &st, const PageRegs<D,
     u32x2 ph = mk2(h01, h23);
     u32x2 pl = mk2(pack_bf16_rne(l0, l1), pack_bf16_rne(l2, l3));
     const s16x4 phv = *reinterpret_cast<s16x4 *>(&ph), plv = *reinterpret_cast<s16x4 *>(&pl);
-    // tokens past the context length may hold anything (even NaN): blank them
-    uint32_t m01 = 0xffffffffu, m23 = 0xffffffffu;
-    if (TAIL) {
-        const int left = valid - 4 * G;
-        m01 = left >= 2 ? 0xffffffffu : (left == 1 ? 0x0000ffffu : 0u);
-        m23 = left >= 4 ? 0xffffffffu : (left == 3 ? 0x0000ffffu : 0u);
-    }
+    if (!tail) {
 #pragma unroll
-    for (int jt = 0; jt < TL::NV; ++jt) {
-        u32x2 a;
-        if (DT == PKV_BF16) {
-            const u32x4 vv = r.v[jt >> 1];
-            a = (jt & 1) ? mk2(vv.z, vv.w) : mk2(vv.x, vv.y);
-        } else {
-            const u32x4 vv = r.v[jt >> 2];
-            const uint32_t w = (jt & 3) == 0 ? vv.x : (jt & 3) == 1 ? vv.y : (jt & 3) == 2 ? vv.z : vv.w;
-            a = fp8x4_to_bf16x4(w);
+        for (int jt = 0; jt < TL::NV; ++jt) {
+            const s16x4 av = v_operand<D, DT>(r, jt, 0xffffffffu, 0xffffffffu);
+            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, phv, st.acc[jt], 0, 0, 0);
+            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, plv, st.acc[jt], 0, 0, 0);
         }
-        if (TAIL) {
-            a.x &= m01;
-            a.y &= m23;
+    } else {
+        // tokens past the context length may hold anything (even NaN): blank their V
+        const int left = valid - 4 * G;
+        const uint32_t m01 = left >= 2 ? 0xffffffffu : (left == 1 ? 0x0000ffffu : 0u);
+        const uint32_t m23 = left >= 4 ? 0xffffffffu : (left == 3 ? 0x0000ffffu : 0u);
+#pragma unroll
+        for (int jt = 0; jt < TL::NV; ++jt) {
+            const s16x4 av = v_operand<D, DT>(r, jt, m01, m23);
+            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, phv, st.acc[jt], 0, 0, 0);
+            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, plv, st.acc[jt], 0, 0, 0);
         }
-        const s16x4 av = *reinterpret_cast<s16x4 *>(&a);
-        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, phv, st.acc[jt], 0, 0, 0);
-        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, plv, st.acc[jt], 0, 0, 0);
     }
 }
 
 // Floats per split-K partial: g rows of D accumulators, then g maxima, then g sums.
 __host__ __device__ inline int partial_floats(int g, int D) { return g * (D + 2); }
 
+#ifndef PKV_RING
+#define PKV_RING 3
+#endif
+#ifndef PKV_WAVES
+#define PKV_WAVES 2
+#endif
+constexpr int RING = PKV_RING;   // pages resident per wave: one in use, the rest in flight
+constexpr int MAX_PIECES = 64;   // pieces of one (sequence, kv head) the merge stages in LDS
+
+// Pages the work split plans for a sequence: its context rounded up to pages, never
+// beyond what its table row holds, and at least one so that an empty sequence still
+// has an owner who writes its zero row.
+__device__ __forceinline__ int ctx_clamped(const AttnDesc &d, int seq) {
+    int L = PKV_CONST(int32_t, d.ctx_lens)[seq];
+    const int cap = (d.row_len ? PKV_CONST(int32_t, d.row_len)[seq] : d.row_stride) * T;
+    return L < 0 ? 0 : (L > cap ? cap : L);
+}
+
+// One piece: pages [pb, pe) of (seq, kvh), 0 <= pb < pe <= n_pages.  Streams the pages
+// through the register ring and leaves the un-normalised accumulators, the running max
+// and the full row sum in `st` / `l_out`.
 template <int D, int DT>
-__device__ __forceinline__ void attn_item(const AttnDesc &d, int item) {
+__device__ __forceinline__ void run_piece(State<D, DT> &st, float &l_out, const AttnDesc &d, int seq, int kvh,
+                                          int pb, int pe, int n_pages, int last_valid, int lane, uint32_t &bad) {
     using TL = Tile<D, DT>;
-    const int lane = threadIdx.x;
     const int G = lane >> 4, n = lane & 15;
-    const int kvh = item % d.Hkv;
-    const int rest = item / d.Hkv;
-    const int chunk = rest % d.max_chunks;
-    const int seq = rest / d.max_chunks;
-    int L = d.ctx_lens[seq];
-    const int cap = d.row_stride * T;
-    L = L < 0 ? 0 : (L > cap ? cap : L);
-    const int n_pages = (L + T - 1) / T;
-    const int C = d.chunk_pages;
-    const int p0 = chunk * C;
     const int g = d.g;
-    const int head = kvh * g + n;
-    float *out_row = d.out + ((size_t)seq * d.Hq + head) * D;
-    if (p0 >= n_pages) {
-        if (chunk == 0 && n < g) {           // empty context: the row is defined as zero
-#pragma unroll
-            for (int jt = 0; jt < TL::NV; ++jt)
-                *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-        return;
-    }
-    const int p1 = p0 + C < n_pages ? p0 + C : n_pages;
-    const int n_chunks = (n_pages + C - 1) / C;
     const int32_t *row = d.table + (size_t)seq * d.row_stride;
+
+    // the first pages go out before anything else is touched
+    PageRegs<D, DT> ring[RING];
+#pragma unroll
+    for (int r = 0; r < RING - 1; ++r) load_page<D, DT>(ring[r], d, row, pb + r, pb + r < pe, kvh, lane, bad);
 
     // q as the B operand: lane (G, n) holds q[head n][8(4j+G) .. +7] for each k-step j
     bf16x8 qf[TL::NK];
     {
-        const uint16_t *qrow = d.q + ((size_t)seq * d.Hq + head) * D;
+        const uint16_t *qrow = d.q + ((size_t)seq * d.Hq + kvh * g + n) * D;
 #pragma unroll
         for (int j = 0; j < TL::NK; ++j) {
             u32x4 v = mk4(0, 0, 0, 0);
@@ -237,56 +276,195 @@ __device__ __forceinline__ void attn_item(const AttnDesc &d, int item) {
             qf[j] = *reinterpret_cast<bf16x8 *>(&v);
         }
     }
-
-    State<D, DT> st;
 #pragma unroll
     for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
     st.m = -INFINITY;
     st.l = 0.f;
 
-    const int last_valid = L - (n_pages - 1) * T;            // tokens in the last page, 1..16
-    const bool tail_here = (p1 == n_pages) && last_valid < T;
-    const int p_full_end = tail_here ? p1 - 1 : p1;          // pages [p0, p_full_end) are full
-
-    PageRegs<D, DT> ra, rb;
-    load_page<D, DT>(ra, d, row, p0, kvh, lane);
-    int p = p0;
-    // two pages per trip so the registers of the page in flight and the page in use
-    // swap roles without copies
-    for (; p + 1 < p_full_end; p += 2) {
-        load_page<D, DT>(rb, d, row, p + 1, kvh, lane);
-        process_page<D, DT, false>(st, ra, qf, d.scale_log2, T, G);
-        if (p + 2 < p1) load_page<D, DT>(ra, d, row, p + 2, kvh, lane);
-        process_page<D, DT, false>(st, rb, qf, d.scale_log2, T, G);
+    // ring of RING register buffers, unrolled so every buffer index is static; the
+    // loads are unconditional (dead pages cost no traffic), only the math is guarded
+    for (int p = pb; p < pe; p += RING) {
+#pragma unroll
+        for (int r = 0; r < RING; ++r) {
+            const int pc = p + r, pn = pc + RING - 1;
+            load_page<D, DT>(ring[(r + RING - 1) % RING], d, row, pn, pn < pe, kvh, lane, bad);
+            if (pc < pe) process_page<D, DT>(st, ring[r], qf, d.scale_log2, pc == n_pages - 1 ? last_valid : T, G);
+        }
     }
-    if (p < p_full_end) {                 // one full page left (ra holds it)
-        if (p + 1 < p1) load_page<D, DT>(rb, d, row, p + 1, kvh, lane);
-        process_page<D, DT, false>(st, ra, qf, d.scale_log2, T, G);
-        ++p;
-        if (p < p1) process_page<D, DT, true>(st, rb, qf, d.scale_log2, last_valid, G);
-    } else if (p < p1) {                  // only the ragged page left (ra holds it)
-        process_page<D, DT, true>(st, ra, qf, d.scale_log2, last_valid, G);
-    }
-
     float l = st.l;
     l += __shfl_xor(l, 16);
     l += __shfl_xor(l, 32);
-    if (n >= g) return;
-    if (n_chunks == 1) {
-        const float inv = 1.0f / l;
-#pragma unroll
-        for (int jt = 0; jt < TL::NV; ++jt)
-            *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = st.acc[jt] * inv;
-    } else {
-        float *w = d.ws + (((size_t)seq * d.Hkv + kvh) * d.max_chunks + chunk) * partial_floats(g, D);
-#pragma unroll
-        for (int jt = 0; jt < TL::NV; ++jt)
-            *reinterpret_cast<f32x4 *>(w + n * D + 16 * jt + 4 * G) = st.acc[jt];
-        if (G == 0) {
-            w[g * D + n] = st.m;
-            w[g * D + g + n] = l;
+    l_out = l;
+}
+
+// Work split ("stream-K" over pages): the (sequence, kv head) segments of a model are
+// laid end to end, a segment being the pages of one sequence for one kv head; the
+// resulting line of W page units is cut into equal shares, one per wave.  A wave's
+// share may end inside a segment and start inside another: such pieces leave a partial
+// (accumulators, max, sum) in uncached memory, and the wave that completes a segment
+// last merges its pieces with the online-softmax rule.  Segments that lie inside one
+// share are finished directly.  Every wave derives the split from ctx_lens itself, so
+// the split follows the real context lengths and needs no host-side plan.
+template <int D, int DT>
+__device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_m, float *s_l) {
+    using TL = Tile<D, DT>;
+    const int lane = threadIdx.x;
+    const int G = lane >> 4, n = lane & 15;
+    const int g = d.g, Hkv = d.Hkv, B = d.batch;
+
+    // --- planned pages per sequence, prefix sums across the wave
+    const int K = (B + 63) >> 6;                    // sequences per lane
+    int my_sum = 0, my_max = 0;
+    for (int k = 0; k < K; ++k) {
+        const int sq = lane * K + k;
+        if (sq < B) {
+            const int np = (ctx_clamped(d, sq) + T - 1) / T;
+            const int pl = np > 0 ? np : 1;
+            my_sum += pl;
+            my_max = pl > my_max ? pl : my_max;
         }
     }
+    int incl = my_sum;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const int v = __shfl_xor(my_max, o);
+        my_max = v > my_max ? v : my_max;
+    }
+    const int total = __builtin_amdgcn_readlane(incl, 63);
+    const uint32_t W = (uint32_t)total * (uint32_t)Hkv;
+    // equal shares, but never so small that a segment falls into more pieces than the
+    // merge can stage
+    uint32_t share = (W + (uint32_t)d.n_items - 1) / (uint32_t)d.n_items;
+    const uint32_t floor_share = ((uint32_t)my_max + (MAX_PIECES - 4) - 1) / (MAX_PIECES - 4);
+    share = share < floor_share ? floor_share : share;
+    share = share < (uint32_t)d.min_share ? (uint32_t)d.min_share : share;
+    const uint32_t gbeg = (uint32_t)item * share;
+    if (gbeg >= W) return;
+    const uint32_t gend = gbeg + share < W ? gbeg + share : W;
+
+    // --- the sequence whose segments contain gbeg
+    int seq, P;                                     // P = planned pages of all earlier sequences
+    {
+        const uint32_t lo = (uint32_t)(incl - my_sum) * Hkv, hi = (uint32_t)incl * Hkv;
+        const unsigned long long own = __ballot(lo <= gbeg && gbeg < hi);
+        const int owner = __ffsll(own) - 1;
+        int fs = 0, fp = incl - my_sum;
+        for (int k = 0; k < K; ++k) {               // only the owner's walk matters
+            const int sq = lane * K + k;
+            if (sq < B) {
+                const int np = (ctx_clamped(d, sq) + T - 1) / T;
+                const int pl = np > 0 ? np : 1;
+                if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl; else { fs = sq; break; }
+            }
+        }
+        seq = __shfl(fs, owner);
+        P = __shfl(fp, owner);
+    }
+    uint32_t bad = 0;
+    const int pf = partial_floats(g, D);
+    float *ws_a = d.ws + (size_t)(2 * item) * pf;       // piece of a segment that began in an earlier share
+    float *ws_b = ws_a + pf;                            // piece of a segment that begins in this share
+
+    while (seq < B) {
+        const int L = __builtin_amdgcn_readfirstlane(ctx_clamped(d, seq));
+        const int n_pages = (L + T - 1) / T;
+        const int pl = n_pages > 0 ? n_pages : 1;
+        const int last_valid = L - (n_pages - 1) * T;
+        const uint32_t seq_g0 = (uint32_t)P * Hkv;
+        if (seq_g0 >= gend) break;
+        int kvh = gbeg > seq_g0 ? (int)((gbeg - seq_g0) / (uint32_t)pl) : 0;
+        for (; kvh < Hkv; ++kvh) {
+            const uint32_t g0 = seq_g0 + (uint32_t)kvh * pl;           // where this segment starts on the line
+            if (g0 >= gend) break;
+            const int pb = gbeg > g0 ? (int)(gbeg - g0) : 0;
+            const int pe = gend - g0 < (uint32_t)pl ? (int)(gend - g0) : pl;
+            float *out_row = d.out + ((size_t)seq * d.Hq + kvh * g + n) * D;
+            if (n_pages == 0) {                  // empty context: the row is defined as zero
+                if (pb == 0 && n < g) {
+#pragma unroll
+                    for (int jt = 0; jt < TL::NV; ++jt)
+                        *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+                continue;
+            }
+            State<D, DT> st;
+            float l;
+            run_piece<D, DT>(st, l, d, seq, kvh, pb, pe, n_pages, last_valid, lane, bad);
+            const uint32_t k0 = g0 / share, k1 = (g0 + (uint32_t)n_pages - 1) / share;
+            if (k0 == k1) {                      // the whole segment was ours
+                if (n < g) {
+                    const float inv = 1.0f / l;
+#pragma unroll
+                    for (int jt = 0; jt < TL::NV; ++jt)
+                        *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = st.acc[jt] * inv;
+                }
+                continue;
+            }
+            // park the partial, then the wave that arrives last merges all of them
+            float *w = pb == 0 ? ws_b : ws_a;
+            if (n < g) {
+#pragma unroll
+                for (int jt = 0; jt < TL::NV; ++jt)
+                    *reinterpret_cast<f32x4 *>(w + n * D + 16 * jt + 4 * G) = st.acc[jt];
+                if (G == 0) {
+                    w[g * D + n] = st.m;
+                    w[g * D + g + n] = l;
+                }
+            }
+#if defined(PKV_EXP_NO_MERGE)
+            continue;   // timing experiment only: results of split segments are wrong
+#endif
+            // The partials and the arrival counters live in uncached device memory, so every
+            // access goes to memory itself and is visible to all XCDs without flushing an L2.
+            // Order is all that is left to enforce: the partial must have landed before the
+            // counter moves, and the merge loads are issued only after the counter came back.
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            uint32_t *cnt = d.cnt + (size_t)seq * Hkv + kvh;
+            uint32_t arrived = 0;
+            if (lane == 0) arrived = atomicAdd(cnt, 1u);
+            arrived = __shfl(arrived, 0);
+            asm volatile("" ::: "memory");
+            if (arrived != k1 - k0) continue;
+            if (lane == 0) *cnt = 0u;                          // ready for the next launch
+            // online-softmax merge: M = max m_c, out = sum_c 2^(m_c-M) a_c / sum_c 2^(m_c-M) l_c.
+            // Piece c of the segment sits in share k0 + c: slot b of that share for c = 0,
+            // slot a otherwise.
+            const int n_pc = (int)(k1 - k0) + 1;
+            const float *base = d.ws + (size_t)(2 * k0) * pf;
+            for (int i = lane; i < n_pc * g; i += 64) {
+                const int c = i / g, hn = i - c * g;
+                const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf + g * D;
+                s_m[i] = wc[hn];
+                s_l[i] = wc[g + hn];
+            }
+            __builtin_amdgcn_wave_barrier();     // one wave per work-group: program order is enough
+            constexpr int D4 = D / 4;
+            for (int e = lane; e < g * D4; e += 64) {
+                const int hn = e / D4, x = e - hn * D4;
+                float M = -INFINITY;
+                for (int c = 0; c < n_pc; ++c) M = fmaxf(M, s_m[c * g + hn]);
+                f32x4 num = {0.f, 0.f, 0.f, 0.f};
+                float den = 0.f;
+#pragma unroll 8
+                for (int c = 0; c < n_pc; ++c) {
+                    const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf;
+                    const float f = __builtin_amdgcn_exp2f(s_m[c * g + hn] - M);
+                    den += f * s_l[c * g + hn];
+                    num += f * *reinterpret_cast<const f32x4 *>(wc + hn * D + 4 * x);
+                }
+                *reinterpret_cast<f32x4 *>(d.out + ((size_t)seq * d.Hq + kvh * g + hn) * D + 4 * x) = num * (1.0f / den);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        P += pl;
+        ++seq;
+    }
+    if (bad && lane == 0) atomicOr(d.err, 1u);
 }
 
 __device__ __forceinline__ int find_model(const AttnGroup &grp, int item) {
@@ -296,58 +474,51 @@ __device__ __forceinline__ int find_model(const AttnGroup &grp, int item) {
     return mi;
 }
 
-__global__ __launch_bounds__(64) void k_attention(const AttnGroup grp) {
+__global__ __launch_bounds__(64, PKV_WAVES) void k_attention(const AttnGroup grp) {
+    __shared__ float s_m[MAX_PIECES * 16], s_l[MAX_PIECES * 16];
     const int gi = blockIdx.x;
     const int mi = find_model(grp, gi);
     const AttnDesc &d = grp.m[mi];
     const int item = gi - d.item_begin;
     if (d.dtype == PKV_BF16) {
-        if (d.D == 128) attn_item<128, PKV_BF16>(d, item);
-        else attn_item<64, PKV_BF16>(d, item);
+        if (d.D == 128) attn_wave<128, PKV_BF16>(d, item, s_m, s_l);
+        else attn_wave<64, PKV_BF16>(d, item, s_m, s_l);
     } else {
-        if (d.D == 128) attn_item<128, PKV_E4M3>(d, item);
-        else attn_item<64, PKV_E4M3>(d, item);
+        if (d.D == 128) attn_wave<128, PKV_E4M3>(d, item, s_m, s_l);
+        else attn_wave<64, PKV_E4M3>(d, item, s_m, s_l);
     }
 }
 
-// Split-K merge (online-softmax rule): with chunk maxima m_c, sums l_c and
-// accumulators a_c,  M = max m_c,  out = sum_c 2^(m_c-M) a_c / sum_c 2^(m_c-M) l_c.
-// One work-group per (sequence, query head), one lane per output element.
-struct MergeGroup {
-    int32_t row_begin[PKV_MAX_GROUP];   // first (seq, head) row of each model
-    int32_t n;
-};
-
-__global__ void k_merge(const AttnGroup grp, const MergeGroup mg) {
-    const int r = blockIdx.x;
-    int mi = 0;
-    for (int i = 1; i < mg.n; ++i)
-        if (r >= mg.row_begin[i]) mi = i;
-    const AttnDesc &d = grp.m[mi];
-    const int rr = r - mg.row_begin[mi];
-    const int seq = rr / d.Hq, head = rr % d.Hq;
-    int L = d.ctx_lens[seq];
-    const int cap = d.row_stride * T;
-    L = L < 0 ? 0 : (L > cap ? cap : L);
-    const int n_pages = (L + T - 1) / T;
-    const int n_chunks = (n_pages + d.chunk_pages - 1) / d.chunk_pages;
-    if (n_chunks <= 1) return;                      // written directly by the attention kernel
-    const int g = d.g, D = d.D;
-    const int kvh = head / g, n = head % g;
-    const int pf = g * (D + 2);
-    const float *w = d.ws + ((size_t)seq * d.Hkv + kvh) * d.max_chunks * pf;
-    float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, w[(size_t)c * pf + g * D + n]);
-    const int t = threadIdx.x;
-    if (t >= D) return;
-    float num = 0.f, den = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        const float *wc = w + (size_t)c * pf;
-        const float f = __builtin_amdgcn_exp2f(wc[g * D + n] - M);
-        num += f * wc[n * D + t];
-        den += f * wc[g * D + g + n];
+// Read ceilings for comparison.  granule == 0: plain streaming read of the buffer,
+// 16 bytes per lane.  granule > 0 (a power-of-two number of KiB): each wave reads
+// whole granules of that size picked in a scrambled order, which is the access pattern
+// of paged KV (contiguous inside a tile, scattered between tiles) without any math.
+__global__ __launch_bounds__(256) void k_stream_read(const u32x4 *src, size_t n16, uint32_t granule16, uint32_t *sink) {
+    u32x4 acc = {0, 0, 0, 0};
+    if (granule16 == 0) {
+        const size_t stride = (size_t)gridDim.x * blockDim.x;
+        size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+        for (; i + 3 * stride < n16; i += 4 * stride) {
+            const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
+            const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride),
+                        e = __builtin_nontemporal_load(src + i + 3 * stride);
+            acc ^= a ^ b ^ c ^ e;
+        }
+        for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+    } else {
+        const size_t n_gran = n16 / granule16;               // a power of two (checked by the host)
+        const size_t waves = (size_t)gridDim.x * (blockDim.x / 64);
+        const int lane = threadIdx.x & 63;
+        for (size_t w = blockIdx.x * (size_t)(blockDim.x / 64) + (threadIdx.x >> 6); w < n_gran; w += waves) {
+            const size_t gidx = (w * 0x9E3779B1ull + 12345ull) & (n_gran - 1);   // odd multiplier: a permutation
+            const u32x4 *g = src + gidx * granule16 + lane;
+            for (uint32_t k = 0; k < granule16; k += 8 * 64) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc ^= __builtin_nontemporal_load(g + k + u * 64);
+            }
+        }
     }
-    d.out[((size_t)seq * d.Hq + head) * D + t] = num / den;
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = 1;   // keeps the loads alive
 }
 
 // kv_write: logical [n_tok][Hkv][D] -> the in-block operand layouts described above.
@@ -415,17 +586,8 @@ hipError_t pkv_launch_kv_write(const AttnDesc &d, int seq, int tok_begin, int n_
 }
 
 hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t *ev) {
-    int items = 0, rows = 0, maxD = 0;
-    bool need_merge = false;
-    MergeGroup mg;
-    mg.n = grp.n;
-    for (int i = 0; i < grp.n; ++i) {
-        items += grp.m[i].n_items;
-        mg.row_begin[i] = rows;
-        rows += grp.m[i].batch * grp.m[i].Hq;
-        if (grp.m[i].D > maxD) maxD = grp.m[i].D;
-        if (grp.m[i].max_chunks > 1) need_merge = true;
-    }
+    int items = 0;
+    for (int i = 0; i < grp.n; ++i) items += grp.m[i].n_items;
     if (items == 0) return hipSuccess;
     hipError_t e;
     if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
@@ -433,11 +595,11 @@ hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t 
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
-    if (need_merge && rows > 0) {
-        hipLaunchKernelGGL(k_merge, dim3(rows), dim3(maxD), 0, s, grp, mg);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-    }
-    if (ev && (e = hipEventRecord(ev[2], s)) != hipSuccess) return e;
     return hipSuccess;
+}
+
+hipError_t pkv_launch_stream_read(const void *src, size_t bytes, size_t granule_bytes, uint32_t *sink, hipStream_t s) {
+    hipLaunchKernelGGL(k_stream_read, dim3(256 * 16), dim3(256), 0, s, (const u32x4 *)src, bytes / 16,
+                       (uint32_t)(granule_bytes / 16), sink);
+    return hipGetLastError();
 }

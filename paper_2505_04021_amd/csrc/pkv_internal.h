@@ -73,17 +73,19 @@ struct AttnDesc {
     const uint16_t *q;          // bf16 [B][Hq][D]
     const int32_t *table;       // [B][row_stride]
     const int32_t *ctx_lens;    // [B]
+    const int32_t *row_len;     // library table: [max_seqs] blocks reserved per row; NULL for a caller's table
     float *out;                 // [B][Hq][D]
-    float *ws;                  // split-K partials of this model
+    float *ws;                  // split-K partials: two per work item (uncached memory)
+    uint32_t *cnt;              // [B][Hkv] arrival counters of the split-K merge, zero between launches
     uint32_t *err;              // device error flags
     uint64_t frame_bytes, block_bytes;
     FastDiv slots_div;
     uint32_t max_block_id;      // n_frames * slots
     int32_t batch, row_stride;
     int32_t Hq, Hkv, g, D, dtype;
-    int32_t chunk_pages, max_chunks;
     int32_t item_begin;         // first work item of this model in a grouped launch
-    int32_t n_items;            // batch * Hkv * max_chunks
+    int32_t n_items;            // work items (waves) of this model
+    int32_t min_share;          // smallest share of pages a wave may get
     float scale_log2;           // log2(e) / sqrt(D)
 };
 
@@ -104,5 +106,6 @@ hipError_t pkv_launch_release(const PoolDev &p, const ModelDev &m, int seq, Book
 
 hipError_t pkv_launch_kv_write(const AttnDesc &d, int seq, int tok_begin, int n_tok, const void *k, const void *v,
                                const float *ks, const float *vs, int page_tokens, hipStream_t s);
-// ev: NULL or three events recorded before the attention kernel, after it, and after the merge
+// ev: NULL or two events recorded before and after the attention kernel
 hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t *ev);
+hipError_t pkv_launch_stream_read(const void *src, size_t bytes, size_t granule_bytes, uint32_t *sink, hipStream_t s);

@@ -110,10 +110,10 @@ def test_edge_lengths_and_shapes(gpu, oracle, hq, hkv, d, dtype):
     """Empty, single-token, page-boundary and multi-chunk lengths; g from 1 to 16;
     the pool starts filled with NaN so any read outside the valid tokens shows."""
     p = Pair(gpu, oracle, hq, hkv, d, dtype, EDGE_CTX, poison=True)
-    for chunk in (0, 1, 3, 4, 64):       # automatic, and forced split-K shapes
-        assert gpu.set_chunk_pages(chunk) == 0
+    for items, share in ((0, 0), (100000, 1), (37, 3), (8, 5), (1, 1)):   # automatic, and forced split shapes
+        assert gpu.set_split(items, share) == 0
         err = p.check()
-    gpu.set_chunk_pages(0)
+    gpu.set_split(0, 0)
     assert_same_state(gpu, oracle, p.pools[0], p.pools[1])
     assert np.array_equal(p.outputs()[0][0], np.zeros((hq, d), np.float32))   # ctx 0 -> zero row
     assert gpu.device_errors() == 0
@@ -154,10 +154,10 @@ def test_peaky_softmax(gpu, oracle):
     """1 % of key rows scaled by 8: sharp peaks stress the running-max rescale and the
     precision of the probabilities."""
     p = Pair(gpu, oracle, 64, 8, 128, BF16, [2048 + 5, 999], pool_bytes=128 << 20, max_blocks=160, peak=0.01)
-    for chunk in (0, 2, 16):
-        gpu.set_chunk_pages(chunk)
+    for items, share in ((0, 0), (5000, 2), (300, 16)):
+        gpu.set_split(items, share)
         err = p.check()
-    gpu.set_chunk_pages(0)
+    gpu.set_split(0, 0)
     p.close()
 
 
