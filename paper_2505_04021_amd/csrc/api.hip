@@ -77,6 +77,7 @@ hipStream_t g_stream = nullptr;
 BookResult *g_res = nullptr;       // pinned host
 int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
 uint32_t *g_err = nullptr;         // device error flags
+uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
 int g_items = 0, g_min_share = 0;   // measurement knobs (0 = automatic)
 bool g_timing = false;
 std::vector<hipEvent_t> g_events;   // pairs: before and after the attention kernel
@@ -153,6 +154,7 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.row_len = own ? m.dev.row_len : nullptr;
     d.out = out;
     d.err = g_err;
+    d.trace = g_trace;
     d.frame_bytes = p.frame_bytes;
     d.block_bytes = m.block_bytes;
     d.slots_div = fastdiv_make((uint32_t)m.slots);
@@ -277,6 +279,14 @@ int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double 
     (void)hipFree(buf);
     return PKV_OK;
 }
+
+#if defined(PKV_TRACE)
+// instrumented builds only: per work-group time stamps of the last attention launch
+int pkv_trace_buffer(void *dev_buf) {
+    g_trace = (uint64_t *)dev_buf;
+    return PKV_OK;
+}
+#endif
 
 uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d) {
     if (d == 0) return 0;

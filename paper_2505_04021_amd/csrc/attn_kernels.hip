@@ -249,52 +249,140 @@ __device__ __forceinline__ int ctx_clamped(const AttnDesc &d, int seq) {
     return L < 0 ? 0 : (L > cap ? cap : L);
 }
 
-// One piece: pages [pb, pe) of (seq, kvh), 0 <= pb < pe <= n_pages.  Streams the pages
-// through the register ring and leaves the un-normalised accumulators, the running max
-// and the full row sum in `st` / `l_out`.
-template <int D, int DT>
-__device__ __forceinline__ void run_piece(State<D, DT> &st, float &l_out, const AttnDesc &d, int seq, int kvh,
-                                          int pb, int pe, int n_pages, int last_valid, int lane, uint32_t &bad) {
-    using TL = Tile<D, DT>;
+// A piece: the pages [pb, pe) of one (sequence, kv head) segment that fall into this
+// wave's share.  All fields are wave-uniform.
+struct Piece {
+    int valid;                  // 0 past the end of the share
+    int seq, kvh;
+    int P;                      // planned pages of all earlier sequences
+    int L, n_pages, pl;         // context length, its pages, planned pages (>= 1)
+    int pb, pe;                 // page range of the piece inside the segment
+    uint32_t g0;                // where the segment starts on the line of page units
+};
+
+__device__ __forceinline__ void piece_set_seq(Piece &pc, const AttnDesc &d, int seq, int P) {
+    pc.seq = seq;
+    pc.P = P;
+    pc.L = seq < d.batch ? __builtin_amdgcn_readfirstlane(ctx_clamped(d, seq < d.batch ? seq : 0)) : 0;
+    pc.n_pages = (pc.L + T - 1) / T;
+    pc.pl = pc.n_pages > 0 ? pc.n_pages : 1;
+}
+
+// clip segment (seq, kvh) against the share [gbeg, gend)
+__device__ __forceinline__ void piece_clip(Piece &pc, const AttnDesc &d, uint32_t gbeg, uint32_t gend) {
+    pc.g0 = (uint32_t)pc.P * d.Hkv + (uint32_t)pc.kvh * pc.pl;
+    pc.valid = (pc.seq < d.batch && pc.g0 < gend) ? 1 : 0;
+    pc.pb = gbeg > pc.g0 ? (int)(gbeg - pc.g0) : 0;
+    pc.pe = gend - pc.g0 < (uint32_t)pc.pl ? (int)(gend - pc.g0) : pc.pl;
+}
+
+__device__ __forceinline__ Piece piece_next(const Piece &c, const AttnDesc &d, uint32_t gbeg, uint32_t gend) {
+    Piece nx = c;
+    if (c.kvh + 1 < d.Hkv) {
+        nx.kvh = c.kvh + 1;
+    } else {
+        nx.kvh = 0;
+        piece_set_seq(nx, d, c.seq + 1, c.P + c.pl);
+    }
+    piece_clip(nx, d, gbeg, gend);
+    return nx;
+}
+
+// q as the B operand: lane (G, n) holds q[head n][8(4j+G) .. +7] for each k-step j
+template <int D>
+__device__ __forceinline__ void load_q(bf16x8 *qf, const AttnDesc &d, int seq, int kvh, int lane) {
     const int G = lane >> 4, n = lane & 15;
-    const int g = d.g;
-    const int32_t *row = d.table + (size_t)seq * d.row_stride;
-
-    // the first pages go out before anything else is touched
-    PageRegs<D, DT> ring[RING];
+    const uint16_t *qrow = d.q + ((size_t)seq * d.Hq + kvh * d.g + n) * D;
 #pragma unroll
-    for (int r = 0; r < RING - 1; ++r) load_page<D, DT>(ring[r], d, row, pb + r, pb + r < pe, kvh, lane, bad);
+    for (int j = 0; j < D / 32; ++j) {
+        u32x4 v = mk4(0, 0, 0, 0);
+        if (n < d.g) v = *reinterpret_cast<const u32x4 *>(qrow + 8 * (4 * j + G));
+        qf[j] = *reinterpret_cast<bf16x8 *>(&v);
+    }
+}
 
-    // q as the B operand: lane (G, n) holds q[head n][8(4j+G) .. +7] for each k-step j
-    bf16x8 qf[TL::NK];
-    {
-        const uint16_t *qrow = d.q + ((size_t)seq * d.Hq + kvh * g + n) * D;
+// What is left to do for a piece whose segment is shared with other waves: once the
+// arrival count is back, the wave that came last merges.
+struct Pending {
+    int valid, seq, kvh;
+    uint32_t k0, k1, arrived;
+};
+
+// online-softmax merge of the pieces of one segment: M = max m_c,
+// out = sum_c 2^(m_c-M) a_c / sum_c 2^(m_c-M) l_c.  Piece c of the segment sits in
+// share k0 + c: slot b of that share for c = 0, slot a otherwise.
+// The partials come from uncached memory, so the cost is memory round trips: the
+// maxima and sums of all pieces are fetched in one trip and staged in LDS, then each
+// lane owns EPL groups of four consecutive output elements and fetches the
+// accumulators of 32 / EPL pieces per trip.
+template <int D, int EPL>
+__device__ __forceinline__ void merge_rows(const AttnDesc &d, const Pending &pd, int lane, const float *s_m,
+                                           const float *s_l, const float *base, int n_pc) {
+    constexpr int D4 = D / 4;
+    constexpr int PB = 32 / EPL;                      // pieces per trip
+    const int g = d.g, pf = partial_floats(g, D);
+    const int E = g * D4;
+    int hn[EPL], x[EPL];
+    float M[EPL], den[EPL];
+    f32x4 num[EPL];
 #pragma unroll
-        for (int j = 0; j < TL::NK; ++j) {
-            u32x4 v = mk4(0, 0, 0, 0);
-            if (n < g) v = *reinterpret_cast<const u32x4 *>(qrow + 8 * (4 * j + G));
-            qf[j] = *reinterpret_cast<bf16x8 *>(&v);
+    for (int k = 0; k < EPL; ++k) {
+        const int e = lane + 64 * k;
+        const int ee = e < E ? e : E - 1;             // idle lanes shadow a valid element
+        hn[k] = ee / D4;
+        x[k] = ee - hn[k] * D4;
+        float mm = -INFINITY;
+        for (int c = 0; c < n_pc; ++c) mm = fmaxf(mm, s_m[c * g + hn[k]]);
+        M[k] = mm;
+        den[k] = 0.f;
+        num[k] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    for (int c0 = 0; c0 < n_pc; c0 += PB) {
+        f32x4 v[PB][EPL];
+#pragma unroll
+        for (int u = 0; u < PB; ++u) {
+            const int c = c0 + u < n_pc ? c0 + u : n_pc - 1;
+            const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf;
+#pragma unroll
+            for (int k = 0; k < EPL; ++k) v[u][k] = *reinterpret_cast<const f32x4 *>(wc + hn[k] * D + 4 * x[k]);
+        }
+#pragma unroll
+        for (int u = 0; u < PB; ++u) {
+            if (c0 + u < n_pc) {
+#pragma unroll
+                for (int k = 0; k < EPL; ++k) {
+                    const float f = __builtin_amdgcn_exp2f(s_m[(c0 + u) * g + hn[k]] - M[k]);
+                    den[k] += f * s_l[(c0 + u) * g + hn[k]];
+                    num[k] += f * v[u][k];
+                }
+            }
         }
     }
 #pragma unroll
-    for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    st.m = -INFINITY;
-    st.l = 0.f;
+    for (int k = 0; k < EPL; ++k)
+        if (lane + 64 * k < E)
+            *reinterpret_cast<f32x4 *>(d.out + ((size_t)pd.seq * d.Hq + pd.kvh * g + hn[k]) * D + 4 * x[k]) =
+                num[k] * (1.0f / den[k]);
+}
 
-    // ring of RING register buffers, unrolled so every buffer index is static; the
-    // loads are unconditional (dead pages cost no traffic), only the math is guarded
-    for (int p = pb; p < pe; p += RING) {
-#pragma unroll
-        for (int r = 0; r < RING; ++r) {
-            const int pc = p + r, pn = pc + RING - 1;
-            load_page<D, DT>(ring[(r + RING - 1) % RING], d, row, pn, pn < pe, kvh, lane, bad);
-            if (pc < pe) process_page<D, DT>(st, ring[r], qf, d.scale_log2, pc == n_pages - 1 ? last_valid : T, G);
-        }
+template <int D>
+__device__ __forceinline__ void merge_segment(const AttnDesc &d, const Pending &pd, int lane, float *s_m, float *s_l) {
+    const int g = d.g, pf = partial_floats(g, D);
+    const int n_pc = (int)(pd.k1 - pd.k0) + 1;
+    const float *base = d.ws + (size_t)(2 * pd.k0) * pf;
+    for (int i = lane; i < n_pc * g; i += 64) {
+        const int c = i / g, hn = i - c * g;
+        const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf + g * D;
+        s_m[i] = wc[hn];
+        s_l[i] = wc[g + hn];
     }
-    float l = st.l;
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
-    l_out = l;
+    __builtin_amdgcn_wave_barrier();     // one wave per work-group: program order is enough
+    const int groups = (g * (D / 4) + 63) / 64;       // element groups per lane
+    if (groups <= 1) merge_rows<D, 1>(d, pd, lane, s_m, s_l, base, n_pc);
+    else if (groups <= 2) merge_rows<D, 2>(d, pd, lane, s_m, s_l, base, n_pc);
+    else if (groups <= 4) merge_rows<D, 4>(d, pd, lane, s_m, s_l, base, n_pc);
+    else merge_rows<D, 8>(d, pd, lane, s_m, s_l, base, n_pc);
+    __builtin_amdgcn_wave_barrier();
 }
 
 // Work split ("stream-K" over pages): the (sequence, kv head) segments of a model are
@@ -305,10 +393,22 @@ __device__ __forceinline__ void run_piece(State<D, DT> &st, float &l_out, const 
 // last merges its pieces with the online-softmax rule.  Segments that lie inside one
 // share are finished directly.  Every wave derives the split from ctx_lens itself, so
 // the split follows the real context lengths and needs no host-side plan.
+//
+// Inside a share the pages of consecutive pieces form ONE stream through the register
+// ring: work proceeds in turns of RING pages, every piece is padded to whole turns
+// with dead pages (no traffic, no math), and during the last turn of a piece the loads
+// already fetch the first pages of the next piece.
+#if defined(PKV_TRACE)
+#define PKV_STAMP(slot) do { if (threadIdx.x == 0 && d.trace) d.trace[(size_t)(blockIdx.x) * 8 + (slot)] = wall_clock64(); } while (0)
+#else
+#define PKV_STAMP(slot) do { } while (0)
+#endif
+
 template <int D, int DT>
 __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_m, float *s_l) {
     using TL = Tile<D, DT>;
     const int lane = threadIdx.x;
+    PKV_STAMP(0);
     const int G = lane >> 4, n = lane & 15;
     const int g = d.g, Hkv = d.Hkv, B = d.batch;
 
@@ -343,12 +443,14 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
     const uint32_t floor_share = ((uint32_t)my_max + (MAX_PIECES - 4) - 1) / (MAX_PIECES - 4);
     share = share < floor_share ? floor_share : share;
     share = share < (uint32_t)d.min_share ? (uint32_t)d.min_share : share;
+    share = (uint32_t)__builtin_amdgcn_readfirstlane((int)share);
     const uint32_t gbeg = (uint32_t)item * share;
     if (gbeg >= W) return;
     const uint32_t gend = gbeg + share < W ? gbeg + share : W;
+    PKV_STAMP(1);
 
-    // --- the sequence whose segments contain gbeg
-    int seq, P;                                     // P = planned pages of all earlier sequences
+    // --- the first piece: the segment that contains gbeg
+    Piece cur;
     {
         const uint32_t lo = (uint32_t)(incl - my_sum) * Hkv, hi = (uint32_t)incl * Hkv;
         const unsigned long long own = __ballot(lo <= gbeg && gbeg < hi);
@@ -362,40 +464,89 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
                 if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl; else { fs = sq; break; }
             }
         }
-        seq = __shfl(fs, owner);
-        P = __shfl(fp, owner);
+        const int seq0 = __builtin_amdgcn_readfirstlane(__shfl(fs, owner));
+        const int P0 = __builtin_amdgcn_readfirstlane(__shfl(fp, owner));
+        piece_set_seq(cur, d, seq0, P0);
+        cur.kvh = (int)((gbeg - (uint32_t)P0 * Hkv) / (uint32_t)cur.pl);
+        piece_clip(cur, d, gbeg, gend);
     }
+
     uint32_t bad = 0;
     const int pf = partial_floats(g, D);
     float *ws_a = d.ws + (size_t)(2 * item) * pf;       // piece of a segment that began in an earlier share
     float *ws_b = ws_a + pf;                            // piece of a segment that begins in this share
+    Pending pend_a, pend_b;
+    pend_a.valid = pend_b.valid = 0;
+    pend_a.arrived = pend_b.arrived = 0;
 
-    while (seq < B) {
-        const int L = __builtin_amdgcn_readfirstlane(ctx_clamped(d, seq));
-        const int n_pages = (L + T - 1) / T;
-        const int pl = n_pages > 0 ? n_pages : 1;
-        const int last_valid = L - (n_pages - 1) * T;
-        const uint32_t seq_g0 = (uint32_t)P * Hkv;
-        if (seq_g0 >= gend) break;
-        int kvh = gbeg > seq_g0 ? (int)((gbeg - seq_g0) / (uint32_t)pl) : 0;
-        for (; kvh < Hkv; ++kvh) {
-            const uint32_t g0 = seq_g0 + (uint32_t)kvh * pl;           // where this segment starts on the line
-            if (g0 >= gend) break;
-            const int pb = gbeg > g0 ? (int)(gbeg - g0) : 0;
-            const int pe = gend - g0 < (uint32_t)pl ? (int)(gend - g0) : pl;
-            float *out_row = d.out + ((size_t)seq * d.Hq + kvh * g + n) * D;
-            if (n_pages == 0) {                  // empty context: the row is defined as zero
-                if (pb == 0 && n < g) {
+    // prologue of the stream: the first pages of the first piece, and its q
+    PageRegs<D, DT> ring[RING];
+    {
+        const int32_t *row = d.table + (size_t)cur.seq * d.row_stride;
+        const int live_n = cur.n_pages > 0 ? cur.pe - cur.pb : 0;
 #pragma unroll
-                    for (int jt = 0; jt < TL::NV; ++jt)
-                        *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int r = 0; r < RING - 1; ++r) load_page<D, DT>(ring[r], d, row, cur.pb + r, r < live_n, cur.kvh, lane, bad);
+    }
+    bf16x8 qf[TL::NK], qn[TL::NK];
+    load_q<D>(qf, d, cur.seq, cur.kvh, lane);
+
+    State<D, DT> st;
+    PKV_STAMP(2);
+    int trace_first = 1;
+    while (cur.valid) {
+        const Piece nxt = piece_next(cur, d, gbeg, gend);
+        // q of the next piece travels while this piece streams (of this piece again if there is no next)
+        load_q<D>(qn, d, nxt.valid ? nxt.seq : cur.seq, nxt.valid ? nxt.kvh : cur.kvh, lane);
+#pragma unroll
+        for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st.m = -INFINITY;
+        st.l = 0.f;
+
+        const int32_t *row_c = d.table + (size_t)cur.seq * d.row_stride;
+        const int32_t *row_n = d.table + (size_t)(nxt.valid ? nxt.seq : cur.seq) * d.row_stride;
+        const int n_live = cur.n_pages > 0 ? cur.pe - cur.pb : 0;       // pages to read and process
+        const int n_next = (nxt.valid && nxt.n_pages > 0) ? nxt.pe - nxt.pb : 0;
+        const int n_turn = n_live > 0 ? n_live : 1;                     // an empty segment still takes a turn
+        const int last_valid = cur.L - (cur.n_pages - 1) * T;
+        for (int t0 = 0; t0 < n_turn; t0 += RING) {
+            const bool last_turn = t0 + RING >= n_turn;
+#pragma unroll
+            for (int r = 0; r < RING; ++r) {
+                // fetch: position RING-1 of this turn (r == 0), else position r-1 of the next
+                // turn, which belongs to the next piece when this is the piece's last turn
+                if (r == 0) {
+                    const int i = t0 + RING - 1;
+                    load_page<D, DT>(ring[RING - 1], d, row_c, cur.pb + i, i < n_live, cur.kvh, lane, bad);
+                } else {
+                    const int j = r - 1;
+                    const int32_t *row = last_turn ? row_n : row_c;
+                    const int page = last_turn ? nxt.pb + j : cur.pb + t0 + RING + j;
+                    const bool live = last_turn ? j < n_next : t0 + RING + j < n_live;
+                    const int kvh = last_turn ? nxt.kvh : cur.kvh;
+                    load_page<D, DT>(ring[j], d, row, page, live, kvh, lane, bad);
                 }
-                continue;
+                const int i = t0 + r;
+                if (i < n_live)
+                    process_page<D, DT>(st, ring[r], qf, d.scale_log2, cur.pb + i == cur.n_pages - 1 ? last_valid : T, G);
+#if defined(PKV_TRACE)
+                if (trace_first) { trace_first = 0; PKV_STAMP(3); }
+#endif
             }
-            State<D, DT> st;
-            float l;
-            run_piece<D, DT>(st, l, d, seq, kvh, pb, pe, n_pages, last_valid, lane, bad);
-            const uint32_t k0 = g0 / share, k1 = (g0 + (uint32_t)n_pages - 1) / share;
+        }
+
+        // --- the piece is done: finish the segment or park a partial
+        float *out_row = d.out + ((size_t)cur.seq * d.Hq + cur.kvh * g + n) * D;
+        if (cur.n_pages == 0) {                  // empty context: the row is defined as zero
+            if (cur.pb == 0 && n < g) {
+#pragma unroll
+                for (int jt = 0; jt < TL::NV; ++jt)
+                    *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        } else {
+            float l = st.l;
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const uint32_t k0 = cur.g0 / share, k1 = (cur.g0 + (uint32_t)cur.n_pages - 1) / share;
             if (k0 == k1) {                      // the whole segment was ours
                 if (n < g) {
                     const float inv = 1.0f / l;
@@ -403,68 +554,60 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
                     for (int jt = 0; jt < TL::NV; ++jt)
                         *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = st.acc[jt] * inv;
                 }
-                continue;
-            }
-            // park the partial, then the wave that arrives last merges all of them
-            float *w = pb == 0 ? ws_b : ws_a;
-            if (n < g) {
+            } else {
+                float *w = cur.pb == 0 ? ws_b : ws_a;
+                if (n < g) {
 #pragma unroll
-                for (int jt = 0; jt < TL::NV; ++jt)
-                    *reinterpret_cast<f32x4 *>(w + n * D + 16 * jt + 4 * G) = st.acc[jt];
-                if (G == 0) {
-                    w[g * D + n] = st.m;
-                    w[g * D + g + n] = l;
+                    for (int jt = 0; jt < TL::NV; ++jt)
+                        *reinterpret_cast<f32x4 *>(w + n * D + 16 * jt + 4 * G) = st.acc[jt];
+                    if (G == 0) {
+                        w[g * D + n] = st.m;
+                        w[g * D + g + n] = l;
+                    }
                 }
-            }
-#if defined(PKV_EXP_NO_MERGE)
-            continue;   // timing experiment only: results of split segments are wrong
+#if !defined(PKV_EXP_NO_MERGE)
+                // The partials and the arrival counters live in uncached device memory, so every
+                // access goes to memory itself and is visible to all XCDs without flushing an L2.
+                // Order is all that is left to enforce: the partial must have landed before the
+                // counter moves.  The count itself is looked at only when the share is finished.
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                uint32_t arrived = 0;
+                if (lane == 0) arrived = atomicAdd(d.cnt + (size_t)cur.seq * Hkv + cur.kvh, 1u);
+                Pending &pd = cur.pb == 0 ? pend_b : pend_a;
+                pd.valid = 1;
+                pd.seq = cur.seq;
+                pd.kvh = cur.kvh;
+                pd.k0 = k0;
+                pd.k1 = k1;
+                pd.arrived = arrived;
 #endif
-            // The partials and the arrival counters live in uncached device memory, so every
-            // access goes to memory itself and is visible to all XCDs without flushing an L2.
-            // Order is all that is left to enforce: the partial must have landed before the
-            // counter moves, and the merge loads are issued only after the counter came back.
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            uint32_t *cnt = d.cnt + (size_t)seq * Hkv + kvh;
-            uint32_t arrived = 0;
-            if (lane == 0) arrived = atomicAdd(cnt, 1u);
-            arrived = __shfl(arrived, 0);
-            asm volatile("" ::: "memory");
-            if (arrived != k1 - k0) continue;
-            if (lane == 0) *cnt = 0u;                          // ready for the next launch
-            // online-softmax merge: M = max m_c, out = sum_c 2^(m_c-M) a_c / sum_c 2^(m_c-M) l_c.
-            // Piece c of the segment sits in share k0 + c: slot b of that share for c = 0,
-            // slot a otherwise.
-            const int n_pc = (int)(k1 - k0) + 1;
-            const float *base = d.ws + (size_t)(2 * k0) * pf;
-            for (int i = lane; i < n_pc * g; i += 64) {
-                const int c = i / g, hn = i - c * g;
-                const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf + g * D;
-                s_m[i] = wc[hn];
-                s_l[i] = wc[g + hn];
             }
-            __builtin_amdgcn_wave_barrier();     // one wave per work-group: program order is enough
-            constexpr int D4 = D / 4;
-            for (int e = lane; e < g * D4; e += 64) {
-                const int hn = e / D4, x = e - hn * D4;
-                float M = -INFINITY;
-                for (int c = 0; c < n_pc; ++c) M = fmaxf(M, s_m[c * g + hn]);
-                f32x4 num = {0.f, 0.f, 0.f, 0.f};
-                float den = 0.f;
-#pragma unroll 8
-                for (int c = 0; c < n_pc; ++c) {
-                    const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf;
-                    const float f = __builtin_amdgcn_exp2f(s_m[c * g + hn] - M);
-                    den += f * s_l[c * g + hn];
-                    num += f * *reinterpret_cast<const f32x4 *>(wc + hn * D + 4 * x);
-                }
-                *reinterpret_cast<f32x4 *>(d.out + ((size_t)seq * d.Hq + kvh * g + hn) * D + 4 * x) = num * (1.0f / den);
-            }
-            __builtin_amdgcn_wave_barrier();
         }
-        P += pl;
-        ++seq;
+        cur = nxt;
+#pragma unroll
+        for (int j = 0; j < TL::NK; ++j) qf[j] = qn[j];
+    }
+
+    // --- merges this wave owes: it arrived last at a segment shared with other waves
+    (void)trace_first;
+    PKV_STAMP(4);
+    asm volatile("" ::: "memory");
+    if (pend_a.valid) {
+        const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)pend_a.arrived);
+        if (arrived == pend_a.k1 - pend_a.k0) {
+            if (lane == 0) d.cnt[(size_t)pend_a.seq * Hkv + pend_a.kvh] = 0u;     // ready for the next launch
+            merge_segment<D>(d, pend_a, lane, s_m, s_l);
+        }
+    }
+    if (pend_b.valid) {
+        const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)pend_b.arrived);
+        if (arrived == pend_b.k1 - pend_b.k0) {
+            if (lane == 0) d.cnt[(size_t)pend_b.seq * Hkv + pend_b.kvh] = 0u;
+            merge_segment<D>(d, pend_b, lane, s_m, s_l);
+        }
     }
     if (bad && lane == 0) atomicOr(d.err, 1u);
+    PKV_STAMP(5);
 }
 
 __device__ __forceinline__ int find_model(const AttnGroup &grp, int item) {

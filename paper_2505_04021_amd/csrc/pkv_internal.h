@@ -78,6 +78,7 @@ struct AttnDesc {
     float *ws;                  // split-K partials: two per work item (uncached memory)
     uint32_t *cnt;              // [B][Hkv] arrival counters of the split-K merge, zero between launches
     uint32_t *err;              // device error flags
+    uint64_t *trace;            // NULL, or [grid][8] time stamps (instrumented builds only)
     uint64_t frame_bytes, block_bytes;
     FastDiv slots_div;
     uint32_t max_block_id;      // n_frames * slots
