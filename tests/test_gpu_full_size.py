@@ -1,0 +1,117 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py
+times (grouped launch over the library's own block tables, automatic work split).
+
+The oracle cannot afford whole batches at these sizes, so both sides write the KV
+of a sample of the sequences only (everything else keeps whatever the pool held);
+bookkeeping is replayed in full and compared bit for bit, attention is compared on
+the sampled sequences' output rows.
+"""
+import numpy as np
+import pytest
+
+from parity import TOL, row_rel_err
+from workloads.scenarios import Runner, make_config
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from paper_2505_04021_amd import PrismKV
+    return PrismKV()
+
+
+def grouped_decode(gpu, rg, t):
+    """One grouped launch over all active models, as the benchmark issues it."""
+    import torch
+    mids = rg.active_models()
+    qs = [torch.from_numpy(rg.queries(t, mi).view(np.int16)).cuda() for mi in mids]
+    ctxs = [torch.from_numpy(rg.ctx[mi]).cuda() for mi in mids]
+    outs = [torch.full((rg.cfg.models[mi].batch, rg.cfg.models[mi].q_heads, rg.cfg.models[mi].head_dim),
+                       float("nan"), dtype=torch.float32, device="cuda") for mi in mids]
+    assert gpu.decode_attention_multi_dev([rg.models[mi] for mi in mids], qs, ctxs, outs) == 0
+    torch.cuda.synchronize()
+    return {mi: o.cpu().numpy() for mi, o in zip(mids, outs)}
+
+
+def compare_sampled(gpu, oracle, rg, ro, t):
+    outs = grouped_decode(gpu, rg, t)
+    worst = 0.0
+    for mi in rg.active_models():
+        rows = rg.filled_rows(mi)
+        assert rows == ro.filled_rows(mi)
+        if not rows:
+            continue
+        rows = np.array(rows)
+        q = ro.queries(t, mi)[rows]
+        table = oracle.block_table_rows(ro.models[mi], rg.cfg.models[mi].batch)[rows]
+        rc, ref = oracle.decode_attention(ro.models[mi], q, ro.ctx[mi][rows], table)
+        assert rc == 0
+        err = row_rel_err(outs[mi][rows], ref)
+        assert err <= TOL[rg.cfg.models[mi].dtype], (t, mi, err)
+        worst = max(worst, err)
+    return worst
+
+
+def sample_longest_median_shortest(cfg, per_model):
+    """uids of the first batch are 0..batch-1 in slot order; pick by drawn length."""
+    probe = Runner(None, cfg)
+    chosen = set()
+    for mi, spec in enumerate(cfg.models):
+        ctx = probe._draw_ctx(spec.batch, (mi, 0))
+        order = np.argsort(ctx, kind="stable")
+        picks = {int(order[0]), int(order[len(order) // 2]), int(order[-1])}
+        for k in list(order[:: max(1, len(order) // per_model)]):
+            if len(picks) < per_model:
+                picks.add(int(k))
+        for s in sorted(picks)[:max(per_model, 3)]:
+            chosen.add((mi, s))
+    return chosen
+
+
+@pytest.mark.parametrize("cfg_id,per_model", [(2, 3), (4, 1), (5, 3)])
+def test_full_size_static(gpu, oracle, cfg_id, per_model):
+    cfg = make_config(cfg_id, "full")
+    fill = sample_longest_median_shortest(cfg, per_model) if cfg_id != 4 else {(0, 5)}
+    rg, ro = Runner(gpu, cfg, fill=fill).setup(), Runner(oracle, cfg, fill=fill).setup()
+    try:
+        assert rg.log == ro.log
+        steps = [0] if cfg_id != 5 else [0, 10, 20]
+        for t in range(max(steps) + 1):
+            rg.step(t)
+            ro.step(t)
+            assert rg.log == ro.log
+            assert np.array_equal(gpu.pool_export_state(rg.pool), oracle.pool_export_state(ro.pool)), t
+            if t in steps:
+                print(f"cfg {cfg_id} step {t}: sampled rel err {compare_sampled(gpu, oracle, rg, ro, t):.2e}")
+        assert gpu.device_errors() == 0
+    finally:
+        rg.teardown()
+        ro.teardown()
+
+
+def test_full_size_bursty_1000_steps(gpu, oracle):
+    """cfg 3 at full size: 8 models on a 160 GB pool, 1000 steps of Markov on/off
+    activity.  Pool state after every step; attention on steps 0..9 and every 50th
+    for the sampled sequences (every 16th admitted sequence of each model)."""
+    cfg = make_config(3, "full")
+    fill = lambda mi, uid: uid % 16 == 0          # noqa: E731
+    rg, ro = Runner(gpu, cfg, fill=fill).setup(), Runner(oracle, cfg, fill=fill).setup()
+    check = set(range(10)) | set(range(0, cfg.steps, 50))
+    worst, n_active = 0.0, 0
+    try:
+        for t in range(cfg.steps):
+            rg.step(t)
+            ro.step(t)
+            assert rg.log == ro.log, t
+            assert np.array_equal(gpu.pool_export_state(rg.pool), oracle.pool_export_state(ro.pool)), t
+            n_active += len(rg.active_models())
+            if t in check and rg.active_models():
+                worst = max(worst, compare_sampled(gpu, oracle, rg, ro, t))
+            if t % 100 == 0:
+                print(f"step {t}: active {rg.active_models()} worst rel err {worst:.2e}", flush=True)
+        assert gpu.device_errors() == 0
+        assert 0.25 < n_active / (cfg.steps * len(cfg.models)) < 0.55      # stationary activity near 0.4
+    finally:
+        rg.teardown()
+        ro.teardown()

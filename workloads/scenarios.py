@@ -124,7 +124,8 @@ def kv_bytes(cfg: Config, spec: ModelSpec, ctx_lens) -> int:
 
 class Runner:
     """Drives one backend through a scenario.  `fill` selects which sequences get
-    their KV written: None = all, else a set of (model index, sequence uid)."""
+    their KV written: None = all, a set of (model index, sequence uid), or a
+    predicate fill(model index, uid)."""
 
     def __init__(self, be, cfg: Config, fill=None, write_kv: bool = True):
         self.be, self.cfg = be, cfg
@@ -152,6 +153,18 @@ class Runner:
         if rc < 0:
             raise RuntimeError(f"{self.be.name}: {what} returned {rc}")
         return rc
+
+    def _wants(self, mi, uid):
+        if self.fill is None:
+            return True
+        if callable(self.fill):
+            return bool(self.fill(mi, int(uid)))
+        return (mi, int(uid)) in self.fill
+
+    def filled_rows(self, mi):
+        """Sequence slots of model mi whose KV has been written."""
+        return [s for s in range(self.cfg.models[mi].batch)
+                if self.uid[mi][s] >= 0 and self._wants(mi, self.uid[mi][s])]
 
     def _draw_ctx(self, n, key):
         c, g = self.cfg, gen.generator(self.cfg.seed, 11, *key)
@@ -186,7 +199,7 @@ class Runner:
             self.uid[mi][s] = u
             self.ctx[mi][s] = n_tok
             self.blocks[mi] += int(self._blocks(n_tok))
-            if self.write_kv and (self.fill is None or (mi, u) in self.fill):
+            if self.write_kv and self._wants(mi, u):
                 kv = gen.seq_kv((c.seed, 13, mi, u), int(n_tok), spec.kv_heads, spec.head_dim,
                                 spec.dtype, c.page_tokens, c.peak_frac)
                 self._need("kv_write", self.be.kv_write(m, int(s), 0, kv["k"], kv["v"],
