@@ -154,7 +154,7 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    gpu.timing_enable(True)
+    gpu.timing_enable(8)          # the kernel's own duration: every 8th launch of the timed region
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -173,7 +173,7 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     gbps = total_bytes / wall / 1e9
     attn_avg_ms = attn_ms / max(n_rec, 1)
-    rec_bytes = sum(kv_per_rep[i % len(reps)] for i in range(n_rec)) / max(n_rec, 1)
+    rec_bytes = sum(kv_per_rep[i % len(reps)] for i in range(0, args.steps, 8)) / max(n_rec, 1)
     attn_gbps = rec_bytes / (attn_avg_ms * 1e-3) / 1e9 if n_rec else 0.0
 
     result = {

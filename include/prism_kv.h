@@ -176,12 +176,12 @@ int decode_attention_multi(int n_models, const int *models, const int *batches,
 long pool_export_state(int pool, void *host_buf, size_t cap);
 int pool_stats(int pool, pkv_stats *out);
 
-/* Per-kernel timing for measurements: while enabled, every decode_attention* call
- * brackets its attention kernel with HIP events on the library's stream (at most
- * 8192 calls are recorded).  pkv_timing_read waits for the stream, returns the
- * number of recorded calls and the summed kernel time in milliseconds, and clears
- * the record. */
-int pkv_timing_enable(int on);
+/* Per-kernel timing for measurements: with every = n > 0, every n-th decode_attention*
+ * call brackets its attention kernel with HIP events on the library's stream (at most
+ * 8192 calls are recorded); 0 switches it off.  pkv_timing_read waits for the stream,
+ * returns the number of recorded calls and the summed kernel time in milliseconds, and
+ * clears the record. */
+int pkv_timing_enable(int every);
 long pkv_timing_read(double *attention_ms);
 /* Measured ceilings for comparison: reads a freshly allocated buffer of `bytes` bytes
  * (a power of two) `iters` times with a kernel that does no arithmetic and reports

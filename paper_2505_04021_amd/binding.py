@@ -109,8 +109,9 @@ class PrismKV:
             raise RuntimeError(f"pkv_stream_read_probe failed: {rc} {self.last_error()}")
         return g.value
 
-    def timing_enable(self, on=True):
-        return self.lib.pkv_timing_enable(1 if on else 0)
+    def timing_enable(self, every=1):
+        """every = n: bracket every n-th attention launch with events; 0 / False = off."""
+        return self.lib.pkv_timing_enable(int(every))
 
     def timing_read(self):
         """(recorded calls, attention kernel ms summed since the last read)."""

@@ -79,7 +79,8 @@ int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
 uint32_t *g_err = nullptr;         // device error flags
 uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
 int g_items = 0, g_min_share = 0;   // measurement knobs (0 = automatic)
-bool g_timing = false;
+int g_timing = 0;                 // 0 = off, n = bracket every n-th attention launch with events
+long g_launches = 0;
 std::vector<hipEvent_t> g_events;   // pairs: before and after the attention kernel
 size_t g_events_used = 0;
 constexpr size_t kMaxTimedLaunches = 8192;
@@ -130,11 +131,12 @@ void free_model_dev(Model &m) {
     m.ws_floats = m.cnt_cap = 0;
 }
 
-// Work items (waves) per attention launch.  The chip holds 256 CUs x 4 SIMDs x 2
-// resident waves of this kernel; twice that many items lets the dispatcher even out
-// CUs that run ahead.  Each model of a grouped launch gets items in proportion to the
-// KV bytes it is expected to read.
-constexpr int kDefaultItems = 4096;
+// Work items (waves) per attention launch: what the chip holds at once (256 CUs x 4 SIMDs
+// x 2 resident waves of this kernel), so every wave starts at once and takes one equal
+// share of the pages.  More, smaller items were measured to be slower: an item that
+// starts while the memory system is saturated pays ~10 us before its first page arrives.
+// Each model of a grouped launch gets items in proportion to the KV bytes it will read.
+constexpr int kDefaultItems = 2048;
 constexpr int kDefaultMinShare = 4;
 
 double est_bytes(const Model &m, bool own, int batch, int row_stride) {
@@ -194,7 +196,7 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
 }
 
 hipEvent_t *next_events() {
-    if (!g_timing || g_events_used + 2 > 2 * kMaxTimedLaunches) return nullptr;
+    if (!g_timing || (g_launches++ % g_timing) != 0 || g_events_used + 2 > 2 * kMaxTimedLaunches) return nullptr;
     while (g_events.size() < g_events_used + 2) {
         hipEvent_t e;
         if (hipEventCreate(&e) != hipSuccess) return nullptr;
@@ -209,8 +211,10 @@ hipEvent_t *next_events() {
 
 extern "C" {
 
-int pkv_timing_enable(int on) {
-    g_timing = on != 0;
+int pkv_timing_enable(int every) {
+    if (every < 0) return PKV_E_ARG;
+    g_timing = every;
+    g_launches = 0;
     g_events_used = 0;
     return PKV_OK;
 }

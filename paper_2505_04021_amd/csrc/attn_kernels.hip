@@ -409,19 +409,45 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
     using TL = Tile<D, DT>;
     const int lane = threadIdx.x;
     PKV_STAMP(0);
+#if defined(PKV_TRACE)
+    if (threadIdx.x == 0 && d.trace)      // where the wave runs: HW_ID in the low word, XCC_ID above
+        d.trace[(size_t)blockIdx.x * 8 + 6] = (uint64_t)__builtin_amdgcn_s_getreg(63492) |
+                                              ((uint64_t)__builtin_amdgcn_s_getreg(63508) << 32);
+#endif
     const int G = lane >> 4, n = lane & 15;
     const int g = d.g, Hkv = d.Hkv, B = d.batch;
 
-    // --- planned pages per sequence, prefix sums across the wave
+    // --- planned pages per sequence, prefix sums across the wave.  Batches of up to
+    // 64 * LINE_REGS sequences keep every context length in registers, so that finding
+    // the first segment costs no further memory access.
+    constexpr int LINE_REGS = 4;
     const int K = (B + 63) >> 6;                    // sequences per lane
+    int Lc[LINE_REGS];
     int my_sum = 0, my_max = 0;
-    for (int k = 0; k < K; ++k) {
+#pragma unroll
+    for (int k = 0; k < LINE_REGS; ++k) {
         const int sq = lane * K + k;
-        if (sq < B) {
-            const int np = (ctx_clamped(d, sq) + T - 1) / T;
-            const int pl = np > 0 ? np : 1;
-            my_sum += pl;
-            my_max = pl > my_max ? pl : my_max;
+        Lc[k] = (k < K && sq < B) ? ctx_clamped(d, sq) : -1;
+    }
+    if (K <= LINE_REGS) {
+#pragma unroll
+        for (int k = 0; k < LINE_REGS; ++k) {
+            if (Lc[k] >= 0) {
+                const int np = (Lc[k] + T - 1) / T;
+                const int pl = np > 0 ? np : 1;
+                my_sum += pl;
+                my_max = pl > my_max ? pl : my_max;
+            }
+        }
+    } else {
+        for (int k = 0; k < K; ++k) {
+            const int sq = lane * K + k;
+            if (sq < B) {
+                const int np = (ctx_clamped(d, sq) + T - 1) / T;
+                const int pl = np > 0 ? np : 1;
+                my_sum += pl;
+                my_max = pl > my_max ? pl : my_max;
+            }
         }
     }
     int incl = my_sum;
@@ -455,19 +481,35 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
         const uint32_t lo = (uint32_t)(incl - my_sum) * Hkv, hi = (uint32_t)incl * Hkv;
         const unsigned long long own = __ballot(lo <= gbeg && gbeg < hi);
         const int owner = __ffsll(own) - 1;
-        int fs = 0, fp = incl - my_sum;
-        for (int k = 0; k < K; ++k) {               // only the owner's walk matters
-            const int sq = lane * K + k;
-            if (sq < B) {
-                const int np = (ctx_clamped(d, sq) + T - 1) / T;
-                const int pl = np > 0 ? np : 1;
-                if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl; else { fs = sq; break; }
+        int fs = 0, fp = incl - my_sum, fl = 0;     // sequence, pages before it, its context length
+        if (K <= LINE_REGS) {
+            bool found = false;
+#pragma unroll
+            for (int k = 0; k < LINE_REGS; ++k) {
+                if (!found && Lc[k] >= 0) {
+                    const int np = (Lc[k] + T - 1) / T;
+                    const int pl = np > 0 ? np : 1;
+                    if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl;
+                    else { fs = lane * K + k; fl = Lc[k]; found = true; }
+                }
+            }
+        } else {
+            for (int k = 0; k < K; ++k) {           // only the owner's walk matters
+                const int sq = lane * K + k;
+                if (sq < B) {
+                    const int L1 = ctx_clamped(d, sq);
+                    const int np = (L1 + T - 1) / T;
+                    const int pl = np > 0 ? np : 1;
+                    if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl; else { fs = sq; fl = L1; break; }
+                }
             }
         }
-        const int seq0 = __builtin_amdgcn_readfirstlane(__shfl(fs, owner));
-        const int P0 = __builtin_amdgcn_readfirstlane(__shfl(fp, owner));
-        piece_set_seq(cur, d, seq0, P0);
-        cur.kvh = (int)((gbeg - (uint32_t)P0 * Hkv) / (uint32_t)cur.pl);
+        cur.seq = __builtin_amdgcn_readfirstlane(__shfl(fs, owner));
+        cur.P = __builtin_amdgcn_readfirstlane(__shfl(fp, owner));
+        cur.L = __builtin_amdgcn_readfirstlane(__shfl(fl, owner));
+        cur.n_pages = (cur.L + T - 1) / T;
+        cur.pl = cur.n_pages > 0 ? cur.n_pages : 1;
+        cur.kvh = (int)((gbeg - (uint32_t)cur.P * Hkv) / (uint32_t)cur.pl);
         piece_clip(cur, d, gbeg, gend);
     }
 
