@@ -35,6 +35,7 @@ def parse_args():
     ap.add_argument("--min-share", type=int, default=0, help="smallest share of pages per wave (0 = automatic)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     ap.add_argument("--no-balloon", action="store_true")
+    ap.add_argument("--page-cost", type=int, default=-1, help="fixed cost of a page in the wave-sharing model, per mille (-1 = default)")
     ap.add_argument("--sweep-items", default="", help="comma list of work-item counts to time before the main run (stderr)")
     return ap.parse_args()
 
@@ -125,6 +126,8 @@ def main():
 
     gpu = PrismKV("cuda:0")
     gpu.set_split(args.items, args.min_share)
+    if args.page_cost >= 0:
+        gpu.set_page_cost(args.page_cost)
     reps = build_replicas(gpu, args.config, args.size, args.replicas)
     inputs = [device_inputs(torch, rep, 0) for rep in reps]
     kv_per_rep = [rep.kv_bytes_step() for rep in reps]

@@ -186,13 +186,16 @@ long pkv_timing_read(double *attention_ms);
 /* Measured ceilings for comparison: reads a freshly allocated buffer of `bytes` bytes
  * (a power of two) `iters` times with a kernel that does no arithmetic and reports
  * the read bandwidth in GB/s.  granule_bytes = 0: plain streaming read; otherwise a
- * power of two >= 8192: whole granules of that size are read in a scrambled order,
+ * power of two >= 1024: whole granules of that size are read in a scrambled order,
  * the access pattern of paged KV tiles.  Allocates and frees its buffer; synchronises. */
 int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double *gbps);
 /* Measurement / test knobs of the attention work split: `items` = work items (waves)
  * per launch, `min_share` = smallest number of pages a wave may be given; 0 selects
  * the automatic value of either. */
 int pkv_set_split(int items, int min_share);
+/* Cost model that shares the waves out among the models of a grouped launch: a page
+ * costs per_mille/1000 + 0.1 per KiB of its K and V tile (default 800). */
+int pkv_set_page_cost(int per_mille);
 /* Host-side check of the multiply-shift division the kernels use to split a block
  * id into (frame, slot): returns n / d computed that way. */
 uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d);

@@ -33,6 +33,7 @@ def _load():
         "pkv_last_error": (C.c_char_p, []),
         "pkv_device_errors": (i, []),
         "pkv_set_split": (i, [i, i]),
+        "pkv_set_page_cost": (i, [i]),
         "pkv_debug_fastdiv": (u32, [u32, u32]),
         "pkv_stream_read_probe": (i, [sz, sz, i, C.POINTER(C.c_double)]),
         "pkv_timing_enable": (i, [i]),
@@ -64,7 +65,7 @@ def _load():
     return lib
 
 
-EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_debug_fastdiv",
+EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_set_page_cost", "pkv_debug_fastdiv",
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
@@ -98,6 +99,9 @@ class PrismKV:
 
     def device_errors(self):
         return self.lib.pkv_device_errors()
+
+    def set_page_cost(self, per_mille=800):
+        return self.lib.pkv_set_page_cost(per_mille)
 
     def set_split(self, items=0, min_share=0):
         return self.lib.pkv_set_split(items, min_share)

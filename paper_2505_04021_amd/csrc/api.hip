@@ -78,7 +78,8 @@ BookResult *g_res = nullptr;       // pinned host
 int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
 uint32_t *g_err = nullptr;         // device error flags
 uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
-int g_items = 0, g_min_share = 0;   // measurement knobs (0 = automatic)
+int g_items = 0, g_min_share = 0;
+double g_page_cost = 0.8;            // fixed cost of a page relative to 0.1 per KiB   // measurement knobs (0 = automatic)
 int g_timing = 0;                 // 0 = off, n = bracket every n-th attention launch with events
 long g_launches = 0;
 std::vector<hipEvent_t> g_events;   // pairs: before and after the attention kernel
@@ -139,9 +140,14 @@ void free_model_dev(Model &m) {
 constexpr int kDefaultItems = 2048;
 constexpr int kDefaultMinShare = 4;
 
+// Expected cost of a model's pages, used to share the waves out among the models of a
+// grouped launch.  A wave spends a fixed time per page (the load - MFMA - softmax - MFMA
+// chain) plus a time per byte; measured on MI355X the two are about equal for a 8 KiB
+// page, so a model of small pages needs more waves than its bytes alone suggest.
 double est_bytes(const Model &m, bool own, int batch, int row_stride) {
     const double blocks = own ? (double)m.used_blocks : (double)batch * row_stride;
-    return blocks * (double)m.block_bytes;
+    const double page_kib = (double)m.block_bytes / m.Hkv / 1024.0;
+    return blocks * m.Hkv * (g_page_cost + 0.1 * page_kib);
 }
 
 int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *table, int row_stride,
@@ -170,7 +176,7 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     const double units = ((own ? (double)m.used_blocks : (double)batch * d.row_stride) + batch) * m.Hkv;
     double items = (g_items > 0 ? g_items : kDefaultItems) * share_of_launch;
     if (items > units / d.min_share) items = units / d.min_share;
-    d.n_items = items < 1.0 ? 1 : (int)(items + 0.5);
+    d.n_items = items < 1.0 ? 1 : (int)items;                // never more than the slots in total
     const size_t need = (size_t)2 * d.n_items * m.g * (m.D + 2);
     if (need > m.ws_floats) {
         HIP_TRY(hipStreamSynchronize(g_stream));
@@ -250,6 +256,12 @@ int pkv_device_errors(void) {
     return (int)v;
 }
 
+int pkv_set_page_cost(int per_mille) {
+    if (per_mille < 0 || per_mille > 100000) return PKV_E_ARG;
+    g_page_cost = per_mille / 1000.0;
+    return PKV_OK;
+}
+
 int pkv_set_split(int items, int min_share) {
     if (items < 0 || items > (1 << 20) || min_share < 0 || min_share > 4096) return PKV_E_ARG;
     g_items = items;
@@ -260,7 +272,7 @@ int pkv_set_split(int items, int min_share) {
 int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double *gbps) {
     if (bytes < (1u << 20) || iters <= 0 || !gbps) return PKV_E_ARG;
     if ((bytes & (bytes - 1)) != 0) return PKV_E_ARG;
-    if (granule_bytes != 0 && (granule_bytes < 8192 || (granule_bytes & (granule_bytes - 1)) != 0 || granule_bytes > bytes))
+    if (granule_bytes != 0 && (granule_bytes < 1024 || (granule_bytes & (granule_bytes - 1)) != 0 || granule_bytes > bytes))
         return PKV_E_ARG;
     int rc = lib_init();
     if (rc) return rc;
@@ -566,6 +578,7 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     grp.n = 1;
     int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
     if (rc) return rc;
+
     HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
     return PKV_OK;
 }

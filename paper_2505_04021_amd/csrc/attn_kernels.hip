@@ -89,6 +89,22 @@ struct PageRegs {
     float sk, sv;
 };
 
+// Block ids of a page pair.  They are read through the scalar cache one step before the
+// loads that need them are issued, so the latency of this dependent access (block table
+// -> address -> K/V load) is covered by the arithmetic of the step in between.
+struct PairIds {
+    uint32_t a, b;
+};
+
+__device__ __forceinline__ PairIds fetch_ids(const AttnDesc &d, const int32_t *row, int page) {
+    const int last = d.row_stride - 1;
+    const int ia = page < last ? page : last, ib = page + 1 < last ? page + 1 : last;
+    PairIds ids;
+    ids.a = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[ia]);
+    ids.b = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[ib]);
+    return ids;
+}
+
 // Issue the loads of one page (K tile, V tile) of one kv head.  Buffer loads with a
 // per-page resource descriptor: a page beyond the chunk (live == false) gets a
 // descriptor of zero records, so its loads return zeros without touching memory.
@@ -96,12 +112,9 @@ struct PageRegs {
 // compiler count outstanding loads exactly (s_waitcnt vmcnt(N) with N > 0) instead of
 // draining the queue at each control-flow join.
 template <int D, int DT>
-__device__ __forceinline__ void load_page(PageRegs<D, DT> &r, const AttnDesc &d, const int32_t *row, int page,
-                                          bool live, int kvh, int lane, uint32_t &bad) {
+__device__ __forceinline__ void load_page(PageRegs<D, DT> &r, const AttnDesc &d, uint32_t id, bool live, int kvh,
+                                          int lane, uint32_t &bad) {
     using TL = Tile<D, DT>;
-    const int idx = page < d.row_stride ? page : d.row_stride - 1;
-    // wave-uniform by construction; say so, so that it lives in scalar registers
-    uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[idx]);
     if (id >= d.max_block_id) {          // never dereference an id outside the pool
         bad |= live ? 1u : 0u;           // reported once, after the last load (no store inside the loop)
         id = 0;
@@ -113,6 +126,7 @@ __device__ __forceinline__ void load_page(PageRegs<D, DT> &r, const AttnDesc &d,
         const float *hdr = reinterpret_cast<const float *>(blk);
         r.sk = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[kvh])));
         r.sv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[d.Hkv + kvh])));
+        if (!live) r.sk = r.sv = 0.f;      // a dead page may sit on a block that was never written
         blk += PKV_FP8_HEADER;
     }
     const uint8_t *tiles = blk + (size_t)kvh * 2 * TL::TILE_BYTES;
@@ -133,29 +147,37 @@ struct State {
     float m, l;                   // running max (log2 domain) and this lane's share of the sum
 };
 
-// A operand of the PV product for output tile jt: V[4G..4G+3][16jt + (lane & 15)]
+// Two consecutive pages of a piece travel and are processed together (32 tokens): one
+// max / rescale step per 32 tokens and 16x16x32 MFMAs for the PV product.
 template <int D, int DT>
-__device__ __forceinline__ s16x4 v_operand(const PageRegs<D, DT> &r, int jt, uint32_t m01, uint32_t m23) {
-    u32x2 a;
-    if (DT == PKV_BF16) {
-        const u32x4 vv = r.v[jt >> 1];
-        a = (jt & 1) ? mk2(vv.z, vv.w) : mk2(vv.x, vv.y);
-    } else {
-        const u32x4 vv = r.v[jt >> 2];
-        const uint32_t w = (jt & 3) == 0 ? vv.x : (jt & 3) == 1 ? vv.y : (jt & 3) == 2 ? vv.z : vv.w;
-        a = fp8x4_to_bf16x4(w);
-    }
-    a.x &= m01;
-    a.y &= m23;
-    return *reinterpret_cast<s16x4 *>(&a);
-}
+struct PairRegs {
+    PageRegs<D, DT> a, b;
+};
 
 template <int D, int DT>
-__device__ __forceinline__ void process_page(State<D, DT> &st, const PageRegs<D, DT> &r, const bf16x8 *qf,
-                                             float scale_log2, int valid /*tokens valid in this page, 1..16*/,
-                                             int G) {
+__device__ __forceinline__ void load_pair(PairRegs<D, DT> &r, const AttnDesc &d, PairIds ids, bool live_a, bool live_b,
+                                          int kvh, int lane, uint32_t &bad) {
+    load_page<D, DT>(r.a, d, ids.a, live_a, kvh, lane, bad);
+    load_page<D, DT>(r.b, d, ids.b, live_b, kvh, lane, bad);
+}
+
+// max over the four 16-lane rows of a wave (lanes l, l^16, l^32, l^48), in every lane.
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of
+// its second, v_permlane16_swap the odd rows of the first with the even rows of the
+// second; fed the same value twice, the two results hold both partners of every lane.
+// No LDS traffic, so the step does not wait on the scalar-load / LDS counter.
+__device__ __forceinline__ float rows_max(float x) {
+    typedef unsigned u2 __attribute__((ext_vector_type(2)));
+    u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+// S[token][head] of one page: K (A operand, row = token) times q (B operand)
+template <int D, int DT>
+__device__ __forceinline__ f32x4 qk_page(const PageRegs<D, DT> &r, const bf16x8 *qf) {
     using TL = Tile<D, DT>;
-    const bool tail = valid < T;          // wave-uniform
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
     if (DT == PKV_BF16) {
 #pragma unroll
@@ -175,15 +197,53 @@ __device__ __forceinline__ void process_page(State<D, DT> &st, const PageRegs<D,
             s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*reinterpret_cast<bf16x8 *>(&kb), qf[2 * j2 + 1], s, 0, 0, 0);
         }
     }
-    const float sc = DT == PKV_E4M3 ? scale_log2 * r.sk : scale_log2;
+    return s;
+}
+
+// V of one page for output tile jt as four bf16: V[4G..4G+3][16jt + (lane & 15)]
+template <int D, int DT>
+__device__ __forceinline__ u32x2 v_half(const PageRegs<D, DT> &r, int jt) {
+    if (DT == PKV_BF16) {
+        const u32x4 vv = r.v[jt >> 1];
+        return (jt & 1) ? mk2(vv.z, vv.w) : mk2(vv.x, vv.y);
+    }
+    const u32x4 vv = r.v[jt >> 2];
+    const uint32_t w = (jt & 3) == 0 ? vv.x : (jt & 3) == 1 ? vv.y : (jt & 3) == 2 ? vv.z : vv.w;
+    return fp8x4_to_bf16x4(w);
+}
+
+// bf16 hi + lo of four probabilities: 16 significant bits reach the matrix unit
+__device__ __forceinline__ void split_p(const float *p, u32x2 &hi, u32x2 &lo) {
+    const uint32_t h01 = pack_bf16_rne(p[0], p[1]), h23 = pack_bf16_rne(p[2], p[3]);
+    const float l0 = p[0] - __uint_as_float(h01 << 16), l1 = p[1] - __uint_as_float(h01 & 0xffff0000u);
+    const float l2 = p[2] - __uint_as_float(h23 << 16), l3 = p[3] - __uint_as_float(h23 & 0xffff0000u);
+    hi = mk2(h01, h23);
+    lo = mk2(pack_bf16_rne(l0, l1), pack_bf16_rne(l2, l3));
+}
+
+// One online-softmax step over the 32 tokens of a page pair.  valid_a is 1..16,
+// valid_b 0..16 (0: the pair has no second page; its registers hold zeros).
+template <int D, int DT>
+__device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D, DT> &r, const bf16x8 *qf,
+                                             float scale_log2, int valid_a, int valid_b, int G) {
+    using TL = Tile<D, DT>;
+    const bool tail = valid_a < T || valid_b < T;          // wave-uniform
+    f32x4 sa = qk_page<D, DT>(r.a, qf);
+    f32x4 sb = qk_page<D, DT>(r.b, qf);
+    const float sca = DT == PKV_E4M3 ? scale_log2 * r.a.sk : scale_log2;
+    const float scb = DT == PKV_E4M3 ? scale_log2 * r.b.sk : scale_log2;
+    float s[8];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        s[i] *= sc;
-        if (tail && 4 * G + i >= valid) s[i] = -INFINITY;   // select, so a NaN logit of a dead token cannot leak
+        s[i] = sa[i] * sca;
+        s[4 + i] = sb[i] * scb;
+        if (tail) {                                        // select, so a NaN logit of a dead token cannot leak
+            if (4 * G + i >= valid_a) s[i] = -INFINITY;
+            if (4 * G + i >= valid_b) s[4 + i] = -INFINITY;
+        }
     }
-    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+    mx = rows_max(mx);
     const float m_new = fmaxf(st.m, mx);
     if (__any(m_new > st.m)) {            // wave-uniform: rescale only when some head's max moved
         const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
@@ -192,52 +252,62 @@ __device__ __forceinline__ void process_page(State<D, DT> &st, const PageRegs<D,
         for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] *= alpha;
         st.m = m_new;
     }
-    float p[4];
+    float p[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - st.m);
-    st.l += (p[0] + p[1]) + (p[2] + p[3]);
+    for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - st.m);
+    st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
     if (DT == PKV_E4M3) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p[i] *= r.sv;
+        for (int i = 0; i < 4; ++i) {
+            p[i] *= r.a.sv;
+            p[4 + i] *= r.b.sv;
+        }
     }
-    // P = hi + lo with both parts bf16: 16 significant bits reach the matrix unit
-    const uint32_t h01 = pack_bf16_rne(p[0], p[1]), h23 = pack_bf16_rne(p[2], p[3]);
-    const float l0 = p[0] - __uint_as_float(h01 << 16), l1 = p[1] - __uint_as_float(h01 & 0xffff0000u);
-    const float l2 = p[2] - __uint_as_float(h23 << 16), l3 = p[3] - __uint_as_float(h23 & 0xffff0000u);
-    u32x2 ph = mk2(h01, h23);
-    u32x2 pl = mk2(pack_bf16_rne(l0, l1), pack_bf16_rne(l2, l3));
-    const s16x4 phv = *reinterpret_cast<s16x4 *>(&ph), plv = *reinterpret_cast<s16x4 *>(&pl);
-    if (!tail) {
+    // B operand of the PV product: lane (G, head) holds P for tokens 4G..4G+3 of page a, then of page b
+    u32x2 ha, la, hb, lb;
+    split_p(p, ha, la);
+    split_p(p + 4, hb, lb);
+    u32x4 ph = mk4(ha.x, ha.y, hb.x, hb.y), pl = mk4(la.x, la.y, lb.x, lb.y);
+    const bf16x8 phv = *reinterpret_cast<bf16x8 *>(&ph), plv = *reinterpret_cast<bf16x8 *>(&pl);
+    // tokens past the context length may hold anything (even NaN): blank their V
+    uint32_t ma01 = 0xffffffffu, ma23 = 0xffffffffu, mb01 = 0xffffffffu, mb23 = 0xffffffffu;
+    if (tail) {
+        const int la_ = valid_a - 4 * G, lb_ = valid_b - 4 * G;
+        ma01 = la_ >= 2 ? 0xffffffffu : (la_ == 1 ? 0x0000ffffu : 0u);
+        ma23 = la_ >= 4 ? 0xffffffffu : (la_ == 3 ? 0x0000ffffu : 0u);
+        mb01 = lb_ >= 2 ? 0xffffffffu : (lb_ == 1 ? 0x0000ffffu : 0u);
+        mb23 = lb_ >= 4 ? 0xffffffffu : (lb_ == 3 ? 0x0000ffffu : 0u);
+    }
 #pragma unroll
-        for (int jt = 0; jt < TL::NV; ++jt) {
-            const s16x4 av = v_operand<D, DT>(r, jt, 0xffffffffu, 0xffffffffu);
-            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, phv, st.acc[jt], 0, 0, 0);
-            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, plv, st.acc[jt], 0, 0, 0);
-        }
-    } else {
-        // tokens past the context length may hold anything (even NaN): blank their V
-        const int left = valid - 4 * G;
-        const uint32_t m01 = left >= 2 ? 0xffffffffu : (left == 1 ? 0x0000ffffu : 0u);
-        const uint32_t m23 = left >= 4 ? 0xffffffffu : (left == 3 ? 0x0000ffffu : 0u);
-#pragma unroll
-        for (int jt = 0; jt < TL::NV; ++jt) {
-            const s16x4 av = v_operand<D, DT>(r, jt, m01, m23);
-            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, phv, st.acc[jt], 0, 0, 0);
-            st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(av, plv, st.acc[jt], 0, 0, 0);
-        }
+    for (int jt = 0; jt < TL::NV; ++jt) {
+        // A operand: V^T, row = output element 16jt + (lane & 15), k = the same eight tokens
+        const u32x2 va = v_half<D, DT>(r.a, jt), vb = v_half<D, DT>(r.b, jt);
+        u32x4 vv = tail ? mk4(va.x & ma01, va.y & ma23, vb.x & mb01, vb.y & mb23) : mk4(va.x, va.y, vb.x, vb.y);
+        const bf16x8 av = *reinterpret_cast<bf16x8 *>(&vv);
+        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phv, st.acc[jt], 0, 0, 0);
+        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
     }
 }
 
 // Floats per split-K partial: g rows of D accumulators, then g maxima, then g sums.
 __host__ __device__ inline int partial_floats(int g, int D) { return g * (D + 2); }
 
-#ifndef PKV_RING
-#define PKV_RING 3
+#ifndef PKV_FLIGHT_KIB
+#define PKV_FLIGHT_KIB 16
 #endif
 #ifndef PKV_WAVES
 #define PKV_WAVES 2
 #endif
-constexpr int RING = PKV_RING;   // pages resident per wave: one in use, the rest in flight
+// Page pairs resident per wave: one in use, the rest in flight.  The memory system
+// serves waves roughly in proportion to the bytes they have outstanding, so every
+// shape keeps the same number of bytes in flight (PKV_FLIGHT_KIB), small pages through
+// a deeper ring; otherwise waves of a small-page model would fall behind the others in
+// a grouped launch.
+template <int D, int DT>
+struct Ring {
+    static constexpr int PAIR_BYTES = 4 * Tile<D, DT>::TILE_BYTES;        // K and V tiles of two pages
+    static constexpr int N = 1 + (PKV_FLIGHT_KIB * 1024 + PAIR_BYTES - 1) / PAIR_BYTES;
+};
 constexpr int MAX_PIECES = 64;   // pieces of one (sequence, kv head) the merge stages in LDS
 
 // Pages the work split plans for a sequence: its context rounded up to pages, never
@@ -395,9 +465,10 @@ __device__ __forceinline__ void merge_segment(const AttnDesc &d, const Pending &
 // the split follows the real context lengths and needs no host-side plan.
 //
 // Inside a share the pages of consecutive pieces form ONE stream through the register
-// ring: work proceeds in turns of RING pages, every piece is padded to whole turns
-// with dead pages (no traffic, no math), and during the last turn of a piece the loads
-// already fetch the first pages of the next piece.
+// ring: pages travel and are processed in pairs (32 tokens), work proceeds in turns of
+// RING pairs, every piece is padded to whole turns with dead pages (no traffic, no
+// math), and during the last turn of a piece the loads already fetch the first pairs of
+// the next piece.
 #if defined(PKV_TRACE)
 #define PKV_STAMP(slot) do { if (threadIdx.x == 0 && d.trace) d.trace[(size_t)(blockIdx.x) * 8 + (slot)] = wall_clock64(); } while (0)
 #else
@@ -521,13 +592,18 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
     pend_a.valid = pend_b.valid = 0;
     pend_a.arrived = pend_b.arrived = 0;
 
-    // prologue of the stream: the first pages of the first piece, and its q
-    PageRegs<D, DT> ring[RING];
+    // prologue of the stream: the first page pairs of the first piece, and its q
+    constexpr int RING = Ring<D, DT>::N;
+    PairRegs<D, DT> ring[RING];
+    PairIds pre;                            // block ids of the next pair to be requested
     {
         const int32_t *row = d.table + (size_t)cur.seq * d.row_stride;
         const int live_n = cur.n_pages > 0 ? cur.pe - cur.pb : 0;
 #pragma unroll
-        for (int r = 0; r < RING - 1; ++r) load_page<D, DT>(ring[r], d, row, cur.pb + r, r < live_n, cur.kvh, lane, bad);
+        for (int r = 0; r < RING - 1; ++r)
+            load_pair<D, DT>(ring[r], d, fetch_ids(d, row, cur.pb + 2 * r), 2 * r < live_n, 2 * r + 1 < live_n,
+                             cur.kvh, lane, bad);
+        pre = fetch_ids(d, row, cur.pb + 2 * (RING - 1));
     }
     bf16x8 qf[TL::NK], qn[TL::NK];
     load_q<D>(qf, d, cur.seq, cur.kvh, lane);
@@ -535,6 +611,9 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
     State<D, DT> st;
     PKV_STAMP(2);
     int trace_first = 1;
+#if defined(PKV_TRACE)
+    uint64_t trace_issue = 0, trace_proc = 0, trace_steps = 0, trace_ids = 0;
+#endif
     while (cur.valid) {
         const Piece nxt = piece_next(cur, d, gbeg, gend);
         // q of the next piece travels while this piece streams (of this piece again if there is no next)
@@ -548,30 +627,59 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
         const int32_t *row_n = d.table + (size_t)(nxt.valid ? nxt.seq : cur.seq) * d.row_stride;
         const int n_live = cur.n_pages > 0 ? cur.pe - cur.pb : 0;       // pages to read and process
         const int n_next = (nxt.valid && nxt.n_pages > 0) ? nxt.pe - nxt.pb : 0;
-        const int n_turn = n_live > 0 ? n_live : 1;                     // an empty segment still takes a turn
+        const int n_pairs = n_live > 0 ? (n_live + 1) >> 1 : 1;         // an empty segment still takes a turn
         const int last_valid = cur.L - (cur.n_pages - 1) * T;
-        for (int t0 = 0; t0 < n_turn; t0 += RING) {
-            const bool last_turn = t0 + RING >= n_turn;
+        for (int t0 = 0; t0 < n_pairs; t0 += RING) {
+            const bool last_turn = t0 + RING >= n_pairs;
 #pragma unroll
             for (int r = 0; r < RING; ++r) {
-                // fetch: position RING-1 of this turn (r == 0), else position r-1 of the next
+#if defined(PKV_TRACE)
+                const uint64_t tr0 = __builtin_readcyclecounter();
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                const uint64_t trA = __builtin_readcyclecounter();
+                trace_ids += trA - tr0;
+#endif
+                // request: position RING-1 of this turn (r == 0), else position r-1 of the next
                 // turn, which belongs to the next piece when this is the piece's last turn
-                if (r == 0) {
-                    const int i = t0 + RING - 1;
-                    load_page<D, DT>(ring[RING - 1], d, row_c, cur.pb + i, i < n_live, cur.kvh, lane, bad);
-                } else {
-                    const int j = r - 1;
-                    const int32_t *row = last_turn ? row_n : row_c;
-                    const int page = last_turn ? nxt.pb + j : cur.pb + t0 + RING + j;
-                    const bool live = last_turn ? j < n_next : t0 + RING + j < n_live;
-                    const int kvh = last_turn ? nxt.kvh : cur.kvh;
-                    load_page<D, DT>(ring[j], d, row, page, live, kvh, lane, bad);
+                {
+                    const bool of_next = r > 0 && last_turn;
+                    const int i = r == 0 ? 2 * (t0 + RING - 1) : (last_turn ? 2 * (r - 1) : 2 * (t0 + RING + r - 1));
+                    const int lim = of_next ? n_next : n_live;
+                    load_pair<D, DT>(ring[(r + RING - 1) % RING], d, pre, i < lim, i + 1 < lim,
+                                     of_next ? nxt.kvh : cur.kvh, lane, bad);
                 }
-                const int i = t0 + r;
-                if (i < n_live)
-                    process_page<D, DT>(st, ring[r], qf, d.scale_log2, cur.pb + i == cur.n_pages - 1 ? last_valid : T, G);
+                // ids of the request after this one: the next step of this turn, or the first
+                // step of the turn that follows (this piece's next turn, else the next piece's first)
+                {
+                    const int32_t *row;
+                    int page;
+                    if (r + 1 < RING) {
+                        row = last_turn ? row_n : row_c;
+                        page = last_turn ? nxt.pb + 2 * r : cur.pb + 2 * (t0 + RING + r);
+                    } else {
+                        row = last_turn ? row_n : row_c;
+                        page = last_turn ? nxt.pb + 2 * (RING - 1) : cur.pb + 2 * (t0 + 2 * RING - 1);
+                    }
+                    pre = fetch_ids(d, row, page);
+                }
+#if defined(PKV_TRACE)
+                const uint64_t tr1 = __builtin_readcyclecounter();
+#endif
+                const int i = 2 * (t0 + r);
+                if (i < n_live) {
+                    const int pa = cur.pb + i;                                  // absolute page of the pair's first half
+                    const int va = pa == cur.n_pages - 1 ? last_valid : T;
+                    const int vb = i + 1 < n_live ? (pa + 1 == cur.n_pages - 1 ? last_valid : T) : 0;
+                    process_pair<D, DT>(st, ring[r], qf, d.scale_log2, va, vb, G);
+                }
 #if defined(PKV_TRACE)
                 if (trace_first) { trace_first = 0; PKV_STAMP(3); }
+                {
+                    const uint64_t tr2 = __builtin_readcyclecounter();
+                    trace_issue += tr1 - tr0;
+                    trace_proc += tr2 - tr1;
+                    trace_steps += 1;
+                }
 #endif
             }
         }
@@ -633,6 +741,13 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
     // --- merges this wave owes: it arrived last at a segment shared with other waves
     (void)trace_first;
     PKV_STAMP(4);
+#if defined(PKV_TRACE)
+    if (threadIdx.x == 0 && d.trace) {
+        d.trace[(size_t)blockIdx.x * 8 + 7] = trace_steps | (trace_issue << 16);
+        d.trace[(size_t)blockIdx.x * 8 + 5] = trace_proc;
+        d.trace[(size_t)blockIdx.x * 8 + 3] = trace_ids;
+    }
+#endif
     asm volatile("" ::: "memory");
     if (pend_a.valid) {
         const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)pend_a.arrived);
@@ -649,20 +764,17 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
         }
     }
     if (bad && lane == 0) atomicOr(d.err, 1u);
+#if !defined(PKV_TRACE)
     PKV_STAMP(5);
-}
-
-__device__ __forceinline__ int find_model(const AttnGroup &grp, int item) {
-    int mi = 0;
-    for (int i = 1; i < grp.n; ++i)
-        if (item >= grp.m[i].item_begin) mi = i;
-    return mi;
+#endif
 }
 
 __global__ __launch_bounds__(64, PKV_WAVES) void k_attention(const AttnGroup grp) {
     __shared__ float s_m[MAX_PIECES * 16], s_l[MAX_PIECES * 16];
     const int gi = blockIdx.x;
-    const int mi = find_model(grp, gi);
+    int mi = 0;
+    for (int i = 1; i < grp.n; ++i)
+        if (gi >= grp.m[i].item_begin) mi = i;
     const AttnDesc &d = grp.m[mi];
     const int item = gi - d.item_begin;
     if (d.dtype == PKV_BF16) {
@@ -697,9 +809,13 @@ __global__ __launch_bounds__(256) void k_stream_read(const u32x4 *src, size_t n1
         for (size_t w = blockIdx.x * (size_t)(blockDim.x / 64) + (threadIdx.x >> 6); w < n_gran; w += waves) {
             const size_t gidx = (w * 0x9E3779B1ull + 12345ull) & (n_gran - 1);   // odd multiplier: a permutation
             const u32x4 *g = src + gidx * granule16 + lane;
-            for (uint32_t k = 0; k < granule16; k += 8 * 64) {
+            if (granule16 >= 8 * 64) {
+                for (uint32_t k = 0; k < granule16; k += 8 * 64) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) acc ^= __builtin_nontemporal_load(g + k + u * 64);
+                    for (int u = 0; u < 8; ++u) acc ^= __builtin_nontemporal_load(g + k + u * 64);
+                }
+            } else {
+                for (uint32_t k = 0; k < granule16; k += 64) acc ^= __builtin_nontemporal_load(g + k);
             }
         }
     }
