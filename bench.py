@@ -40,6 +40,18 @@ def parse_args():
     return ap.parse_args()
 
 
+def profiled_traffic(workload, size):
+    """HBM bytes per k_attention launch from the committed rocprofv3 counter summary of this
+    workload (FETCH_SIZE and WRITE_SIZE runs, scaled by kernels of known size); counters cannot
+    be read from inside a timed run, so the figure is the stored one or None."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"k_attention_{workload}.md")
+    if size != "full" or not os.path.exists(path):
+        return None
+    m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read())
+    return int(m.group(1)) if m else None
+
+
 def build_replicas(gpu, cfg_id, size, n):
     import copy
     from workloads.scenarios import Runner, make_config
@@ -200,7 +212,8 @@ def main():
         "device_ms_per_step": round(dev_ms / args.steps, 5),
         "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None, "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": n_rec},
+                     "traffic": profiled_traffic(reps[0].cfg.name, args.size),
+                     "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": n_rec},
     }
     result["read_ceiling_gbps"] = {"stream": round(gpu.stream_read_probe(4 << 30, 0, 10), 1),
                                    "scattered_8KiB": round(gpu.stream_read_probe(4 << 30, 8 << 10, 10), 1),

@@ -18,11 +18,13 @@
 //     shuffles between load and matrix op;
 //   * the g query heads that share a kv head are padded to the 16 columns of one
 //     MFMA tile: S[token][head] = K . q^T is a 16x16x32 bf16 MFMA per 32 elements of
-//     head_dim, and out^T[d][head] += V^T . P is a 16x16x16 bf16 MFMA per 16 elements
-//     of head_dim, with P split into bf16 high and low parts (two MFMAs) so that the
-//     probabilities keep 16 significant bits; accumulation is fp32 throughout;
-//   * the softmax runs on the MFMA accumulator layout (lane = 4 tokens x 1 head):
-//     in-lane max / sum plus two cross-lane steps per page.
+//     head_dim; pages are taken two at a time, so out^T[d][head] += V^T . P contracts
+//     over 32 tokens (4 + 4 per lane, one half from each page) in one 16x16x32 bf16
+//     MFMA per 16 elements of head_dim, with P split into bf16 high and low parts (two
+//     MFMAs) so that the probabilities keep 16 significant bits; accumulation is fp32;
+//   * the softmax runs on the MFMA accumulator layout (lane = 4 tokens x 1 head, per
+//     page): in-lane max / sum, then lane-permute swaps across the four lane rows,
+//     once per page pair; no LDS in the streaming loop.
 //
 // In-block layout (per kv head: K tile then V tile, T = 16 tokens):
 //   bf16 K: 16-byte unit (c, t)      = K[t][8c .. 8c+7]                 at ((c*16)+t)*16
