@@ -35,6 +35,8 @@ def parse_args():
     ap.add_argument("--min-share", type=int, default=0, help="smallest share of pages per wave (0 = automatic)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     ap.add_argument("--no-balloon", action="store_true")
+    ap.add_argument("--seg-cost", type=int, default=-1, help="allowance per segment in the work split, pages (-1 = default)")
+    ap.add_argument("--tune", type=int, default=48, help="untimed launches that tune the per-XCD share weights before the warm-up (0 = equal weights)")
     ap.add_argument("--page-cost", type=int, default=-1, help="fixed cost of a page in the wave-sharing model, per mille (-1 = default)")
     ap.add_argument("--sweep-items", default="", help="comma list of work-item counts to time before the main run (stderr)")
     return ap.parse_args()
@@ -140,6 +142,7 @@ def main():
     gpu.set_split(args.items, args.min_share)
     if args.page_cost >= 0:
         gpu.set_page_cost(args.page_cost)
+    gpu.set_segment_cost(args.seg_cost)
     reps = build_replicas(gpu, args.config, args.size, args.replicas)
     inputs = [device_inputs(torch, rep, 0) for rep in reps]
     kv_per_rep = [rep.kv_bytes_step() for rep in reps]
@@ -166,6 +169,11 @@ def main():
               file=sys.stderr, flush=True)
     gpu.set_split(args.items, args.min_share)
 
+    if args.tune > 0:             # part of the set-up, like any autotuning: never inside the timed region
+        gpu.tune_xcd(args.tune)
+        for i in range(args.tune):
+            step(i)
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -206,7 +214,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": reps[0].cfg.name, "cfg": args.config, "size": args.size,
                    "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
-                   "work_items": args.items or "auto"},
+                   "work_items": args.items or "auto", "xcd_tune_launches": args.tune,
+                   "xcd_weights": [round(x, 3) for x in gpu.get_xcd_weights()]},
         "step_us": round(ms_per_step * 1e3, 2),
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "device_ms_per_step": round(dev_ms / args.steps, 5),

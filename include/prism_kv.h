@@ -193,9 +193,26 @@ int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double 
  * per launch, `min_share` = smallest number of pages a wave may be given; 0 selects
  * the automatic value of either. */
 int pkv_set_split(int items, int min_share);
+/* What a (sequence, kv head) segment is taken to cost besides its pages when the pages
+ * are cut into shares, in pages (0..256; -1 = the default).  A wave whose share holds
+ * many short sequences then gets fewer pages than one inside a long sequence. */
+int pkv_set_segment_cost(int pages);
 /* Cost model that shares the waves out among the models of a grouped launch: a page
  * costs per_mille/1000 + 0.1 per KiB of its K and V tile (default 800). */
 int pkv_set_page_cost(int per_mille);
+/* The eight XCDs of the chip do not get the same memory bandwidth, and work-groups are
+ * dealt to them in turn; so each block of eight consecutive attention work items is
+ * cut in proportion to eight weights rather than evenly.  pkv_set_xcd_weights sets
+ * them (w: 8 positive floats, host memory, copied; NULL = all equal; they are scaled to
+ * mean 1 and clamped to [0.75, 1.25]); pkv_get_xcd_weights copies the current ones to
+ * w[8].  pkv_tune_xcd(n) makes the next n attention launches measure when each XCD's
+ * waves finish and move the weights toward equal finishing times; those launches
+ * compute their results as usual but wait for the stream before they return.  Weights
+ * change where the split-K boundaries fall, hence the rounding of the results (by
+ * about 1e-6 relative), not what is computed.  PKV_E_ARG on a bad argument. */
+int pkv_set_xcd_weights(const float *w);
+int pkv_get_xcd_weights(float *w);
+int pkv_tune_xcd(int launches);
 /* Host-side check of the multiply-shift division the kernels use to split a block
  * id into (frame, slot): returns n / d computed that way. */
 uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d);

@@ -35,6 +35,10 @@ def _load():
         "pkv_set_split": (i, [i, i]),
         "pkv_set_page_cost": (i, [i]),
         "pkv_debug_fastdiv": (u32, [u32, u32]),
+        "pkv_set_xcd_weights": (i, [C.POINTER(C.c_float)]),
+        "pkv_get_xcd_weights": (i, [C.POINTER(C.c_float)]),
+        "pkv_tune_xcd": (i, [i]),
+        "pkv_set_segment_cost": (i, [i]),
         "pkv_stream_read_probe": (i, [sz, sz, i, C.POINTER(C.c_double)]),
         "pkv_timing_enable": (i, [i]),
         "pkv_timing_read": (l, [C.POINTER(C.c_double)]),
@@ -66,6 +70,7 @@ def _load():
 
 
 EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_set_page_cost", "pkv_debug_fastdiv",
+           "pkv_set_xcd_weights", "pkv_get_xcd_weights", "pkv_tune_xcd", "pkv_set_segment_cost",
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
@@ -102,6 +107,25 @@ class PrismKV:
 
     def set_page_cost(self, per_mille=800):
         return self.lib.pkv_set_page_cost(per_mille)
+
+    def set_xcd_weights(self, w=None):
+        if w is None:
+            return self.lib.pkv_set_xcd_weights(None)
+        arr = (C.c_float * 8)(*[float(x) for x in w])
+        return self.lib.pkv_set_xcd_weights(arr)
+
+    def get_xcd_weights(self):
+        arr = (C.c_float * 8)()
+        rc = self.lib.pkv_get_xcd_weights(arr)
+        if rc:
+            raise RuntimeError(f"pkv_get_xcd_weights: {rc}")
+        return [float(x) for x in arr]
+
+    def tune_xcd(self, launches):
+        return self.lib.pkv_tune_xcd(int(launches))
+
+    def set_segment_cost(self, pages=-1):
+        return self.lib.pkv_set_segment_cost(int(pages))
 
     def set_split(self, items=0, min_share=0):
         return self.lib.pkv_set_split(items, min_share)

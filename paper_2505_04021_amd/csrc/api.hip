@@ -78,7 +78,13 @@ BookResult *g_res = nullptr;       // pinned host
 int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
 uint32_t *g_err = nullptr;         // device error flags
 uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
-int g_items = 0, g_min_share = 0;
+int g_items = 0, g_min_share = 0, g_seg_cost = -1;
+// How a block of eight shares is cut among the XCDs: weights (mean 1), and the state of a
+// tuning run that derives them from when each XCD's waves finish.
+float g_xcd_w[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+uint64_t *g_xcd_stat = nullptr;       // device: [8][2]
+int g_tune_left = 0, g_tune_done = 0;
+constexpr float kXcdWeightMin = 0.75f, kXcdWeightMax = 1.25f;
 double g_page_cost = 0.8;            // fixed cost of a page relative to 0.1 per KiB   // measurement knobs (0 = automatic)
 int g_timing = 0;                 // 0 = off, n = bracket every n-th attention launch with events
 long g_launches = 0;
@@ -139,6 +145,7 @@ void free_model_dev(Model &m) {
 // Each model of a grouped launch gets items in proportion to the KV bytes it will read.
 constexpr int kDefaultItems = 2048;
 constexpr int kDefaultMinShare = 4;
+constexpr int kDefaultSegCost = 6;
 
 // Expected cost of a model's pages, used to share the waves out among the models of a
 // grouped launch.  A wave spends a fixed time per page (the load - MFMA - softmax - MFMA
@@ -172,11 +179,15 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.item_begin = 0;
     d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m.D));
     d.min_share = g_min_share > 0 ? g_min_share : kDefaultMinShare;
+    d.seg_cost = g_seg_cost >= 0 ? g_seg_cost : kDefaultSegCost;
     // no more items than there can be shares of min_share pages (an empty row counts as one page)
-    const double units = ((own ? (double)m.used_blocks : (double)batch * d.row_stride) + batch) * m.Hkv;
+    const double units = ((own ? (double)m.used_blocks : (double)batch * d.row_stride) +
+                          (double)batch * (d.seg_cost + 1)) * m.Hkv;
     double items = (g_items > 0 ? g_items : kDefaultItems) * share_of_launch;
     if (items > units / d.min_share) items = units / d.min_share;
     d.n_items = items < 1.0 ? 1 : (int)items;                // never more than the slots in total
+    if (d.n_items >= 8) d.n_items &= ~7;                     // whole blocks of eight: one item per XCD
+    d.weighted = d.n_items % 8 == 0 ? 1 : 0;
     const size_t need = (size_t)2 * d.n_items * m.g * (m.D + 2);
     if (need > m.ws_floats) {
         HIP_TRY(hipStreamSynchronize(g_stream));
@@ -256,6 +267,91 @@ int pkv_device_errors(void) {
     return (int)v;
 }
 
+/* ------------------------------------------------------------ XCD weights */
+
+void normalise_xcd_weights(float *w) {
+    for (int pass = 0; pass < 4; ++pass) {          // mean 1 inside the clamp
+        double sum = 0.0;
+        for (int i = 0; i < 8; ++i) sum += w[i];
+        for (int i = 0; i < 8; ++i) {
+            w[i] = (float)(w[i] * 8.0 / sum);
+            w[i] = w[i] < kXcdWeightMin ? kXcdWeightMin : (w[i] > kXcdWeightMax ? kXcdWeightMax : w[i]);
+        }
+    }
+}
+
+void fill_tune(AttnTune &t, bool record) {
+    double sum = 0.0, acc = 0.0;
+    for (int i = 0; i < 8; ++i) sum += g_xcd_w[i];
+    t.cum[0] = 0;
+    for (int i = 0; i < 8; ++i) {
+        acc += g_xcd_w[i];
+        t.cum[i + 1] = (uint32_t)(65536.0 * acc / sum + 0.5);
+    }
+    t.cum[8] = 65536;
+    t.stat = record ? g_xcd_stat : nullptr;
+}
+
+// One attention launch; during a tuning run it also records when each XCD's waves finish
+// and moves the weights toward equal finishing times (synchronises in that case).
+int launch_attention(AttnGroup &grp) {
+    const bool tune = g_tune_left > 0;
+    if (tune) {
+        if (!g_xcd_stat) HIP_TRY(hipMalloc((void **)&g_xcd_stat, 16 * sizeof(uint64_t)));
+        HIP_TRY(hipMemsetAsync(g_xcd_stat, 0, 16 * sizeof(uint64_t), g_stream));
+    }
+    fill_tune(grp.tune, tune);
+    HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
+    if (tune) {
+        uint64_t st[16];
+        HIP_TRY(hipStreamSynchronize(g_stream));
+        HIP_TRY(hipMemcpy(st, g_xcd_stat, sizeof st, hipMemcpyDeviceToHost));
+        --g_tune_left;
+        double t[8], mean = 0.0;
+        bool ok = true;
+        for (int i = 0; i < 8; ++i) {
+            if (st[2 * i + 1] < 8) { ok = false; break; }      // too few waves on this XCD to judge
+            t[i] = (double)st[2 * i] / (double)st[2 * i + 1];
+            mean += t[i] / 8.0;
+        }
+        if (ok && mean > 0.0) {
+            // a wave's time is its share over its XCD's rate: move each weight part of the way
+            // to where the times would be equal, and let the next launches correct the rest
+            const double gain = g_tune_done < 8 ? 0.5 : 0.2;      // coarse first, then averaging out the noise
+            for (int i = 0; i < 8; ++i) g_xcd_w[i] = (float)(g_xcd_w[i] * pow(mean / t[i], gain));
+            ++g_tune_done;
+            normalise_xcd_weights(g_xcd_w);
+        }
+    }
+    return PKV_OK;
+}
+
+int pkv_set_xcd_weights(const float *w) {
+    float v[8];
+    for (int i = 0; i < 8; ++i) {
+        v[i] = w ? w[i] : 1.f;
+        if (!(v[i] > 0.f) || !(v[i] < 1e6f)) return PKV_E_ARG;
+    }
+    normalise_xcd_weights(v);
+    for (int i = 0; i < 8; ++i) g_xcd_w[i] = v[i];
+    return PKV_OK;
+}
+
+int pkv_get_xcd_weights(float *w) {
+    if (!w) return PKV_E_ARG;
+    for (int i = 0; i < 8; ++i) w[i] = g_xcd_w[i];
+    return PKV_OK;
+}
+
+int pkv_tune_xcd(int launches) {
+    if (launches < 0 || launches > 100000) return PKV_E_ARG;
+    int rc = lib_init();
+    if (rc) return rc;
+    g_tune_left = launches;
+    g_tune_done = 0;
+    return PKV_OK;
+}
+
 int pkv_set_page_cost(int per_mille) {
     if (per_mille < 0 || per_mille > 100000) return PKV_E_ARG;
     g_page_cost = per_mille / 1000.0;
@@ -266,6 +362,12 @@ int pkv_set_split(int items, int min_share) {
     if (items < 0 || items > (1 << 20) || min_share < 0 || min_share > 4096) return PKV_E_ARG;
     g_items = items;
     g_min_share = min_share;
+    return PKV_OK;
+}
+
+int pkv_set_segment_cost(int pages) {
+    if (pages < -1 || pages > 256) return PKV_E_ARG;
+    g_seg_cost = pages;
     return PKV_OK;
 }
 
@@ -579,8 +681,7 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
     if (rc) return rc;
 
-    HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
-    return PKV_OK;
+    return launch_attention(grp);
 }
 
 int decode_attention(int model, const void *q, const int32_t *block_table, const int32_t *ctx_lens, float *out) {
@@ -620,12 +721,12 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
         int rc = fill_desc(d, *m, batches[i], q[i], nullptr, 0, ctx_lens[i], out[i], frac);
         if (rc) return rc;
         d.item_begin = items;
+        if (items % 8 != 0) d.weighted = 0;          // its items would not line up with the XCDs
         items += d.n_items;
         grp.n++;
     }
     if (grp.n == 0) return PKV_OK;
-    HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
-    return PKV_OK;
+    return launch_attention(grp);
 }
 
 /* ------------------------------------------------------------ observation */

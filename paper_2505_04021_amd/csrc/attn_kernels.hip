@@ -297,6 +297,9 @@ __host__ __device__ inline int partial_floats(int g, int D) { return g * (D + 2)
 #ifndef PKV_FLIGHT_KIB
 #define PKV_FLIGHT_KIB 16
 #endif
+#ifndef PKV_PRIO
+#define PKV_PRIO 1
+#endif
 #ifndef PKV_WAVES
 #define PKV_WAVES 2
 #endif
@@ -321,6 +324,15 @@ __device__ __forceinline__ int ctx_clamped(const AttnDesc &d, int seq) {
     return L < 0 ? 0 : (L > cap ? cap : L);
 }
 
+// Length a segment is given on the line the shares are cut from: its pages plus a fixed
+// allowance for what every segment costs besides its pages (the turn it does not fill,
+// the gap in the stream at its boundary, writing its result), at least 1 so that an
+// empty sequence still has an owner who writes its zero row.
+__device__ __forceinline__ int planned(const AttnDesc &d, int n_pages) {
+    const int pl = n_pages + d.seg_cost;
+    return pl > 0 ? pl : 1;
+}
+
 // A piece: the pages [pb, pe) of one (sequence, kv head) segment that fall into this
 // wave's share.  All fields are wave-uniform.
 struct Piece {
@@ -337,7 +349,7 @@ __device__ __forceinline__ void piece_set_seq(Piece &pc, const AttnDesc &d, int 
     pc.P = P;
     pc.L = seq < d.batch ? __builtin_amdgcn_readfirstlane(ctx_clamped(d, seq < d.batch ? seq : 0)) : 0;
     pc.n_pages = (pc.L + T - 1) / T;
-    pc.pl = pc.n_pages > 0 ? pc.n_pages : 1;
+    pc.pl = planned(d, pc.n_pages);
 }
 
 // clip segment (seq, kvh) against the share [gbeg, gend)
@@ -346,6 +358,9 @@ __device__ __forceinline__ void piece_clip(Piece &pc, const AttnDesc &d, uint32_
     pc.valid = (pc.seq < d.batch && pc.g0 < gend) ? 1 : 0;
     pc.pb = gbeg > pc.g0 ? (int)(gbeg - pc.g0) : 0;
     pc.pe = gend - pc.g0 < (uint32_t)pc.pl ? (int)(gend - pc.g0) : pc.pl;
+    // the allowance past the last page holds no work; an empty sequence has the one unit [0, 1)
+    const int real = pc.n_pages > 0 ? pc.n_pages : 1;
+    pc.pe = pc.pe < real ? pc.pe : real;
 }
 
 __device__ __forceinline__ Piece piece_next(const Piece &c, const AttnDesc &d, uint32_t gbeg, uint32_t gend) {
@@ -383,26 +398,45 @@ struct Pending {
 // online-softmax merge of the pieces of one segment: M = max m_c,
 // out = sum_c 2^(m_c-M) a_c / sum_c 2^(m_c-M) l_c.  Piece c of the segment sits in
 // share k0 + c: slot b of that share for c = 0, slot a otherwise.
-// The partials come from uncached memory, so the cost is memory round trips: the
-// maxima and sums of all pieces are fetched in one trip and staged in LDS, then each
-// lane owns EPL groups of four consecutive output elements and fetches the
-// accumulators of 32 / EPL pieces per trip.
+// The partials come from uncached memory, so the cost is memory round trips: each lane
+// owns EPL groups of four consecutive output elements and fetches the accumulators of
+// 32 / EPL pieces per trip; the maxima and sums of all pieces travel with the first trip
+// and are staged in LDS.
 template <int D, int EPL>
-__device__ __forceinline__ void merge_rows(const AttnDesc &d, const Pending &pd, int lane, const float *s_m,
-                                           const float *s_l, const float *base, int n_pc) {
+__device__ __forceinline__ void merge_rows(const AttnDesc &d, const Pending &pd, int lane, float *s_m, float *s_l,
+                                           const float *base, int n_pc) {
     constexpr int D4 = D / 4;
     constexpr int PB = 32 / EPL;                      // pieces per trip
     const int g = d.g, pf = partial_floats(g, D);
     const int E = g * D4;
     int hn[EPL], x[EPL];
-    float M[EPL], den[EPL];
-    f32x4 num[EPL];
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
         const int e = lane + 64 * k;
         const int ee = e < E ? e : E - 1;             // idle lanes shadow a valid element
         hn[k] = ee / D4;
         x[k] = ee - hn[k] * D4;
+    }
+    // first trip: the accumulators of the first PB pieces travel together with all maxima and sums
+    f32x4 v[PB][EPL];
+#pragma unroll
+    for (int u = 0; u < PB; ++u) {
+        const int c = u < n_pc ? u : n_pc - 1;
+        const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf;
+#pragma unroll
+        for (int k = 0; k < EPL; ++k) v[u][k] = *reinterpret_cast<const f32x4 *>(wc + hn[k] * D + 4 * x[k]);
+    }
+    for (int i = lane; i < n_pc * g; i += 64) {
+        const int c = i / g, h = i - c * g;
+        const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf + g * D;
+        s_m[i] = wc[h];
+        s_l[i] = wc[g + h];
+    }
+    __builtin_amdgcn_wave_barrier();     // one wave per work-group: program order is enough
+    float M[EPL], den[EPL];
+    f32x4 num[EPL];
+#pragma unroll
+    for (int k = 0; k < EPL; ++k) {
         float mm = -INFINITY;
         for (int c = 0; c < n_pc; ++c) mm = fmaxf(mm, s_m[c * g + hn[k]]);
         M[k] = mm;
@@ -410,13 +444,14 @@ __device__ __forceinline__ void merge_rows(const AttnDesc &d, const Pending &pd,
         num[k] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
     for (int c0 = 0; c0 < n_pc; c0 += PB) {
-        f32x4 v[PB][EPL];
+        if (c0 > 0) {
 #pragma unroll
-        for (int u = 0; u < PB; ++u) {
-            const int c = c0 + u < n_pc ? c0 + u : n_pc - 1;
-            const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf;
+            for (int u = 0; u < PB; ++u) {
+                const int c = c0 + u < n_pc ? c0 + u : n_pc - 1;
+                const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf;
 #pragma unroll
-            for (int k = 0; k < EPL; ++k) v[u][k] = *reinterpret_cast<const f32x4 *>(wc + hn[k] * D + 4 * x[k]);
+                for (int k = 0; k < EPL; ++k) v[u][k] = *reinterpret_cast<const f32x4 *>(wc + hn[k] * D + 4 * x[k]);
+            }
         }
 #pragma unroll
         for (int u = 0; u < PB; ++u) {
@@ -435,6 +470,7 @@ __device__ __forceinline__ void merge_rows(const AttnDesc &d, const Pending &pd,
         if (lane + 64 * k < E)
             *reinterpret_cast<f32x4 *>(d.out + ((size_t)pd.seq * d.Hq + pd.kvh * g + hn[k]) * D + 4 * x[k]) =
                 num[k] * (1.0f / den[k]);
+    __builtin_amdgcn_wave_barrier();
 }
 
 template <int D>
@@ -442,19 +478,11 @@ __device__ __forceinline__ void merge_segment(const AttnDesc &d, const Pending &
     const int g = d.g, pf = partial_floats(g, D);
     const int n_pc = (int)(pd.k1 - pd.k0) + 1;
     const float *base = d.ws + (size_t)(2 * pd.k0) * pf;
-    for (int i = lane; i < n_pc * g; i += 64) {
-        const int c = i / g, hn = i - c * g;
-        const float *wc = base + (size_t)(2 * c + (c == 0 ? 1 : 0)) * pf + g * D;
-        s_m[i] = wc[hn];
-        s_l[i] = wc[g + hn];
-    }
-    __builtin_amdgcn_wave_barrier();     // one wave per work-group: program order is enough
     const int groups = (g * (D / 4) + 63) / 64;       // element groups per lane
     if (groups <= 1) merge_rows<D, 1>(d, pd, lane, s_m, s_l, base, n_pc);
     else if (groups <= 2) merge_rows<D, 2>(d, pd, lane, s_m, s_l, base, n_pc);
     else if (groups <= 4) merge_rows<D, 4>(d, pd, lane, s_m, s_l, base, n_pc);
     else merge_rows<D, 8>(d, pd, lane, s_m, s_l, base, n_pc);
-    __builtin_amdgcn_wave_barrier();
 }
 
 // Work split ("stream-K" over pages): the (sequence, kv head) segments of a model are
@@ -471,24 +499,53 @@ __device__ __forceinline__ void merge_segment(const AttnDesc &d, const Pending &
 // RING pairs, every piece is padded to whole turns with dead pages (no traffic, no
 // math), and during the last turn of a piece the loads already fetch the first pairs of
 // the next piece.
+// Where the shares of the work items begin on the line of page units.  Items come in
+// blocks of eight (one per XCD); a block spans 8 * share units and is cut at
+// cum[j] / 65536 of its length (cum[0] = 0, cum[8] = 65536), or evenly without weights.
+constexpr uint32_t WEIGHTED_SHARE_MIN = 16;     // below this, uneven cuts could leave a share empty
+struct Cut {
+    uint32_t share;
+    const uint32_t *cum;        // kernel-argument memory, or NULL for even cuts
+
+    __device__ __forceinline__ uint32_t begin(uint32_t item) const {
+        if (!cum) return item * share;
+        const uint32_t blk = item >> 3, j = item & 7u;
+        return blk * 8u * share + (uint32_t)(((uint64_t)(8u * share) * PKV_CONST(uint32_t, cum)[j]) >> 16);
+    }
+    // the item whose share holds line position x
+    __device__ __forceinline__ uint32_t index(uint32_t x) const {
+        if (!cum) return x / share;
+        const uint32_t s8 = 8u * share, blk = x / s8, rem = x - blk * s8;
+        uint32_t j = 0;
+#pragma unroll
+        for (uint32_t t = 1; t < 8; ++t)
+            j += rem >= (uint32_t)(((uint64_t)s8 * PKV_CONST(uint32_t, cum)[t]) >> 16) ? 1u : 0u;
+        return blk * 8u + j;
+    }
+};
+
 #if defined(PKV_TRACE)
-#define PKV_STAMP(slot) do { if (threadIdx.x == 0 && d.trace) d.trace[(size_t)(blockIdx.x) * 8 + (slot)] = wall_clock64(); } while (0)
+#define PKV_STAMP(slot) do { if (threadIdx.x == 0 && d.trace) d.trace[(size_t)(blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
 #else
 #define PKV_STAMP(slot) do { } while (0)
 #endif
 
 template <int D, int DT>
-__device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_m, float *s_l) {
+__device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, int item, float *s_m, float *s_l) {
     using TL = Tile<D, DT>;
     const int lane = threadIdx.x;
+#if PKV_PRIO
+    __builtin_amdgcn_s_setprio(3);      // from the first instruction: a wave still setting up must not wait behind streaming ones
+#endif
     PKV_STAMP(0);
 #if defined(PKV_TRACE)
     if (threadIdx.x == 0 && d.trace)      // where the wave runs: HW_ID in the low word, XCC_ID above
-        d.trace[(size_t)blockIdx.x * 8 + 6] = (uint64_t)__builtin_amdgcn_s_getreg(63492) |
+        d.trace[(size_t)blockIdx.x * 16 + 6] = (uint64_t)__builtin_amdgcn_s_getreg(63492) |
                                               ((uint64_t)__builtin_amdgcn_s_getreg(63508) << 32);
 #endif
     const int G = lane >> 4, n = lane & 15;
     const int g = d.g, Hkv = d.Hkv, B = d.batch;
+    const uint64_t t_begin = w.stat ? wall_clock64() : 0;
 
     // --- planned pages per sequence, prefix sums across the wave.  Batches of up to
     // 64 * LINE_REGS sequences keep every context length in registers, so that finding
@@ -507,7 +564,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
         for (int k = 0; k < LINE_REGS; ++k) {
             if (Lc[k] >= 0) {
                 const int np = (Lc[k] + T - 1) / T;
-                const int pl = np > 0 ? np : 1;
+                const int pl = planned(d, np);
                 my_sum += pl;
                 my_max = pl > my_max ? pl : my_max;
             }
@@ -517,7 +574,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
             const int sq = lane * K + k;
             if (sq < B) {
                 const int np = (ctx_clamped(d, sq) + T - 1) / T;
-                const int pl = np > 0 ? np : 1;
+                const int pl = planned(d, np);
                 my_sum += pl;
                 my_max = pl > my_max ? pl : my_max;
             }
@@ -536,16 +593,20 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
     }
     const int total = __builtin_amdgcn_readlane(incl, 63);
     const uint32_t W = (uint32_t)total * (uint32_t)Hkv;
-    // equal shares, but never so small that a segment falls into more pieces than the
-    // merge can stage
+    // Shares: equal in the mean, but never so small that a segment falls into more pieces
+    // than the merge can stage.  Eight consecutive items run on the eight XCDs (work-groups
+    // are dealt to them in turn), and XCDs do not all get the same memory bandwidth; so a
+    // block of eight shares is cut at the caller's cumulative weights instead of evenly.
     uint32_t share = (W + (uint32_t)d.n_items - 1) / (uint32_t)d.n_items;
-    const uint32_t floor_share = ((uint32_t)my_max + (MAX_PIECES - 4) - 1) / (MAX_PIECES - 4);
+    const uint32_t floor_share = ((uint32_t)my_max + (MAX_PIECES - 24) - 1) / (MAX_PIECES - 24);
     share = share < floor_share ? floor_share : share;
     share = share < (uint32_t)d.min_share ? (uint32_t)d.min_share : share;
     share = (uint32_t)__builtin_amdgcn_readfirstlane((int)share);
-    const uint32_t gbeg = (uint32_t)item * share;
+    const Cut cut = Cut{share, (share >= WEIGHTED_SHARE_MIN && d.weighted) ? w.cum : nullptr};
+    const uint32_t gbeg = cut.begin((uint32_t)item);
+    uint32_t gend = cut.begin((uint32_t)item + 1);
     if (gbeg >= W) return;
-    const uint32_t gend = gbeg + share < W ? gbeg + share : W;
+    gend = gend < W ? gend : W;
     PKV_STAMP(1);
 
     // --- the first piece: the segment that contains gbeg
@@ -561,7 +622,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
             for (int k = 0; k < LINE_REGS; ++k) {
                 if (!found && Lc[k] >= 0) {
                     const int np = (Lc[k] + T - 1) / T;
-                    const int pl = np > 0 ? np : 1;
+                    const int pl = planned(d, np);
                     if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl;
                     else { fs = lane * K + k; fl = Lc[k]; found = true; }
                 }
@@ -572,7 +633,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
                 if (sq < B) {
                     const int L1 = ctx_clamped(d, sq);
                     const int np = (L1 + T - 1) / T;
-                    const int pl = np > 0 ? np : 1;
+                    const int pl = planned(d, np);
                     if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl; else { fs = sq; fl = L1; break; }
                 }
             }
@@ -581,9 +642,12 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
         cur.P = __builtin_amdgcn_readfirstlane(__shfl(fp, owner));
         cur.L = __builtin_amdgcn_readfirstlane(__shfl(fl, owner));
         cur.n_pages = (cur.L + T - 1) / T;
-        cur.pl = cur.n_pages > 0 ? cur.n_pages : 1;
+        cur.pl = planned(d, cur.n_pages);
         cur.kvh = (int)((gbeg - (uint32_t)cur.P * Hkv) / (uint32_t)cur.pl);
         piece_clip(cur, d, gbeg, gend);
+        // a share may begin in the allowance behind a segment's last page: nothing to do there
+        if (cur.pb >= cur.pe) cur = piece_next(cur, d, gbeg, gend);
+        if (!cur.valid) return;
     }
 
     uint32_t bad = 0;
@@ -612,6 +676,15 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
 
     State<D, DT> st;
     PKV_STAMP(2);
+#if PKV_PRIO
+    // Instruction issue favours the older wave of a SIMD, and at two waves per SIMD the
+    // younger one can starve for tens of microseconds before it gets its turn.  A wave
+    // therefore starts at the highest priority and steps down as its share proceeds, so
+    // whichever wave is behind is the one that is favoured.
+    const uint32_t prio_total = gend - gbeg + 1;
+    uint32_t prio_done = 0;
+    int prio_lvl = 0;
+#endif
     int trace_first = 1;
 #if defined(PKV_TRACE)
     uint64_t trace_issue = 0, trace_proc = 0, trace_steps = 0, trace_ids = 0;
@@ -640,6 +713,17 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                 const uint64_t trA = __builtin_readcyclecounter();
                 trace_ids += trA - tr0;
+#endif
+#if PKV_PRIO
+                {
+                    const int lvl = (int)(prio_done * 4u / prio_total) & 3;
+                    if (lvl != prio_lvl) {
+                        prio_lvl = lvl;
+                        if (lvl == 1) __builtin_amdgcn_s_setprio(2);
+                        else if (lvl == 2) __builtin_amdgcn_s_setprio(1);
+                        else __builtin_amdgcn_s_setprio(0);
+                    }
+                }
 #endif
                 // request: position RING-1 of this turn (r == 0), else position r-1 of the next
                 // turn, which belongs to the next piece when this is the piece's last turn
@@ -673,6 +757,9 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
                     const int va = pa == cur.n_pages - 1 ? last_valid : T;
                     const int vb = i + 1 < n_live ? (pa + 1 == cur.n_pages - 1 ? last_valid : T) : 0;
                     process_pair<D, DT>(st, ring[r], qf, d.scale_log2, va, vb, G);
+#if PKV_PRIO
+                    prio_done += 2;
+#endif
                 }
 #if defined(PKV_TRACE)
                 if (trace_first) { trace_first = 0; PKV_STAMP(3); }
@@ -698,7 +785,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
             float l = st.l;
             l += __shfl_xor(l, 16);
             l += __shfl_xor(l, 32);
-            const uint32_t k0 = cur.g0 / share, k1 = (cur.g0 + (uint32_t)cur.n_pages - 1) / share;
+            const uint32_t k0 = cut.index(cur.g0), k1 = cut.index(cur.g0 + (uint32_t)cur.n_pages - 1);
             if (k0 == k1) {                      // the whole segment was ours
                 if (n < g) {
                     const float inv = 1.0f / l;
@@ -743,11 +830,16 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
     // --- merges this wave owes: it arrived last at a segment shared with other waves
     (void)trace_first;
     PKV_STAMP(4);
+    if (w.stat && lane == 0) {          // tuning launches only: when did this XCD's waves finish streaming
+        const unsigned xcd = blockIdx.x & 7u;
+        atomicAdd(reinterpret_cast<unsigned long long *>(w.stat) + 2 * xcd, (unsigned long long)(wall_clock64() - t_begin));
+        atomicAdd(reinterpret_cast<unsigned long long *>(w.stat) + 2 * xcd + 1, 1ull);
+    }
 #if defined(PKV_TRACE)
     if (threadIdx.x == 0 && d.trace) {
-        d.trace[(size_t)blockIdx.x * 8 + 7] = trace_steps | (trace_issue << 16);
-        d.trace[(size_t)blockIdx.x * 8 + 5] = trace_proc;
-        d.trace[(size_t)blockIdx.x * 8 + 3] = trace_ids;
+        d.trace[(size_t)blockIdx.x * 16 + 7] = trace_steps | (trace_issue << 16);
+        d.trace[(size_t)blockIdx.x * 16 + 8] = trace_proc;
+        d.trace[(size_t)blockIdx.x * 16 + 9] = trace_ids;
     }
 #endif
     asm volatile("" ::: "memory");
@@ -766,9 +858,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, int item, float *s_
         }
     }
     if (bad && lane == 0) atomicOr(d.err, 1u);
-#if !defined(PKV_TRACE)
     PKV_STAMP(5);
-#endif
 }
 
 __global__ __launch_bounds__(64, PKV_WAVES) void k_attention(const AttnGroup grp) {
@@ -780,11 +870,11 @@ __global__ __launch_bounds__(64, PKV_WAVES) void k_attention(const AttnGroup grp
     const AttnDesc &d = grp.m[mi];
     const int item = gi - d.item_begin;
     if (d.dtype == PKV_BF16) {
-        if (d.D == 128) attn_wave<128, PKV_BF16>(d, item, s_m, s_l);
-        else attn_wave<64, PKV_BF16>(d, item, s_m, s_l);
+        if (d.D == 128) attn_wave<128, PKV_BF16>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_BF16>(d, grp.tune, item, s_m, s_l);
     } else {
-        if (d.D == 128) attn_wave<128, PKV_E4M3>(d, item, s_m, s_l);
-        else attn_wave<64, PKV_E4M3>(d, item, s_m, s_l);
+        if (d.D == 128) attn_wave<128, PKV_E4M3>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_E4M3>(d, grp.tune, item, s_m, s_l);
     }
 }
 

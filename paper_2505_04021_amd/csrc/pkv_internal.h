@@ -78,7 +78,7 @@ struct AttnDesc {
     float *ws;                  // split-K partials: two per work item (uncached memory)
     uint32_t *cnt;              // [B][Hkv] arrival counters of the split-K merge, zero between launches
     uint32_t *err;              // device error flags
-    uint64_t *trace;            // NULL, or [grid][8] time stamps (instrumented builds only)
+    uint64_t *trace;            // NULL, or [grid][16] time stamps and counters (instrumented builds only)
     uint64_t frame_bytes, block_bytes;
     FastDiv slots_div;
     uint32_t max_block_id;      // n_frames * slots
@@ -87,13 +87,23 @@ struct AttnDesc {
     int32_t item_begin;         // first work item of this model in a grouped launch
     int32_t n_items;            // work items (waves) of this model
     int32_t min_share;          // smallest share of pages a wave may get
+    int32_t weighted;           // items come in whole blocks of eight aligned with the XCDs
+    int32_t seg_cost;           // what a segment costs besides its pages, in pages (for the split only)
     float scale_log2;           // log2(e) / sqrt(D)
 };
 
 #define PKV_MAX_GROUP 16
 
+// How a launch cuts each block of eight consecutive shares among the eight XCDs.
+struct AttnTune {
+    uint32_t cum[9];            // cumulative weights in 1/65536: cum[0] = 0 <= ... <= cum[8] = 65536
+    uint64_t *stat;             // NULL, or [8][2]: per XCD the sum of its waves' streaming times
+                                // (100 MHz ticks) and their number; set in tuning launches only
+};
+
 struct AttnGroup {
     AttnDesc m[PKV_MAX_GROUP];
+    AttnTune tune;
     int32_t n;
 };
 

@@ -101,6 +101,7 @@ class Pair:
 
 
 EDGE_CTX = [0, 1, 15, 16, 17, 31, 32, 33, 255, 256, 257, 300]
+UNEVEN = [1.25, 0.75, 1.1, 0.9, 1.2, 0.8, 1.0, 1.0]
 
 
 @pytest.mark.parametrize("hq,hkv,d,dtype", [
@@ -113,7 +114,16 @@ def test_edge_lengths_and_shapes(gpu, oracle, hq, hkv, d, dtype):
     for items, share in ((0, 0), (100000, 1), (37, 3), (8, 5), (1, 1)):   # automatic, and forced split shapes
         assert gpu.set_split(items, share) == 0
         err = p.check()
+    # the same with an allowance per segment in the split, and with uneven cuts among the XCDs
+    for items, share, seg, w in ((0, 0, 3, None), (100000, 1, 2, None), (37, 3, 7, None), (64, 16, 0, UNEVEN),
+                                 (64, 16, 5, UNEVEN), (24, 20, 40, UNEVEN)):
+        assert gpu.set_split(items, share) == 0
+        assert gpu.set_segment_cost(seg) == 0
+        assert gpu.set_xcd_weights(w) == 0
+        err = p.check()
     gpu.set_split(0, 0)
+    gpu.set_segment_cost(-1)
+    gpu.set_xcd_weights(None)
     assert_same_state(gpu, oracle, p.pools[0], p.pools[1])
     assert np.array_equal(p.outputs()[0][0], np.zeros((hq, d), np.float32))   # ctx 0 -> zero row
     assert gpu.device_errors() == 0
@@ -242,3 +252,23 @@ def test_bookkeeping_is_deterministic(gpu, oracle):
         r.teardown()
     for a, b in zip(*imgs):
         assert np.array_equal(a, b)
+
+
+def test_xcd_weights_api_and_tuning(gpu, oracle):
+    """Weights are scaled to mean 1 and clamped; a tuning run leaves valid weights and
+    the launches inside it still compute the right result."""
+    assert gpu.set_xcd_weights([1, 1, 1, 1, 1, 1, 1, -1]) != 0
+    assert gpu.set_xcd_weights([2, 2, 2, 2, 2, 2, 2, 2]) == 0
+    assert np.allclose(gpu.get_xcd_weights(), 1.0)
+    assert gpu.set_xcd_weights([10, 1, 1, 1, 1, 1, 1, 1]) == 0
+    w = gpu.get_xcd_weights()
+    assert max(w) <= 1.25 + 1e-6 and min(w) >= 0.75 - 1e-6
+    gpu.set_xcd_weights(None)
+    p = Pair(gpu, oracle, 32, 8, 128, BF16, [700, 33, 1200, 64, 2000, 5], pool_bytes=128 << 20, max_blocks=160)
+    assert gpu.tune_xcd(6) == 0
+    for _ in range(8):
+        p.check()
+    w = gpu.get_xcd_weights()
+    assert abs(sum(w) / 8 - 1.0) < 0.05 and max(w) <= 1.25 + 1e-6 and min(w) >= 0.75 - 1e-6
+    gpu.set_xcd_weights(None)
+    p.close()
