@@ -7,8 +7,9 @@
 //
 // Mapping to the hardware
 //   * one wavefront (64 lanes) per work item; the pages of all (sequence, kv head)
-//     pairs are laid end to end and cut into equal shares, so every wave reads the
-//     same number of bytes whatever the mix of context lengths; where a share boundary
+//     pairs are laid end to end and cut into shares of equal expected time (pages plus
+//     an allowance per segment, scaled by a weight per XCD), whatever the mix of
+//     context lengths; where a share boundary
 //     cuts a sequence, the wave that finishes it last merges the pieces with the
 //     online-softmax rule inside the same kernel (partials and arrival counters sit in
 //     uncached memory: no cache flush, no second launch);
