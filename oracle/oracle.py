@@ -52,6 +52,10 @@ def _load():
         "orc_model_block_table": (C.POINTER(C.c_int32), [i, C.POINTER(i)]),
         "orc_model_row_len": (i, [i, i]),
         "orc_e4m3_decode": (C.c_double, [C.c_uint8]),
+        "orc_e4m3_encode": (C.c_uint8, [C.c_float]),
+        "orc_kv_append": (i, [i, i, vp, vp, vp]),
+        "orc_kv_read": (i, [i, i, i, i, vp, vp, vp, vp]),
+        "orc_prefill_attention": (i, [i, i, vp, vp, vp, i, vp, vp]),
         "orc_num_threads": (i, []),
         "orc_set_num_threads": (None, [i]),
     }
@@ -133,6 +137,47 @@ class Oracle:
         ks = _arr(k_scale, np.float32)
         vs = _arr(v_scale, np.float32)
         return self.lib.orc_kv_write(model, seq, tok_begin, k.shape[0], _ptr(k), _ptr(v), _ptr(ks), _ptr(vs))
+
+    def kv_append(self, model, k_new, v_new, ctx_lens):
+        """k_new, v_new: uint16 (bf16 bits) [B][Hkv][D]; writes token ctx_lens[s] - 1 of every sequence."""
+        _, hkv, d, _ = self._shape[model]
+        k_new = _arr(k_new, np.uint16)
+        v_new = _arr(v_new, np.uint16)
+        ctx_lens = _arr(ctx_lens, np.int32)
+        assert k_new.shape == v_new.shape == (ctx_lens.size, hkv, d)
+        return self.lib.orc_kv_append(model, ctx_lens.size, _ptr(k_new), _ptr(v_new), _ptr(ctx_lens))
+
+    def kv_read(self, model, seq, tok_begin, n_tok):
+        """-> (code, k, v, k_scale, v_scale): elements [n_tok][Hkv][D], scales [n_tok][Hkv] (None for bf16)."""
+        _, hkv, d, dtype = self._shape[model]
+        et = np.uint16 if dtype == ORC_BF16 else np.uint8
+        k = np.zeros((n_tok, hkv, d), dtype=et)
+        v = np.zeros((n_tok, hkv, d), dtype=et)
+        ks = vs = None
+        if dtype != ORC_BF16:
+            ks = np.zeros((n_tok, hkv), dtype=np.float32)
+            vs = np.zeros((n_tok, hkv), dtype=np.float32)
+        rc = self.lib.orc_kv_read(model, seq, tok_begin, n_tok, _ptr(k), _ptr(v), _ptr(ks), _ptr(vs))
+        return rc, k, v, ks, vs
+
+    def prefill_attention(self, model, q, q_lens, ctx_lens, block_table=None):
+        """q: uint16 [sum q_lens][Hq][D]; returns (code, out fp32 [sum q_lens][Hq][D])."""
+        hq, _, d, _ = self._shape[model]
+        q = _arr(q, np.uint16)
+        q_lens = _arr(q_lens, np.int32)
+        ctx_lens = _arr(ctx_lens, np.int32)
+        assert q.shape == (int(q_lens.sum()), hq, d), (q.shape, q_lens.sum(), hq, d)
+        out = np.empty(q.shape, dtype=np.float32)
+        stride = 0
+        if block_table is not None:
+            block_table = _arr(block_table, np.int32)
+            stride = block_table.shape[1]
+        rc = self.lib.orc_prefill_attention(model, ctx_lens.size, _ptr(q), _ptr(q_lens), _ptr(block_table), stride,
+                                            _ptr(ctx_lens), _ptr(out))
+        return rc, out
+
+    def e4m3_encode(self, y):
+        return int(self.lib.orc_e4m3_encode(float(y)))
 
     def decode_attention(self, model, q, ctx_lens, block_table=None):
         """q: uint16 [B][Hq][D]; returns (code, out fp32 [B][Hq][D])."""

@@ -421,6 +421,128 @@ int orc_kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, co
     return n_tok;
 }
 
+/* Nearest E4M3 value of y, ties to the even code, magnitudes beyond the largest
+ * finite value (448) saturating to it: written out as a search over the 127 finite
+ * magnitudes, whose values are exact in double. */
+uint8_t orc_e4m3_encode(float y) {
+    if (y != y) return 0x7F;
+    uint8_t sign = signbit(y) ? 0x80 : 0x00;
+    double a = fabs((double)y);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7E);
+    int best = 0;
+    double best_err = a;                         /* code 0 is +0 */
+    for (int c = 1; c <= 0x7E; ++c) {
+        double err = fabs(orc_e4m3_decode((uint8_t)c) - a);
+        if (err < best_err || (err == best_err && (c & 1) == 0)) { best = c; best_err = err; }
+    }
+    return (uint8_t)(sign | best);
+}
+
+/* The write path of a decode step (paper: Sec. 4.2 D2, a sequence that grows takes its
+ * next token block from the slots of its pages; the new token's K and V are scattered
+ * into that block).  For every sequence s of the batch the token with index
+ * ctx_lens[s] - 1 is written; k_new, v_new are bf16 bit patterns [batch][Hkv][D].
+ *
+ * bf16 models store the values as they are.  e4m3 models keep one fp32 scale per (block,
+ * kv head) for K and one for V, equal to the running maximum of amax / 448 over the
+ * block's tokens, all arithmetic in fp32:
+ *   slot 0 of a block:   scale = amax > 0 ? amax / 448 : 1
+ *   later slots:         cand = amax / 448; if cand > scale, every code c already in the
+ *                        block becomes encode((decode(c) * scale) / cand) and scale = cand
+ *   the new token:       code = encode(x / scale)
+ * where amax = max_d |x[d]| of the token's row for that kv head. */
+static void append_row_e4m3(const model_t *m, const pool_t *p, uint8_t *blk, int kvh, int which, int slot,
+                            const uint16_t *x_bf16) {
+    float *scale_p = (float *)(blk + sizeof(float) * ((size_t)which * m->Hkv + kvh));
+    uint8_t *codes = blk + ORC_FP8_HEADER;
+    float amax = 0.0f;
+    for (int d = 0; d < m->D; ++d) {
+        float x = (float)bf16_to_double(x_bf16[d]);
+        if (fabsf(x) > amax) amax = fabsf(x);
+    }
+    float cand = amax / 448.0f;
+    float scale;
+    if (slot == 0) {
+        scale = amax > 0.0f ? cand : 1.0f;
+    } else {
+        memcpy(&scale, scale_p, sizeof scale);
+        if (cand > scale) {
+            for (int t = 0; t < slot; ++t)
+                for (int d = 0; d < m->D; ++d) {
+                    uint8_t *c = &codes[elem_index(m, p, kvh, which, t, d)];
+                    float v = (float)orc_e4m3_decode(*c) * scale;     /* fp32 product */
+                    *c = orc_e4m3_encode(v / cand);                    /* fp32 quotient */
+                }
+            scale = cand;
+        }
+    }
+    memcpy(scale_p, &scale, sizeof scale);
+    for (int d = 0; d < m->D; ++d) {
+        float x = (float)bf16_to_double(x_bf16[d]);
+        codes[elem_index(m, p, kvh, which, slot, d)] = orc_e4m3_encode(x / scale);
+    }
+}
+
+int orc_kv_append(int model, int batch, const uint16_t *k_new, const uint16_t *v_new, const int32_t *ctx_lens) {
+    model_t *m = get_model(model);
+    if (!m) return ORC_E_HANDLE;
+    if (batch < 0 || batch > m->max_seqs) return ORC_E_RANGE;
+    if (batch == 0) return 0;
+    if (!k_new || !v_new || !ctx_lens) return ORC_E_ARG;
+    pool_t *p = &g_pools[m->pool];
+    for (int s = 0; s < batch; ++s)
+        if (ctx_lens[s] < 1 || blocks_for(p, ctx_lens[s]) > m->row_len[s]) return ORC_E_RANGE;
+    for (int s = 0; s < batch; ++s) {
+        int tok = ctx_lens[s] - 1, slot = tok % p->T;
+        int32_t id = m->rows[(size_t)s * m->max_blocks + tok / p->T];
+        uint8_t *blk = p->mem + block_addr(m, p, id);
+        for (int h = 0; h < m->Hkv; ++h) {
+            const uint16_t *kx = k_new + ((size_t)s * m->Hkv + h) * m->D;
+            const uint16_t *vx = v_new + ((size_t)s * m->Hkv + h) * m->D;
+            if (m->dtype == ORC_BF16) {
+                memcpy(blk + elem_index(m, p, h, 0, slot, 0) * 2, kx, (size_t)m->D * 2);
+                memcpy(blk + elem_index(m, p, h, 1, slot, 0) * 2, vx, (size_t)m->D * 2);
+            } else {
+                append_row_e4m3(m, p, blk, h, 0, slot, kx);
+                append_row_e4m3(m, p, blk, h, 1, slot, vx);
+            }
+        }
+    }
+    return batch;
+}
+
+/* Read tokens back in the logical layout of orc_kv_write: k_out, v_out [n_tok][Hkv][D]
+ * elements; e4m3 only: k_scale_out, v_scale_out fp32 [n_tok][Hkv], the scale of the block
+ * each token lives in. */
+int orc_kv_read(int model, int seq, int tok_begin, int n_tok, void *k_out, void *v_out,
+                float *k_scale_out, float *v_scale_out) {
+    model_t *m = get_model(model);
+    if (!m) return ORC_E_HANDLE;
+    if (seq < 0 || seq >= m->max_seqs || tok_begin < 0 || n_tok < 0) return ORC_E_ARG;
+    if (n_tok == 0) return 0;
+    if (!k_out || !v_out) return ORC_E_ARG;
+    if (m->dtype == ORC_E4M3 && (!k_scale_out || !v_scale_out)) return ORC_E_ARG;
+    pool_t *p = &g_pools[m->pool];
+    if (((long)tok_begin + n_tok + p->T - 1) / p->T > m->row_len[seq]) return ORC_E_RANGE;
+    size_t e = m->dtype == ORC_BF16 ? 2 : 1;
+    size_t hdr = m->dtype == ORC_E4M3 ? ORC_FP8_HEADER : 0;
+    for (int t = 0; t < n_tok; ++t) {
+        int tok = tok_begin + t;
+        int32_t id = m->rows[(size_t)seq * m->max_blocks + tok / p->T];
+        const uint8_t *blk = p->mem + block_addr(m, p, id);
+        for (int h = 0; h < m->Hkv; ++h) {
+            size_t dst = ((size_t)t * m->Hkv + h) * m->D * e;
+            memcpy((uint8_t *)k_out + dst, blk + hdr + elem_index(m, p, h, 0, tok % p->T, 0) * e, m->D * e);
+            memcpy((uint8_t *)v_out + dst, blk + hdr + elem_index(m, p, h, 1, tok % p->T, 0) * e, m->D * e);
+            if (m->dtype == ORC_E4M3) {
+                memcpy(&k_scale_out[(size_t)t * m->Hkv + h], blk + sizeof(float) * (size_t)h, sizeof(float));
+                memcpy(&v_scale_out[(size_t)t * m->Hkv + h], blk + sizeof(float) * ((size_t)m->Hkv + h), sizeof(float));
+            }
+        }
+    }
+    return n_tok;
+}
+
 /* ------------------------------------------------------------- attention */
 
 static int check_row(const model_t *m, const pool_t *p, const int32_t *row, int ctx_len) {
@@ -497,6 +619,66 @@ int orc_decode_attention(int model, int batch, const uint16_t *q, const int32_t 
             free(pr);
         }
     }
+    return failed ? ORC_E_INTERNAL : ORC_OK;
+}
+
+/* Causal attention of a chunk of new tokens against the paged cache (paper: Sec. 5.2,
+ * prefill proceeds in chunks, every chunk attending to the cache built so far).  Sequence
+ * s brings q_lens[s] queries, packed one sequence after the other in q [sum q_lens][Hq][D];
+ * its cache already holds ctx_lens[s] tokens, the chunk's own included.  Query i of the
+ * sequence stands at position pos = ctx_lens[s] - q_lens[s] + i and sees the tokens
+ * t <= pos:   out = softmax_t<=pos(q . k[t] / sqrt(D)) V,   fp64, stored as fp32
+ * [sum q_lens][Hq][D]. */
+int orc_prefill_attention(int model, int batch, const uint16_t *q, const int32_t *q_lens,
+                          const int32_t *block_table, int row_stride, const int32_t *ctx_lens, float *out) {
+    model_t *m = get_model(model);
+    if (!m) return ORC_E_HANDLE;
+    if (batch < 0 || (batch > 0 && (!q || !q_lens || !ctx_lens || !out))) return ORC_E_ARG;
+    pool_t *p = &g_pools[m->pool];
+    if (!block_table) {
+        if (batch > m->max_seqs) return ORC_E_RANGE;
+        block_table = m->rows;
+        row_stride = m->max_blocks;
+        for (int s = 0; s < batch; ++s)
+            if (blocks_for(p, ctx_lens[s]) > m->row_len[s]) return ORC_E_RANGE;
+    }
+    long total_q = 0;
+    for (int s = 0; s < batch; ++s) {
+        if (q_lens[s] < 0 || ctx_lens[s] < q_lens[s] || blocks_for(p, ctx_lens[s]) > row_stride) return ORC_E_RANGE;
+        if (check_row(m, p, block_table + (size_t)s * row_stride, ctx_lens[s])) return ORC_E_RANGE;
+        total_q += q_lens[s];
+    }
+    /* one flat list of (sequence, query) so that the rows can be shared out evenly */
+    int32_t *seq_of = malloc(sizeof(int32_t) * (size_t)(total_q > 0 ? total_q : 1));
+    int32_t *idx_of = malloc(sizeof(int32_t) * (size_t)(total_q > 0 ? total_q : 1));
+    if (!seq_of || !idx_of) { free(seq_of); free(idx_of); return ORC_E_INTERNAL; }
+    long r = 0;
+    for (int s = 0; s < batch; ++s)
+        for (int i = 0; i < q_lens[s]; ++i) { seq_of[r] = s; idx_of[r] = i; ++r; }
+    int failed = 0;
+#pragma omp parallel for collapse(2) schedule(dynamic, 1)
+    for (long row_i = 0; row_i < total_q; ++row_i) {
+        for (int h = 0; h < m->Hq; ++h) {
+            int s = seq_of[row_i];
+            int L = ctx_lens[s] - q_lens[s] + idx_of[row_i] + 1;      /* tokens this query sees */
+            const int32_t *row = block_table + (size_t)s * row_stride;
+            const uint16_t *q_row = q + ((size_t)row_i * m->Hq + h) * m->D;
+            float *o = out + ((size_t)row_i * m->Hq + h) * m->D;
+            int kvh = h / m->g;
+            double *pr = malloc(sizeof(double) * (size_t)L);
+            if (!pr) { failed = 1; continue; }
+            softmax_row(m, p, q_row, row, L, kvh, pr);
+            for (int d = 0; d < m->D; ++d) {
+                double acc = 0.0;
+                for (int t = 0; t < L; ++t)
+                    acc += pr[t] * kv_value(m, p, row[t / p->T], kvh, 1, t % p->T, d);
+                o[d] = (float)acc;
+            }
+            free(pr);
+        }
+    }
+    free(seq_of);
+    free(idx_of);
     return failed ? ORC_E_INTERNAL : ORC_OK;
 }
 

@@ -66,10 +66,26 @@ int orc_seq_release(int model, int seq);
 int orc_kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const void *v,
                  const float *k_scale, const float *v_scale);
 
+/* decode-step write path: the token with index ctx_lens[s] - 1 of every sequence
+ * s < batch; k_new, v_new bf16 bit patterns [batch][Hkv][D].  e4m3 models quantise
+ * with a running per-(block, kv head) scale (rule stated at the definition). */
+int orc_kv_append(int model, int batch, const uint16_t *k_new, const uint16_t *v_new, const int32_t *ctx_lens);
+
+/* tokens back in the logical layout of orc_kv_write; e4m3 only: scales per token
+ * [n_tok][Hkv] (the scale of the token's block). */
+int orc_kv_read(int model, int seq, int tok_begin, int n_tok, void *k_out, void *v_out,
+                float *k_scale_out, float *v_scale_out);
+
 /* q: bf16 bit patterns [B][Hq][D]; block_table NULL = the model's own rows 0..B-1
  * (row_stride ignored); out fp32 [B][Hq][D]. */
 int orc_decode_attention(int model, int batch, const uint16_t *q, const int32_t *block_table,
                          int row_stride, const int32_t *ctx_lens, float *out);
+
+/* causal attention of a chunk: q [sum q_lens][Hq][D] packed by sequence, the cache
+ * holds ctx_lens[s] tokens (the chunk's included), query i of s sees t <= ctx_lens[s]
+ * - q_lens[s] + i; out fp32 [sum q_lens][Hq][D]. */
+int orc_prefill_attention(int model, int batch, const uint16_t *q, const int32_t *q_lens,
+                          const int32_t *block_table, int row_stride, const int32_t *ctx_lens, float *out);
 
 /* debug: the softmax row p[0..ctx_len) of one (sequence, q head), in fp64 */
 int orc_attention_probs(int model, const uint16_t *q_row, const int32_t *table_row, int ctx_len,
@@ -90,6 +106,7 @@ const int32_t *orc_model_block_table(int model, int *row_stride);
 int orc_model_row_len(int model, int seq);
 
 double orc_e4m3_decode(uint8_t code);
+uint8_t orc_e4m3_encode(float y);   /* nearest value, ties to even code, saturating at 448 */
 int orc_num_threads(void);
 void orc_set_num_threads(int n);
 
