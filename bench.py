@@ -103,6 +103,32 @@ def balloon_latency(gpu, torch):
             "kind": "host wall clock per call, median of 50"}
 
 
+def append_latency(gpu, torch, rep, inputs):
+    """The decode step's write path (kv_append) for the models of one replica: every sequence's
+    last token is written again, 100 times; device time per call from events on the stream."""
+    import numpy as np
+    mids, qs, ctxs, outs = inputs
+    res = {}
+    for m, ctx, mi in zip(mids, ctxs, rep.active_models()):
+        spec = rep.cfg.models[mi]
+        g = torch.Generator(device="cpu"); g.manual_seed(1234 + mi)
+        kx = torch.randn((spec.batch, spec.kv_heads, spec.head_dim), generator=g).to(torch.bfloat16).view(torch.int16).cuda()
+        vx = torch.randn((spec.batch, spec.kv_heads, spec.head_dim), generator=g).to(torch.bfloat16).view(torch.int16).cuda()
+        for _ in range(10):
+            assert gpu.kv_append_dev(m, kx, vx, ctx) == spec.batch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(100):
+            gpu.kv_append_dev(m, kx, vx, ctx)
+        e1.record()
+        torch.cuda.synchronize()
+        res[f"model{mi}_batch{spec.batch}_{'e4m3' if spec.dtype else 'bf16'}_us"] = round(e0.elapsed_time(e1) * 10.0, 2)
+    assert gpu.device_errors() == 0
+    res["kind"] = "device time per kv_append call (one new token per sequence), mean of 100 back-to-back calls"
+    return res
+
+
 def cpu_baseline(rep, seconds):
     """The oracle, as it stands, on the same workload: the same bookkeeping calls and
     KV, decode attention of every model's batch on all host cores, repeated with the
@@ -229,6 +255,7 @@ def main():
                                    "scattered_64KiB": round(gpu.stream_read_probe(4 << 30, 64 << 10, 10), 1)}
     if not args.no_balloon:
         result["balloon_resize"] = balloon_latency(gpu, torch)
+        result["kv_append"] = append_latency(gpu, torch, reps[0], inputs[0])
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(reps[0], args.cpu_seconds)
     for rep in reps:

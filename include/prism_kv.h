@@ -137,6 +137,29 @@ const int32_t *model_block_table(int model, int *row_stride);
 int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const void *v,
              const float *k_scale, const float *v_scale);
 
+/* The write path of a decode step (paper Sec. 4.2, D2: a growing sequence takes its next
+ * token block from the slots of its pages): for every sequence s < batch the token with
+ * index ctx_lens[s] - 1 is written into the row's reserved blocks (the library's table).
+ * k_new, v_new: dev, bf16 [batch][kv_heads][head_dim], the values as the model produced
+ * them, for both cache types.  ctx_lens: dev int32 [batch].
+ * e4m3 models quantise here, one fp32 scale per (block, kv head) for K and for V, kept
+ * equal to the running maximum of amax / 448 over the block's tokens (fp32 arithmetic,
+ * round to nearest even, saturating):  slot 0 of a block: scale = amax > 0 ? amax/448 : 1;
+ * later slots: cand = amax/448, and if cand > scale every code c already in the block
+ * becomes encode((decode(c) * scale) / cand) and scale = cand;  the new token's codes are
+ * encode(x / scale).
+ * A context length outside 1 .. 16 * (blocks reserved for the row) is skipped and sets
+ * bit 1 of pkv_device_errors().  Returns batch; PKV_E_RANGE if batch exceeds the model's
+ * rows.  Enqueues only. */
+int kv_append(int model, int batch, const void *k_new, const void *v_new, const int32_t *ctx_lens);
+
+/* Tokens [tok_begin, tok_begin + n_tok) of a sequence back in the logical layout of
+ * kv_write: k_out, v_out dev [n_tok][kv_heads][head_dim] (bf16 values or e4m3 codes);
+ * e4m3 only: k_scale_out, v_scale_out dev fp32 [n_tok][kv_heads], the scale of the
+ * block each token lives in.  For tests and debugging.  Enqueues only. */
+int kv_read(int model, int seq, int tok_begin, int n_tok, void *k_out, void *v_out,
+            float *k_scale_out, float *v_scale_out);
+
 /* ---- decode attention (Background: paged attention over the block table) -- */
 
 /* Batch shape used by decode_attention: `batch` sequences, caller block tables
@@ -162,6 +185,21 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
 int decode_attention_multi(int n_models, const int *models, const int *batches,
                            const void *const *q, const int32_t *const *ctx_lens,
                            float *const *out);
+
+/* Causal attention of prefill chunks against the paged cache (paper Sec. 5.2: prefill runs
+ * in chunks, each attending to the cache built so far).  Sequence s < batch brings
+ * q_lens[s] new query tokens, packed one sequence after the other in q (dev, bf16
+ * [sum q_lens][q_heads][head_dim]); its cache holds ctx_lens[s] tokens, the chunk's own
+ * included (write them first: kv_write or kv_append).  Query i of the sequence stands at
+ * position ctx_lens[s] - q_lens[s] + i and sees the tokens at or before it:
+ *     out = softmax over t <= position of (q . k[t] / sqrt(head_dim)) V
+ * out: dev fp32 [sum q_lens][q_heads][head_dim].  q_lens: HOST int32 [batch] (the caller's
+ * scheduler chose the chunk sizes); ctx_lens: dev int32 [batch].  The library's table is
+ * used.  A sequence whose ctx_lens is below its q_lens gets zero rows for the queries
+ * that would stand before position 0.  Enqueues only (a small host-to-device copy of the
+ * row plan included). */
+int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens,
+                      const int32_t *ctx_lens, float *out);
 
 /* ---- observation ----------------------------------------------------------- */
 

@@ -55,10 +55,13 @@ def _load():
         "seq_release": (i, [i, i]),
         "model_block_table": (vp, [i, C.POINTER(i)]),
         "kv_write": (i, [i, i, i, i, vp, vp, vp, vp]),
+        "kv_append": (i, [i, i, vp, vp, vp]),
+        "kv_read": (i, [i, i, i, i, vp, vp, vp, vp]),
         "model_set_batch": (i, [i, i, i]),
         "decode_attention": (i, [i, vp, vp, vp, vp]),
         "decode_attention_ex": (i, [i, i, vp, vp, i, vp, vp]),
         "decode_attention_multi": (i, [i, vp, vp, vp, vp, vp]),
+        "prefill_attention": (i, [i, i, vp, vp, vp, vp]),
         "pool_export_state": (l, [i, vp, sz]),
         "pool_stats": (i, [i, vp]),
     }
@@ -74,8 +77,8 @@ EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_spl
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
-           "seq_release", "model_block_table", "kv_write", "model_set_batch", "decode_attention",
-           "decode_attention_ex", "decode_attention_multi", "pool_export_state", "pool_stats"]
+           "seq_release", "model_block_table", "kv_write", "kv_append", "kv_read", "model_set_batch", "decode_attention",
+           "decode_attention_ex", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats"]
 
 
 class PrismKV:
@@ -231,6 +234,37 @@ class PrismKV:
         self.torch.cuda.current_stream(self.device).synchronize()
         return rc
 
+    def kv_append_dev(self, model, k_new, v_new, ctx_lens):
+        """Device tensors (bf16 bits [B][Hkv][D], int32 [B]); only enqueues."""
+        return self.lib.kv_append(model, ctx_lens.numel(), self._p(k_new), self._p(v_new), self._p(ctx_lens))
+
+    def kv_append(self, model, k_new, v_new, ctx_lens):
+        _, hkv, d, _ = self._shape[model]
+        k_new, v_new = self._dev(np.ascontiguousarray(k_new)), self._dev(np.ascontiguousarray(v_new))
+        ctx = self._dev(np.ascontiguousarray(ctx_lens, dtype=np.int32))
+        assert tuple(k_new.shape) == (ctx.numel(), hkv, d) and k_new.shape == v_new.shape
+        rc = self.kv_append_dev(model, k_new, v_new, ctx)
+        self.torch.cuda.current_stream(self.device).synchronize()
+        return rc
+
+    def kv_read(self, model, seq, tok_begin, n_tok):
+        """-> (code, k, v, k_scale, v_scale) as numpy: elements [n_tok][Hkv][D], scales [n_tok][Hkv] (None for bf16)."""
+        t = self.torch
+        _, hkv, d, dtype = self._shape[model]
+        et = t.int16 if dtype == 0 else t.uint8
+        k = t.zeros((n_tok, hkv, d), dtype=et, device=self.device)
+        v = t.zeros((n_tok, hkv, d), dtype=et, device=self.device)
+        ks = vs = None
+        if dtype != 0:
+            ks = t.zeros((n_tok, hkv), dtype=t.float32, device=self.device)
+            vs = t.zeros((n_tok, hkv), dtype=t.float32, device=self.device)
+        rc = self.lib.kv_read(model, seq, tok_begin, n_tok, self._p(k), self._p(v), self._p(ks), self._p(vs))
+        t.cuda.current_stream(self.device).synchronize()
+        kn, vn = k.cpu().numpy(), v.cpu().numpy()
+        if dtype == 0:
+            kn, vn = kn.view(np.uint16), vn.view(np.uint16)
+        return rc, kn, vn, (None if ks is None else ks.cpu().numpy()), (None if vs is None else vs.cpu().numpy())
+
     def model_set_batch(self, model, batch, row_stride):
         return self.lib.model_set_batch(model, batch, row_stride)
 
@@ -254,6 +288,25 @@ class PrismKV:
                            if isinstance(block_table, np.ndarray) else block_table)
         out = t.empty((ctx.numel(), hq, d), dtype=t.float32, device=self.device)
         rc = self.decode_attention_dev(model, q, ctx, out, bt)
+        t.cuda.current_stream(self.device).synchronize()
+        return rc, out.cpu().numpy()
+
+    def prefill_attention_dev(self, model, q, q_lens, ctx_lens, out):
+        """q, ctx_lens, out: device tensors; q_lens: host int32 numpy array.  Only enqueues."""
+        q_lens = np.ascontiguousarray(q_lens, dtype=np.int32)
+        return self.lib.prefill_attention(model, q_lens.size, self._p(q), q_lens.ctypes.data_as(C.c_void_p),
+                                          self._p(ctx_lens), self._p(out))
+
+    def prefill_attention(self, model, q, q_lens, ctx_lens):
+        """Convenience for tests: -> (code, out as numpy fp32 [sum q_lens][Hq][D])."""
+        t = self.torch
+        hq, _, d, _ = self._shape[model]
+        q = self._dev(q)
+        ctx = self._dev(np.ascontiguousarray(ctx_lens, dtype=np.int32))
+        q_lens = np.ascontiguousarray(q_lens, dtype=np.int32)
+        assert tuple(q.shape) == (int(q_lens.sum()), hq, d)
+        out = t.empty((int(q_lens.sum()), hq, d), dtype=t.float32, device=self.device)
+        rc = self.prefill_attention_dev(model, q, q_lens, ctx, out)
         t.cuda.current_stream(self.device).synchronize()
         return rc, out.cpu().numpy()
 

@@ -40,6 +40,8 @@ struct Model {
     size_t ws_floats = 0;
     uint32_t *cnt = nullptr;                // arrival counters, zero between launches
     size_t cnt_cap = 0;
+    int4 *vmap = nullptr;                   // device: the rows (query tiles) of the last prefill launch
+    size_t vmap_cap = 0;
 };
 
 // Uncached device memory for split-K partials and arrival counters.  Blocks are
@@ -132,6 +134,9 @@ void free_model_dev(Model &m) {
     (void)hipFree(m.dev.row_len); (void)hipFree(m.dev.counters);
     uc_release(m.ws);
     uc_release(m.cnt);
+    (void)hipFree(m.vmap);
+    m.vmap = nullptr;
+    m.vmap_cap = 0;
     m.dev = ModelDev{};
     m.ws = nullptr;
     m.cnt = nullptr;
@@ -157,8 +162,10 @@ double est_bytes(const Model &m, bool own, int batch, int row_stride) {
     return blocks * m.Hkv * (g_page_cost + 0.1 * page_kib);
 }
 
+// cols: MFMA columns per kv head (0 = g: one query token per row); units_hint: upper bound of the
+// page units of the launch when the rows are not whole sequences (0 = derive from the blocks in use)
 int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *table, int row_stride,
-              const int32_t *ctx_lens, float *out, double share_of_launch) {
+              const int32_t *ctx_lens, float *out, double share_of_launch, int cols = 0, double units_hint = 0.0) {
     Pool &p = g_pools[m.pool];
     const bool own = table == nullptr;
     d.pool_base = p.base;
@@ -176,19 +183,22 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.max_block_id = (uint32_t)(p.n_frames * m.slots);
     d.batch = batch;
     d.Hq = m.Hq; d.Hkv = m.Hkv; d.g = m.g; d.D = m.D; d.dtype = m.dtype;
+    d.vmap = nullptr;
+    d.cols = cols > 0 ? cols : m.g;
     d.item_begin = 0;
     d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m.D));
     d.min_share = g_min_share > 0 ? g_min_share : kDefaultMinShare;
     d.seg_cost = g_seg_cost >= 0 ? g_seg_cost : kDefaultSegCost;
     // no more items than there can be shares of min_share pages (an empty row counts as one page)
-    const double units = ((own ? (double)m.used_blocks : (double)batch * d.row_stride) +
-                          (double)batch * (d.seg_cost + 1)) * m.Hkv;
+    const double units = units_hint > 0.0 ? units_hint
+                                          : ((own ? (double)m.used_blocks : (double)batch * d.row_stride) +
+                                             (double)batch * (d.seg_cost + 1)) * m.Hkv;
     double items = (g_items > 0 ? g_items : kDefaultItems) * share_of_launch;
     if (items > units / d.min_share) items = units / d.min_share;
     d.n_items = items < 1.0 ? 1 : (int)items;                // never more than the slots in total
     if (d.n_items >= 8) d.n_items &= ~7;                     // whole blocks of eight: one item per XCD
     d.weighted = d.n_items % 8 == 0 ? 1 : 0;
-    const size_t need = (size_t)2 * d.n_items * m.g * (m.D + 2);
+    const size_t need = (size_t)2 * d.n_items * d.cols * (m.D + 2);
     if (need > m.ws_floats) {
         HIP_TRY(hipStreamSynchronize(g_stream));
         uc_release(m.ws);
@@ -652,6 +662,51 @@ int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const 
     return n_tok;
 }
 
+// the part of a descriptor that addressing a model's own blocks needs
+static void fill_addressing(AttnDesc &d, const Model &m) {
+    const Pool &p = g_pools[m.pool];
+    d.pool_base = p.base;
+    d.table = m.dev.rows;
+    d.row_stride = m.dev.max_blocks;
+    d.row_len = m.dev.row_len;
+    d.err = g_err;
+    d.frame_bytes = p.frame_bytes;
+    d.block_bytes = m.block_bytes;
+    d.slots_div = fastdiv_make((uint32_t)m.slots);
+    d.max_block_id = (uint32_t)(p.n_frames * m.slots);
+    d.Hq = m.Hq; d.Hkv = m.Hkv; d.g = m.g; d.D = m.D; d.dtype = m.dtype;
+}
+
+int kv_read(int model, int seq, int tok_begin, int n_tok, void *k_out, void *v_out, float *k_scale_out,
+            float *v_scale_out) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (seq < 0 || seq >= m->dev.max_seqs || tok_begin < 0 || n_tok < 0) return PKV_E_ARG;
+    if (n_tok == 0) return 0;
+    if (!k_out || !v_out) return PKV_E_ARG;
+    if (m->dtype == PKV_E4M3 && (!k_scale_out || !v_scale_out)) return PKV_E_ARG;
+    Pool &p = g_pools[m->pool];
+    if (((int64_t)tok_begin + n_tok + p.T - 1) / p.T > m->row_len[seq]) return PKV_E_RANGE;
+    AttnDesc d{};
+    fill_addressing(d, *m);
+    HIP_TRY(pkv_launch_kv_read(d, seq, tok_begin, n_tok, k_out, v_out, k_scale_out, v_scale_out, g_stream));
+    return n_tok;
+}
+
+int kv_append(int model, int batch, const void *k_new, const void *v_new, const int32_t *ctx_lens) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (batch < 0 || batch > m->dev.max_seqs) return PKV_E_RANGE;
+    if (batch == 0) return 0;
+    if (!k_new || !v_new || !ctx_lens) return PKV_E_ARG;
+    AttnDesc d{};
+    fill_addressing(d, *m);
+    d.batch = batch;
+    d.ctx_lens = ctx_lens;
+    HIP_TRY(pkv_launch_kv_append(d, k_new, v_new, g_stream));
+    return batch;
+}
+
 /* -------------------------------------------------------- decode attention */
 
 int model_set_batch(int model, int batch, int row_stride) {
@@ -681,6 +736,48 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
     if (rc) return rc;
 
+    return launch_attention(grp);
+}
+
+int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens, const int32_t *ctx_lens, float *out) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (batch < 0 || batch > m->dev.max_seqs) return PKV_E_RANGE;
+    if (batch == 0) return PKV_OK;
+    if (!q || !q_lens || !ctx_lens || !out) return PKV_E_ARG;
+    if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return PKV_E_ARG;
+    // rows of the launch: tiles of as many consecutive query tokens as fit the 16 MFMA columns with g heads
+    const int tile = 16 / m->g > 0 ? 16 / m->g : 1;
+    std::vector<int4> rows;
+    double units = 0.0;
+    const int seg = g_seg_cost >= 0 ? g_seg_cost : kDefaultSegCost;
+    int64_t first = 0;
+    for (int s = 0; s < batch; ++s) {
+        if (q_lens[s] < 0) return PKV_E_ARG;
+        for (int t0 = 0; t0 < q_lens[s]; t0 += tile) {
+            const int n = q_lens[s] - t0 < tile ? q_lens[s] - t0 : tile;
+            rows.push_back(make_int4(s, (int)(first + t0), q_lens[s] - (t0 + n), n));
+            units += ((double)m->row_len[s] + seg + 1) * m->Hkv;
+        }
+        first += q_lens[s];
+        if (first > (int64_t)1 << 24) return PKV_E_RANGE;
+    }
+    if (rows.empty()) return PKV_OK;
+    if (rows.size() > m->vmap_cap) {
+        HIP_TRY(hipStreamSynchronize(g_stream));
+        (void)hipFree(m->vmap);
+        m->vmap = nullptr;
+        m->vmap_cap = 0;
+        HIP_TRY(hipMalloc((void **)&m->vmap, rows.size() * 2 * sizeof(int4)));
+        m->vmap_cap = rows.size() * 2;
+    }
+    // pageable source: the copy has read `rows` when the call returns, and runs in stream order
+    HIP_TRY(hipMemcpyAsync(m->vmap, rows.data(), rows.size() * sizeof(int4), hipMemcpyHostToDevice, g_stream));
+    AttnGroup grp;
+    grp.n = 1;
+    int rc = fill_desc(grp.m[0], *m, (int)rows.size(), q, nullptr, 0, ctx_lens, out, 1.0, tile * m->g, units);
+    if (rc) return rc;
+    grp.m[0].vmap = m->vmap;
     return launch_attention(grp);
 }
 

@@ -228,9 +228,11 @@ __device__ __forceinline__ void split_p(const float *p, u32x2 &hi, u32x2 &lo) {
 // valid_b 0..16 (0: the pair has no second page; its registers hold zeros).
 template <int D, int DT>
 __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D, DT> &r, const bf16x8 *qf,
-                                             float scale_log2, int valid_a, int valid_b, int G) {
+                                             float scale_log2, int valid_a, int valid_b, int G, int lim_a, bool causal) {
     using TL = Tile<D, DT>;
-    const bool tail = valid_a < T || valid_b < T;          // wave-uniform
+    // lim_a: how many tokens of page a this lane's column may see (any integer; page b: lim_a - 16);
+    // causal: some column's limit falls inside the pair (wave-uniform)
+    const bool tail = valid_a < T || valid_b < T || causal;
     f32x4 sa = qk_page<D, DT>(r.a, qf);
     f32x4 sb = qk_page<D, DT>(r.b, qf);
     const float sca = DT == PKV_E4M3 ? scale_log2 * r.a.sk : scale_log2;
@@ -241,23 +243,26 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
         s[i] = sa[i] * sca;
         s[4 + i] = sb[i] * scb;
         if (tail) {                                        // select, so a NaN logit of a dead token cannot leak
-            if (4 * G + i >= valid_a) s[i] = -INFINITY;
-            if (4 * G + i >= valid_b) s[4 + i] = -INFINITY;
+            const int la = lim_a < valid_a ? lim_a : valid_a, lb = lim_a - T < valid_b ? lim_a - T : valid_b;
+            if (4 * G + i >= la) s[i] = -INFINITY;
+            if (4 * G + i >= lb) s[4 + i] = -INFINITY;
         }
     }
     float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
     mx = rows_max(mx);
     const float m_new = fmaxf(st.m, mx);
-    if (__any(m_new > st.m)) {            // wave-uniform: rescale only when some head's max moved
-        const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    if (__any(m_new > st.m)) {            // wave-uniform: rescale only when some column's max moved
+        // a column that has seen no token yet (prefill tiles only) has m = -inf on both sides
+        const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
         st.l *= alpha;
 #pragma unroll
         for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] *= alpha;
         st.m = m_new;
     }
     float p[8];
+    const float m_ref = st.m == -INFINITY ? 0.f : st.m;     // then every s is -inf and every p is 0
 #pragma unroll
-    for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - st.m);
+    for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
     st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
     if (DT == PKV_E4M3) {
 #pragma unroll
@@ -316,11 +321,39 @@ struct Ring {
 };
 constexpr int MAX_PIECES = 64;   // pieces of one (sequence, kv head) the merge stages in LDS
 
-// Pages the work split plans for a sequence: its context rounded up to pages, never
-// beyond what its table row holds, and at least one so that an empty sequence still
-// has an owner who writes its zero row.
-__device__ __forceinline__ int ctx_clamped(const AttnDesc &d, int seq) {
-    int L = PKV_CONST(int32_t, d.ctx_lens)[seq];
+// A row of a launch.  In a decode step it is a sequence with its one new query token.  In a
+// prefill launch it is a tile of consecutive query tokens of a sequence's chunk (as many as
+// fit the 16 MFMA columns together with the g heads of a kv head): `seq` is the sequence,
+// `q0` the first of the tile's rows in the packed q and out arrays, `ntok` their number,
+// and `back` how many chunk tokens follow the tile, so that the tile's last token sees
+// ctx_lens[seq] - back tokens.
+struct RowInfo {
+    int seq, q0, back, ntok;
+};
+
+__device__ __forceinline__ RowInfo row_info(const AttnDesc &d, int row) {
+    if (!d.vmap) return RowInfo{row, row, 0, 1};
+    const int4 v = d.vmap[row];
+    return RowInfo{v.x, v.y, v.z, v.w};
+}
+
+__device__ __forceinline__ RowInfo row_info_uniform(const AttnDesc &d, int row) {
+    if (!d.vmap) return RowInfo{row, row, 0, 1};
+    const int32_t *v = reinterpret_cast<const int32_t *>(d.vmap + row);
+    return RowInfo{__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, v)[0]), __builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, v)[1]),
+                   __builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, v)[2]), __builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, v)[3])};
+}
+
+// Pages the work split plans for a row: the tokens its last query sees, rounded up to
+// pages, never beyond what the sequence's table row holds.
+__device__ __forceinline__ int ctx_clamped(const AttnDesc &d, int row) {
+    int seq = row, back = 0;
+    if (d.vmap) {
+        const int4 v = d.vmap[row];
+        seq = v.x;
+        back = v.z;
+    }
+    int L = PKV_CONST(int32_t, d.ctx_lens)[seq] - back;
     const int cap = (d.row_len ? PKV_CONST(int32_t, d.row_len)[seq] : d.row_stride) * T;
     return L < 0 ? 0 : (L > cap ? cap : L);
 }
@@ -376,15 +409,26 @@ __device__ __forceinline__ Piece piece_next(const Piece &c, const AttnDesc &d, u
     return nx;
 }
 
-// q as the B operand: lane (G, n) holds q[head n][8(4j+G) .. +7] for each k-step j
+// Which (query token of the row, head of the kv head's group) an MFMA column stands for.
+struct Column {
+    int tok, head;      // column n = tok * g + head
+};
+
+__device__ __forceinline__ Column column_of(const AttnDesc &d, int n) {
+    const int tok = n / d.g;
+    return Column{tok, n - tok * d.g};
+}
+
+// q as the B operand: lane (G, n) holds q[column n][8(4j+G) .. +7] for each k-step j
 template <int D>
-__device__ __forceinline__ void load_q(bf16x8 *qf, const AttnDesc &d, int seq, int kvh, int lane) {
+__device__ __forceinline__ void load_q(bf16x8 *qf, const AttnDesc &d, const RowInfo &ri, int kvh, int lane, Column col) {
     const int G = lane >> 4, n = lane & 15;
-    const uint16_t *qrow = d.q + ((size_t)seq * d.Hq + kvh * d.g + n) * D;
+    const uint16_t *qrow = d.q + ((size_t)(ri.q0 + col.tok) * d.Hq + kvh * d.g + col.head) * D;
+    const bool live = n < d.cols && col.tok < ri.ntok;
 #pragma unroll
     for (int j = 0; j < D / 32; ++j) {
         u32x4 v = mk4(0, 0, 0, 0);
-        if (n < d.g) v = *reinterpret_cast<const u32x4 *>(qrow + 8 * (4 * j + G));
+        if (live) v = *reinterpret_cast<const u32x4 *>(qrow + 8 * (4 * j + G));
         qf[j] = *reinterpret_cast<bf16x8 *>(&v);
     }
 }
@@ -408,8 +452,9 @@ __device__ __forceinline__ void merge_rows(const AttnDesc &d, const Pending &pd,
                                            const float *base, int n_pc) {
     constexpr int D4 = D / 4;
     constexpr int PB = 32 / EPL;                      // pieces per trip
-    const int g = d.g, pf = partial_floats(g, D);
+    const int g = d.cols, pf = partial_floats(g, D);  // g: columns (query token, head) of a partial
     const int E = g * D4;
+    const RowInfo ri = row_info_uniform(d, pd.seq);
     int hn[EPL], x[EPL];
 #pragma unroll
     for (int k = 0; k < EPL; ++k) {
@@ -467,16 +512,18 @@ __device__ __forceinline__ void merge_rows(const AttnDesc &d, const Pending &pd,
         }
     }
 #pragma unroll
-    for (int k = 0; k < EPL; ++k)
-        if (lane + 64 * k < E)
-            *reinterpret_cast<f32x4 *>(d.out + ((size_t)pd.seq * d.Hq + pd.kvh * g + hn[k]) * D + 4 * x[k]) =
+    for (int k = 0; k < EPL; ++k) {
+        const Column col = column_of(d, hn[k]);
+        if (lane + 64 * k < E && col.tok < ri.ntok)
+            *reinterpret_cast<f32x4 *>(d.out + ((size_t)(ri.q0 + col.tok) * d.Hq + pd.kvh * d.g + col.head) * D + 4 * x[k]) =
                 num[k] * (1.0f / den[k]);
+    }
     __builtin_amdgcn_wave_barrier();
 }
 
 template <int D>
 __device__ __forceinline__ void merge_segment(const AttnDesc &d, const Pending &pd, int lane, float *s_m, float *s_l) {
-    const int g = d.g, pf = partial_floats(g, D);
+    const int g = d.cols, pf = partial_floats(g, D);
     const int n_pc = (int)(pd.k1 - pd.k0) + 1;
     const float *base = d.ws + (size_t)(2 * pd.k0) * pf;
     const int groups = (g * (D / 4) + 63) / 64;       // element groups per lane
@@ -545,7 +592,8 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                                               ((uint64_t)__builtin_amdgcn_s_getreg(63508) << 32);
 #endif
     const int G = lane >> 4, n = lane & 15;
-    const int g = d.g, Hkv = d.Hkv, B = d.batch;
+    const int g = d.cols, Hkv = d.Hkv, B = d.batch;   // g: columns in use, (query tokens of a row) x (heads of a kv head)
+    const Column col = column_of(d, n);
     const uint64_t t_begin = w.stat ? wall_clock64() : 0;
 
     // --- planned pages per sequence, prefix sums across the wave.  Batches of up to
@@ -663,8 +711,9 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     constexpr int RING = Ring<D, DT>::N;
     PairRegs<D, DT> ring[RING];
     PairIds pre;                            // block ids of the next pair to be requested
+    RowInfo ri_c = row_info_uniform(d, cur.seq);       // the row of the piece being worked on
     {
-        const int32_t *row = d.table + (size_t)cur.seq * d.row_stride;
+        const int32_t *row = d.table + (size_t)ri_c.seq * d.row_stride;
         const int live_n = cur.n_pages > 0 ? cur.pe - cur.pb : 0;
 #pragma unroll
         for (int r = 0; r < RING - 1; ++r)
@@ -673,7 +722,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
         pre = fetch_ids(d, row, cur.pb + 2 * (RING - 1));
     }
     bf16x8 qf[TL::NK], qn[TL::NK];
-    load_q<D>(qf, d, cur.seq, cur.kvh, lane);
+    load_q<D>(qf, d, ri_c, cur.kvh, lane, col);
 
     State<D, DT> st;
     PKV_STAMP(2);
@@ -692,15 +741,20 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
 #endif
     while (cur.valid) {
         const Piece nxt = piece_next(cur, d, gbeg, gend);
+        const RowInfo ri_n = nxt.valid ? row_info_uniform(d, nxt.seq) : ri_c;
         // q of the next piece travels while this piece streams (of this piece again if there is no next)
-        load_q<D>(qn, d, nxt.valid ? nxt.seq : cur.seq, nxt.valid ? nxt.kvh : cur.kvh, lane);
+        load_q<D>(qn, d, ri_n, nxt.valid ? nxt.kvh : cur.kvh, lane, col);
 #pragma unroll
         for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
         st.m = -INFINITY;
         st.l = 0.f;
 
-        const int32_t *row_c = d.table + (size_t)cur.seq * d.row_stride;
-        const int32_t *row_n = d.table + (size_t)(nxt.valid ? nxt.seq : cur.seq) * d.row_stride;
+        const int32_t *row_c = d.table + (size_t)ri_c.seq * d.row_stride;
+        const int32_t *row_n = d.table + (size_t)ri_n.seq * d.row_stride;
+        // tokens this lane's column may see: the row's last query sees cur.L, the one before it one less, ...
+        const bool col_live = n < g && col.tok < ri_c.ntok;
+        const int col_lim = col_live ? cur.L - (ri_c.ntok - 1 - col.tok) : cur.L;
+        const int causal_from = cur.L - (ri_c.ntok - 1);              // the first token some column may not see
         const int n_live = cur.n_pages > 0 ? cur.pe - cur.pb : 0;       // pages to read and process
         const int n_next = (nxt.valid && nxt.n_pages > 0) ? nxt.pe - nxt.pb : 0;
         const int n_pairs = n_live > 0 ? (n_live + 1) >> 1 : 1;         // an empty segment still takes a turn
@@ -757,7 +811,8 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                     const int pa = cur.pb + i;                                  // absolute page of the pair's first half
                     const int va = pa == cur.n_pages - 1 ? last_valid : T;
                     const int vb = i + 1 < n_live ? (pa + 1 == cur.n_pages - 1 ? last_valid : T) : 0;
-                    process_pair<D, DT>(st, ring[r], qf, d.scale_log2, va, vb, G);
+                    process_pair<D, DT>(st, ring[r], qf, d.scale_log2, va, vb, G, col_lim - pa * T,
+                                        (pa + 2) * T > causal_from);
 #if PKV_PRIO
                     prio_done += 2;
 #endif
@@ -775,9 +830,9 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
         }
 
         // --- the piece is done: finish the segment or park a partial
-        float *out_row = d.out + ((size_t)cur.seq * d.Hq + cur.kvh * g + n) * D;
+        float *out_row = d.out + ((size_t)(ri_c.q0 + col.tok) * d.Hq + cur.kvh * d.g + col.head) * D;
         if (cur.n_pages == 0) {                  // empty context: the row is defined as zero
-            if (cur.pb == 0 && n < g) {
+            if (cur.pb == 0 && col_live) {
 #pragma unroll
                 for (int jt = 0; jt < TL::NV; ++jt)
                     *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -788,7 +843,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
             l += __shfl_xor(l, 32);
             const uint32_t k0 = cut.index(cur.g0), k1 = cut.index(cur.g0 + (uint32_t)cur.n_pages - 1);
             if (k0 == k1) {                      // the whole segment was ours
-                if (n < g) {
+                if (col_live) {
                     const float inv = 1.0f / l;
 #pragma unroll
                     for (int jt = 0; jt < TL::NV; ++jt)
@@ -796,7 +851,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                 }
             } else {
                 float *w = cur.pb == 0 ? ws_b : ws_a;
-                if (n < g) {
+                if (col_live) {
 #pragma unroll
                     for (int jt = 0; jt < TL::NV; ++jt)
                         *reinterpret_cast<f32x4 *>(w + n * D + 16 * jt + 4 * G) = st.acc[jt];
@@ -824,6 +879,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
             }
         }
         cur = nxt;
+        ri_c = ri_n;
 #pragma unroll
         for (int j = 0; j < TL::NK; ++j) qf[j] = qn[j];
     }
@@ -915,69 +971,7 @@ __global__ __launch_bounds__(256) void k_stream_read(const u32x4 *src, size_t n1
     if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = 1;   // keeps the loads alive
 }
 
-// kv_write: logical [n_tok][Hkv][D] -> the in-block operand layouts described above.
-// One lane per (token, kv head, element); K and V handled together.
-template <int DT>
-__global__ void k_kv_write(AttnDesc d, const int32_t *row, int tok_begin, int n_tok, const uint8_t *k,
-                           const uint8_t *v, const float *ks, const float *vs) {
-    constexpr int E = DT == PKV_BF16 ? 2 : 1;
-    const int D = d.D, Hkv = d.Hkv;
-    const int64_t total = (int64_t)n_tok * Hkv * D;
-    const int64_t idx = blockIdx.x * (int64_t)blockDim.x + threadIdx.x;
-    if (idx >= total) return;
-    const int dd = (int)(idx % D);
-    const int h = (int)((idx / D) % Hkv);
-    const int ti = (int)(idx / ((int64_t)D * Hkv));
-    const int tok = tok_begin + ti;
-    const int page = tok / T, t = tok % T;
-    const uint32_t id = (uint32_t)row[page];
-    const uint32_t f = fastdiv_div(id, d.slots_div);
-    const uint32_t s = id - f * d.slots_div.d;
-    uint8_t *blk = const_cast<uint8_t *>(d.pool_base) + (uint64_t)f * d.frame_bytes + (uint64_t)s * d.block_bytes;
-    if (DT == PKV_E4M3) {
-        if (dd == 0) {
-            const int srow = page - tok_begin / T;
-            reinterpret_cast<float *>(blk)[h] = ks[(size_t)srow * Hkv + h];
-            reinterpret_cast<float *>(blk)[Hkv + h] = vs[(size_t)srow * Hkv + h];
-        }
-        blk += PKV_FP8_HEADER;
-    }
-    const size_t tile = (size_t)T * D * E;
-    uint8_t *kt = blk + (size_t)h * 2 * tile, *vt = kt + tile;
-    const int G = t >> 2, e = t & 3;
-    if (DT == PKV_BF16) {
-        const size_t ko = ((size_t)((dd >> 3) * 16 + t)) * 8 + (dd & 7);
-        const int jp = dd >> 5, half = (dd >> 4) & 1, dl = dd & 15;
-        const size_t vo = ((size_t)((jp * 4 + G) * 16 + dl)) * 8 + half * 4 + e;
-        reinterpret_cast<uint16_t *>(kt)[ko] = reinterpret_cast<const uint16_t *>(k)[idx];
-        reinterpret_cast<uint16_t *>(vt)[vo] = reinterpret_cast<const uint16_t *>(v)[idx];
-    } else {
-        const int c8 = dd >> 3, j = c8 >> 2, Gk = c8 & 3, j2 = j >> 1, hf = j & 1;
-        const size_t ko = ((size_t)((j2 * 4 + Gk) * 16 + t)) * 16 + hf * 8 + (dd & 7);
-        const int jq = dd >> 6, u = (dd >> 4) & 3, dl = dd & 15;
-        const size_t vo = ((size_t)((jq * 4 + G) * 16 + dl)) * 16 + u * 4 + e;
-        kt[ko] = k[idx];
-        vt[vo] = v[idx];
-    }
-}
-
 }  // namespace
-
-hipError_t pkv_launch_kv_write(const AttnDesc &d, int seq, int tok_begin, int n_tok, const void *k, const void *v,
-                               const float *ks, const float *vs, int page_tokens, hipStream_t s) {
-    (void)page_tokens;
-    const int64_t total = (int64_t)n_tok * d.Hkv * d.D;
-    if (total == 0) return hipSuccess;
-    const int32_t *row = d.table + (size_t)seq * d.row_stride;
-    const unsigned blocks = (unsigned)((total + 255) / 256);
-    if (d.dtype == PKV_BF16)
-        hipLaunchKernelGGL(k_kv_write<PKV_BF16>, dim3(blocks), dim3(256), 0, s, d, row, tok_begin, n_tok,
-                           (const uint8_t *)k, (const uint8_t *)v, ks, vs);
-    else
-        hipLaunchKernelGGL(k_kv_write<PKV_E4M3>, dim3(blocks), dim3(256), 0, s, d, row, tok_begin, n_tok,
-                           (const uint8_t *)k, (const uint8_t *)v, ks, vs);
-    return hipGetLastError();
-}
 
 hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t *ev) {
     int items = 0;

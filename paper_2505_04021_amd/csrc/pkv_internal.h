@@ -74,6 +74,8 @@ struct AttnDesc {
     const int32_t *table;       // [B][row_stride]
     const int32_t *ctx_lens;    // [B]
     const int32_t *row_len;     // library table: [max_seqs] blocks reserved per row; NULL for a caller's table
+    const int4 *vmap;           // NULL: row r of the launch is sequence r with one query token (decode);
+                                // else [batch] {sequence, first q/out row, chunk tokens after the tile, tokens in the tile}
     float *out;                 // [B][Hq][D]
     float *ws;                  // split-K partials: two per work item (uncached memory)
     uint32_t *cnt;              // [B][Hkv] arrival counters of the split-K merge, zero between launches
@@ -84,6 +86,7 @@ struct AttnDesc {
     uint32_t max_block_id;      // n_frames * slots
     int32_t batch, row_stride;
     int32_t Hq, Hkv, g, D, dtype;
+    int32_t cols;               // MFMA columns in use per kv head: (query tokens per row) * g, at most 16
     int32_t item_begin;         // first work item of this model in a grouped launch
     int32_t n_items;            // work items (waves) of this model
     int32_t min_share;          // smallest share of pages a wave may get
@@ -117,6 +120,10 @@ hipError_t pkv_launch_release(const PoolDev &p, const ModelDev &m, int seq, Book
 
 hipError_t pkv_launch_kv_write(const AttnDesc &d, int seq, int tok_begin, int n_tok, const void *k, const void *v,
                                const float *ks, const float *vs, int page_tokens, hipStream_t s);
+hipError_t pkv_launch_kv_read(const AttnDesc &d, int seq, int tok_begin, int n_tok, void *k, void *v, float *ks, float *vs,
+                              hipStream_t s);
+// d.batch sequences, d.ctx_lens / d.row_len / d.table as for attention
+hipError_t pkv_launch_kv_append(const AttnDesc &d, const void *k_new, const void *v_new, hipStream_t s);
 // ev: NULL or two events recorded before and after the attention kernel
 hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t *ev);
 hipError_t pkv_launch_stream_read(const void *src, size_t bytes, size_t granule_bytes, uint32_t *sink, hipStream_t s);

@@ -1,0 +1,125 @@
+"""GPU parity of chunked-prefill attention (causal, against the paged cache) with the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from parity import TOL, row_rel_err
+from workloads import gen
+
+pytestmark = pytest.mark.gpu
+
+BF16, E4M3 = 0, 1
+UNEVEN = [1.25, 0.75, 1.1, 0.9, 1.2, 0.8, 1.0, 1.0]
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from paper_2505_04021_amd import PrismKV
+    return PrismKV()
+
+
+class Twin:
+    def __init__(self, gpu, oracle, hq, hkv, d, dtype, ctx, seed=13, poison=True, pool_bytes=64 << 20, max_blocks=64):
+        self.be = (gpu, oracle)
+        self.ctx = np.array(ctx, dtype=np.int32)
+        self.pools, self.models = [], []
+        frame_bytes = 2 << 20
+        perm = gen.free_order(pool_bytes // frame_bytes, gen.generator(seed, 1))
+        for be in self.be:
+            storage = None
+            if be is gpu and poison:          # every byte decodes to NaN until written
+                storage = torch.full((pool_bytes,), 0xFF, dtype=torch.uint8, device="cuda")
+            pool = be.pool_create(pool_bytes, 16, frame_bytes, storage) if be is gpu else be.pool_create(pool_bytes, 16, frame_bytes)
+            assert pool >= 0 and be.pool_seed_free_order(pool, perm) == 0
+            m = be.model_register(pool, hq, hkv, d, dtype, len(ctx), max_blocks)
+            assert m >= 0
+            assert be.balloon_resize(m, pool_bytes // frame_bytes) > 0
+            for upto in range(48, max(max(ctx), 1) + 48, 48):       # interleave the rows' blocks
+                assert be.seq_reserve_batch(m, list(range(len(ctx))), [min(c, upto) for c in ctx]) >= 0
+            self.pools.append(pool)
+            self.models.append(m)
+        for s, c in enumerate(ctx):
+            if c:
+                kv = gen.seq_kv((seed, s), c, hkv, d, dtype, 16)
+                for be, m in zip(self.be, self.models):
+                    assert be.kv_write(m, s, 0, kv["k"], kv["v"], kv.get("k_scale"), kv.get("v_scale")) == c
+
+    def close(self):
+        for be, m, pool in zip(self.be, self.models, self.pools):
+            for s in range(len(self.ctx)):
+                be.seq_release(m, s)
+            assert be.balloon_resize(m, 0) == 0 and be.model_unregister(m) == 0 and be.pool_destroy(pool) == 0
+
+
+CASES = [(13, 5), (6, 6), (9, 1), (300, 37), (64, 64), (33, 17), (16, 16), (100, 0), (257, 256), (48, 32)]
+
+
+@pytest.mark.parametrize("hq,hkv,d,dtype", [
+    (32, 8, 128, BF16), (8, 2, 64, BF16), (64, 8, 128, BF16), (16, 1, 128, BF16), (3, 3, 64, BF16),
+    (12, 4, 64, E4M3), (32, 8, 128, E4M3)])
+def test_prefill_matches_oracle(gpu, oracle, hq, hkv, d, dtype):
+    """Chunks that start at 0, inside and on page boundaries, of 0, 1 and many tokens; tiles of 1 to 16
+    query tokens per MFMA pass (g = 16 ... 1); the pool starts as NaN."""
+    ctx = [c for c, _ in CASES]
+    qlen = [q for _, q in CASES]
+    t = Twin(gpu, oracle, hq, hkv, d, dtype, ctx)
+    q = gen.queries((17, d, hq), sum(qlen), hq, d)
+    rc_o, out_o = oracle.prefill_attention(t.models[1], q, qlen, ctx)
+    assert rc_o == 0
+    for items, share, seg, w in ((0, 0, -1, None), (100000, 1, 0, None), (37, 3, 2, None), (64, 16, 5, UNEVEN)):
+        assert gpu.set_split(items, share) == 0 and gpu.set_segment_cost(seg) == 0 and gpu.set_xcd_weights(w) == 0
+        rc_g, out_g = gpu.prefill_attention(t.models[0], q, qlen, ctx)
+        assert rc_g == 0
+        err = row_rel_err(out_g, out_o)
+        assert err <= TOL[dtype], (items, share, err)
+    gpu.set_split(0, 0)
+    gpu.set_segment_cost(-1)
+    gpu.set_xcd_weights(None)
+    assert gpu.device_errors() == 0
+    # the last query of every chunk is a decode step
+    sel = [i for i, ql in enumerate(qlen) if ql > 0]
+    last = (np.cumsum(qlen) - 1)[sel]
+    rc_d, out_d = gpu.decode_attention(t.models[0], q[last], np.array(ctx, dtype=np.int32)[sel]) if len(sel) == len(ctx) else (0, None)
+    if out_d is not None:
+        assert rc_d == 0 and row_rel_err(out_d, out_o[last]) <= TOL[dtype]
+    t.close()
+
+
+def test_prefill_then_decode_steps(gpu, oracle):
+    """A sequence is prefilled in two chunks, then decoded: append, attend, repeat."""
+    hq, hkv, d = 32, 8, 128
+    total, c1, c2, steps = 90, 50, 40, 6
+    t = Twin(gpu, oracle, hq, hkv, d, BF16, [total + steps, total + steps], poison=False)
+    ctx_full = np.array([total + steps] * 2, dtype=np.int32)
+    for (lo, n) in ((0, c1), (c1, c2)):
+        q = gen.queries((23, lo), 2 * n, hq, d)
+        ctx = np.array([lo + n] * 2, dtype=np.int32)
+        rc_g, g_ = gpu.prefill_attention(t.models[0], q, [n, n], ctx)
+        rc_o, o_ = oracle.prefill_attention(t.models[1], q, [n, n], ctx)
+        assert rc_g == 0 and rc_o == 0 and row_rel_err(g_, o_) <= TOL[BF16]
+    g = gen.generator(29)
+    ctx = np.array([total] * 2, dtype=np.int32)
+    for step in range(steps):
+        kx = gen.to_bf16_bits(torch.randn((2, hkv, d), generator=g))
+        vx = gen.to_bf16_bits(torch.randn((2, hkv, d), generator=g))
+        ctx += 1
+        for be, m in zip(t.be, t.models):
+            assert be.kv_append(m, kx, vx, ctx) == 2
+        q = gen.queries((23, 100 + step), 2, hq, d)
+        rc_g, g_ = gpu.decode_attention(t.models[0], q, ctx)
+        rc_o, o_ = oracle.decode_attention(t.models[1], q, ctx)
+        assert rc_g == 0 and rc_o == 0 and row_rel_err(g_, o_) <= TOL[BF16]
+    assert np.array_equal(ctx, ctx_full)
+    t.close()
+
+
+def test_prefill_arguments(gpu, oracle):
+    t = Twin(gpu, oracle, 8, 2, 64, BF16, [40, 40], poison=False)
+    q = gen.queries((1, 2), 8, 8, 64)
+    qd = torch.from_numpy(q.view(np.int16)).cuda()
+    ctx = torch.tensor([40, 40], dtype=torch.int32, device="cuda")
+    out = torch.empty((8, 8, 64), dtype=torch.float32, device="cuda")
+    assert gpu.prefill_attention_dev(t.models[0], qd, np.array([4, -1], dtype=np.int32), ctx, out) < 0
+    assert gpu.prefill_attention_dev(9999, qd, np.array([4, 4], dtype=np.int32), ctx, out) < 0
+    assert gpu.prefill_attention_dev(t.models[0], qd, np.array([0, 0], dtype=np.int32), ctx, out) == 0
+    t.close()
