@@ -129,6 +129,49 @@ def append_latency(gpu, torch, rep, inputs):
     return res
 
 
+def prefill_leg(gpu, torch):
+    """Chunked prefill on one model of the headline workload's shape (32 q heads, 8 kv heads, head dim
+    128, bf16 cache): 8 sequences with 2048 cached tokens each take a chunk of 512.  Reports device time
+    per call and the rate of useful attention flops (4 * D * heads * visible (query, key) pairs)."""
+    import numpy as np
+    from workloads import gen
+    hq, hkv, d, B, prefix, chunk = 32, 8, 128, 8, 2048, 512
+    pool = gpu.pool_create(8 << 30, 16, 2 << 20)
+    assert pool >= 0 and gpu.pool_seed_free_order(pool, gen.free_order((8 << 30) // (2 << 20), gen.generator(5))) == 0
+    m = gpu.model_register(pool, hq, hkv, d, 0, B, 1024)
+    ctx = prefix + chunk
+    assert m >= 0 and gpu.balloon_resize(m, 1024) == 1024
+    assert gpu.seq_reserve_batch(m, list(range(B)), [ctx] * B) >= 0
+    for s in range(B):
+        kv = gen.seq_kv((3, s), ctx, hkv, d, 0, 16)
+        assert gpu.kv_write(m, s, 0, kv["k"], kv["v"]) == ctx
+    g = torch.Generator(device="cpu"); g.manual_seed(1)
+    q = torch.randn((B * chunk, hq, d), generator=g).to(torch.bfloat16).view(torch.int16).cuda()
+    out = torch.empty((B * chunk, hq, d), dtype=torch.float32, device="cuda")
+    ctxd = torch.full((B,), ctx, dtype=torch.int32, device="cuda")
+    ql = np.full(B, chunk, dtype=np.int32)
+    for _ in range(3):
+        assert gpu.prefill_attention_dev(m, q, ql, ctxd, out) == 0
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        gpu.prefill_attention_dev(m, q, ql, ctxd, out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 20
+    assert gpu.device_errors() == 0
+    pairs = B * sum(prefix + i + 1 for i in range(chunk))
+    flops = 4.0 * d * hq * pairs
+    for s in range(B):
+        gpu.seq_release(m, s)
+    gpu.balloon_resize(m, 0); gpu.model_unregister(m); gpu.pool_destroy(pool)
+    tf = flops / ms / 1e9
+    return {"workload": "8 sequences x (2048 cached + 512 new tokens), 32 q heads / 8 kv heads / head dim 128, bf16 cache",
+            "us_per_call": round(ms * 1e3, 1), "useful_tflops": round(tf, 1), "gflop_per_call": round(flops / 1e9, 1),
+            "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tf / 2500.0, 4)}}
+
+
 def cpu_baseline(rep, seconds):
     """The oracle, as it stands, on the same workload: the same bookkeeping calls and
     KV, decode attention of every model's batch on all host cores, repeated with the
@@ -256,6 +299,7 @@ def main():
     if not args.no_balloon:
         result["balloon_resize"] = balloon_latency(gpu, torch)
         result["kv_append"] = append_latency(gpu, torch, reps[0], inputs[0])
+        result["prefill_attention"] = prefill_leg(gpu, torch)
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(reps[0], args.cpu_seconds)
     for rep in reps:

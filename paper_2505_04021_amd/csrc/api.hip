@@ -746,18 +746,18 @@ int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens
     if (batch == 0) return PKV_OK;
     if (!q || !q_lens || !ctx_lens || !out) return PKV_E_ARG;
     if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return PKV_E_ARG;
-    // rows of the launch: tiles of as many consecutive query tokens as fit the 16 MFMA columns with g heads
+    // A wave takes as many consecutive query tokens as fit the 16 MFMA columns with the g heads of a
+    // kv head; a work-group takes PKV_PREFILL_TILES such tiles and shares the K and V it fetches.
     const int tile = 16 / m->g > 0 ? 16 / m->g : 1;
+    const int group = PKV_PREFILL_TILES * tile;
     std::vector<int4> rows;
-    double units = 0.0;
-    const int seg = g_seg_cost >= 0 ? g_seg_cost : kDefaultSegCost;
     int64_t first = 0;
     for (int s = 0; s < batch; ++s) {
         if (q_lens[s] < 0) return PKV_E_ARG;
-        for (int t0 = 0; t0 < q_lens[s]; t0 += tile) {
-            const int n = q_lens[s] - t0 < tile ? q_lens[s] - t0 : tile;
+        // longest groups of a sequence first: they take the most pages
+        for (int t0 = ((q_lens[s] - 1) / group) * group; q_lens[s] > 0 && t0 >= 0; t0 -= group) {
+            const int n = q_lens[s] - t0 < group ? q_lens[s] - t0 : group;
             rows.push_back(make_int4(s, (int)(first + t0), q_lens[s] - (t0 + n), n));
-            units += ((double)m->row_len[s] + seg + 1) * m->Hkv;
         }
         first += q_lens[s];
         if (first > (int64_t)1 << 24) return PKV_E_RANGE;
@@ -773,12 +773,17 @@ int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens
     }
     // pageable source: the copy has read `rows` when the call returns, and runs in stream order
     HIP_TRY(hipMemcpyAsync(m->vmap, rows.data(), rows.size() * sizeof(int4), hipMemcpyHostToDevice, g_stream));
-    AttnGroup grp;
-    grp.n = 1;
-    int rc = fill_desc(grp.m[0], *m, (int)rows.size(), q, nullptr, 0, ctx_lens, out, 1.0, tile * m->g, units);
-    if (rc) return rc;
-    grp.m[0].vmap = m->vmap;
-    return launch_attention(grp);
+    AttnDesc d{};
+    fill_addressing(d, *m);
+    d.q = (const uint16_t *)q;
+    d.ctx_lens = ctx_lens;
+    d.out = out;
+    d.batch = batch;
+    d.vmap = m->vmap;
+    d.cols = tile * m->g;
+    d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m->D));
+    HIP_TRY(pkv_launch_prefill(d, (int)rows.size(), g_stream));
+    return PKV_OK;
 }
 
 int decode_attention(int model, const void *q, const int32_t *block_table, const int32_t *ctx_lens, float *out) {

@@ -935,6 +935,215 @@ __global__ __launch_bounds__(64, PKV_WAVES) void k_attention(const AttnGroup grp
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Chunked prefill: causal attention of a group of consecutive query tokens against the
+// paged cache (paper Sec. 5.2).  One work-group of four waves per (group, kv head).  Every
+// wave owns one tile of query tokens (16 MFMA columns = tokens x the g heads of the kv
+// head); the K and V tiles of a page pair are fetched once per work-group, one tile per
+// wave, and passed through LDS in the very byte order they have in the block, so each
+// wave reads its MFMA operands back with conflict-free 16-byte LDS loads.  Four tiles
+// share each byte fetched, against one in the decode kernel.  A group is never split:
+// no partials, no merge.  `vmap` lists the groups like the rows of a decode launch, with
+// up to 4 tiles of tokens each.
+// NL x 1 KiB from the pool straight into LDS: lane l's 16 bytes at src + 1024 j land at
+// dst + 1024 j + 16 l (the hardware adds the lane's offset to the LDS base held in M0).
+// Written as assembly so that the compiler neither drains all loads in flight before the
+// next one that targets the same LDS array, nor before LDS reads of another buffer; the
+// waits are counted by hand where the data is needed (s_waitcnt vmcnt).
+template <int NL>
+__device__ __forceinline__ void lds_fill(const uint8_t *src, uint8_t *dst) {
+    // wave-uniform by construction (the wave's tile of the buffer); tell the compiler so
+    const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(size_t)(__attribute__((address_space(3))) uint8_t *)dst);
+    if (NL == 1)
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(base) : "memory", "m0");
+    else if (NL == 2)
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %0, off offset:1024" ::"v"(src),
+                     "s"(base)
+                     : "memory", "m0");
+    else
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off\n\tglobal_load_lds_dwordx4 %0, off offset:1024\n\t"
+                     "global_load_lds_dwordx4 %0, off offset:2048\n\tglobal_load_lds_dwordx4 %0, off offset:3072" ::"v"(src),
+                     "s"(base)
+                     : "memory", "m0");
+    static_assert(NL == 1 || NL == 2 || NL == 4, "tile sizes of 1, 2 or 4 KiB");
+}
+
+constexpr int PF_WAVES = 4;
+constexpr int PF_TILES = 2;     // tiles of query tokens per wave: each operand read from LDS serves both
+constexpr int PF_BUFS = 4;      // page pairs resident in LDS: one in use, three travelling
+static_assert(PF_WAVES * PF_TILES == PKV_PREFILL_TILES, "host and kernel must agree on the group size");
+
+template <int D, int DT>
+__device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, uint8_t *lds1, uint8_t *lds2, uint8_t *lds3) {
+    using TL = Tile<D, DT>;
+    constexpr int PAIR_LDS = 4 * TL::TILE_BYTES;            // K a, V a, K b, V b
+    constexpr int NT = PF_TILES;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int G = lane >> 4, n = lane & 15;
+    const int group = blockIdx.x / d.Hkv, kvh = blockIdx.x - group * d.Hkv;
+    const RowInfo gi = row_info_uniform(d, group);
+    const int tile_tok = d.cols / d.g;                      // query tokens per tile
+    const Column col = column_of(d, n);
+    // tokens the group's last query sees, never beyond what the row holds
+    int L = PKV_CONST(int32_t, d.ctx_lens)[gi.seq] - gi.back;
+    const int cap = PKV_CONST(int32_t, d.row_len)[gi.seq] * T;
+    L = L < 0 ? 0 : (L > cap ? cap : L);
+    L = __builtin_amdgcn_readfirstlane(L);
+    const int n_pages = (L + T - 1) / T, n_pairs = (n_pages + 1) >> 1;
+    const int last_valid = L - (n_pages - 1) * T;
+    const int causal_from = L - (gi.ntok - 1);              // first token some column of the group may not see
+
+    // this wave's tiles of the group: tile u covers the group's tokens [(w * NT + u) * tile_tok, ...)
+    RowInfo ri[NT];
+    bool col_live[NT];
+    int col_lim[NT], tile_lim[NT];
+    bf16x8 qf[NT][TL::NK];
+    State<D, DT> st[NT];
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        const int t0 = (w * NT + u) * tile_tok;
+        ri[u].seq = gi.seq;
+        ri[u].q0 = gi.q0 + t0;
+        ri[u].back = 0;
+        ri[u].ntok = gi.ntok - t0;
+        ri[u].ntok = ri[u].ntok < 0 ? 0 : (ri[u].ntok > tile_tok ? tile_tok : ri[u].ntok);
+        col_live[u] = n < d.cols && col.tok < ri[u].ntok;
+        // the group's last token sees L; token i of the group sees L - (gi.ntok - 1 - i)
+        col_lim[u] = col_live[u] ? L - (gi.ntok - 1 - (t0 + col.tok)) : L;
+        tile_lim[u] = L - (gi.ntok - 1 - (t0 + ri[u].ntok - 1));      // what the tile's last token sees
+        load_q<D>(qf[u], d, ri[u], kvh, lane, col);
+#pragma unroll
+        for (int jt = 0; jt < TL::NV; ++jt) st[u].acc[jt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        st[u].m = -INFINITY;
+        st[u].l = 0.f;
+    }
+
+    const int32_t *row = d.table + (size_t)gi.seq * d.row_stride;
+    uint32_t bad = 0;
+
+    // A pair travels from the pool straight into LDS (no staging registers), NBUF - 1 pairs ahead
+    // of the one being worked on.  wave 0: K of page a, wave 1: V of page a, wave 2: K of page b,
+    // wave 3: V of page b.  Every request issues exactly NL loads per lane (a page past the end is
+    // replaced by the last one, and masked later), so the number of loads in flight tells which
+    // pairs have landed.
+    auto fetch = [&](int pair, uint8_t *buf) {
+        int page = 2 * pair + (w >> 1);
+        page = page < n_pages ? page : n_pages - 1;
+        const int last = d.row_stride - 1;
+        uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[page < last ? page : last]);
+        if (id >= d.max_block_id) {
+            bad |= 1u;
+            id = 0;
+        }
+        const uint32_t f = fastdiv_div(id, d.slots_div);
+        const uint32_t sl = id - f * d.slots_div.d;
+        const uint8_t *blk = d.pool_base + (uint64_t)f * d.frame_bytes + (uint64_t)sl * d.block_bytes +
+                             (DT == PKV_E4M3 ? PKV_FP8_HEADER : 0);
+        const uint8_t *src = blk + ((size_t)kvh * 2 + (w & 1)) * TL::TILE_BYTES + lane * 16;
+        lds_fill<TL::NL>(src, buf + (size_t)w * TL::TILE_BYTES);
+    };
+    // wait until the loads of all but the `ahead` most recent requests have landed
+    auto landed = [&](int ahead) {
+        if (ahead >= 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * TL::NL) : "memory");
+        else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TL::NL) : "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    };
+    auto step = [&](int p, const uint8_t *buf, uint8_t *refill) {
+        const int pa = 2 * p;
+        // wave-uniform: does any token of the pair lie before what this wave's tiles see
+        bool mine[NT];
+        bool any_mine = false;
+#pragma unroll
+        for (int u = 0; u < NT; ++u) {
+            mine[u] = ri[u].ntok > 0 && pa * T < tile_lim[u];
+            any_mine |= mine[u];
+        }
+        // the buffer worked on in the last step is free (barrier): the pair NBUF - 1 ahead goes there
+        if (p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
+        PairRegs<D, DT> r;
+        if (any_mine) {
+            const uint8_t *src = buf + lane * 16;
+#pragma unroll
+            for (int j = 0; j < TL::NL; ++j) {
+                r.a.k[j] = *reinterpret_cast<const u32x4 *>(src + 0 * TL::TILE_BYTES + j * 1024);
+                r.a.v[j] = *reinterpret_cast<const u32x4 *>(src + 1 * TL::TILE_BYTES + j * 1024);
+                r.b.k[j] = *reinterpret_cast<const u32x4 *>(src + 2 * TL::TILE_BYTES + j * 1024);
+                r.b.v[j] = *reinterpret_cast<const u32x4 *>(src + 3 * TL::TILE_BYTES + j * 1024);
+            }
+            r.a.sk = r.a.sv = r.b.sk = r.b.sv = 1.f;
+            if (DT == PKV_E4M3) {
+                const int last = d.row_stride - 1;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int page = pa + h;
+                    const bool live = page < n_pages;
+                    uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[page < last ? page : last]);
+                    if (id >= d.max_block_id) id = 0;
+                    const uint32_t f = fastdiv_div(id, d.slots_div);
+                    const uint32_t sl = id - f * d.slots_div.d;
+                    const float *hdr = reinterpret_cast<const float *>(d.pool_base + (uint64_t)f * d.frame_bytes +
+                                                                       (uint64_t)sl * d.block_bytes);
+                    float sk = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[kvh])));
+                    float sv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[d.Hkv + kvh])));
+                    if (!live) sk = sv = 0.f;
+                    if (h == 0) { r.a.sk = sk; r.a.sv = sv; } else { r.b.sk = sk; r.b.sv = sv; }
+                }
+            }
+        }
+        const int va = pa == n_pages - 1 ? last_valid : T;
+        const int vb = pa + 1 < n_pages ? (pa + 1 == n_pages - 1 ? last_valid : T) : 0;
+#pragma unroll
+        for (int u = 0; u < NT; ++u)
+            if (mine[u])
+                process_pair<D, DT>(st[u], r, qf[u], d.scale_log2, va, vb, G, col_lim[u] - pa * T, (pa + 2) * T > causal_from);
+        // the next pair must have landed before anybody reads it; pairs requested after it may still travel
+        const int newest = p + PF_BUFS - 1 < n_pairs - 1 ? p + PF_BUFS - 1 : n_pairs - 1;
+        landed(newest - (p + 1));
+        __builtin_amdgcn_s_barrier();      // every read of this step's buffer has been consumed by then
+    };
+
+    // prologue: the first NBUF - 1 pairs
+    if (n_pairs > 0) fetch(0, lds0);
+    if (n_pairs > 1) fetch(1, lds1);
+    if (n_pairs > 2) fetch(2, lds2);
+    landed((n_pairs < PF_BUFS - 1 ? n_pairs : PF_BUFS - 1) - 1);
+    __builtin_amdgcn_s_barrier();
+    for (int p = 0; p < n_pairs; p += PF_BUFS) {
+        step(p, lds0, lds3);
+        if (p + 1 < n_pairs) step(p + 1, lds1, lds0);
+        if (p + 2 < n_pairs) step(p + 2, lds2, lds1);
+        if (p + 3 < n_pairs) step(p + 3, lds3, lds2);
+    }
+
+#pragma unroll
+    for (int u = 0; u < NT; ++u) {
+        if (col_live[u]) {
+            float *out_row = d.out + ((size_t)(ri[u].q0 + col.tok) * d.Hq + kvh * d.g + col.head) * D;
+            float l = st[u].l;
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            const float inv = l > 0.f ? 1.0f / l : 0.f;          // no visible token: the row is defined as zero
+#pragma unroll
+            for (int jt = 0; jt < TL::NV; ++jt)
+                *reinterpret_cast<f32x4 *>(out_row + 16 * jt + 4 * G) = st[u].acc[jt] * inv;
+        }
+    }
+    if (bad && lane == 0) atomicOr(d.err, 1u);
+}
+
+__global__ __launch_bounds__(64 * PF_WAVES, 2) void k_prefill(const AttnDesc d) {
+    // one array per buffer: distinct objects, so that a read of one buffer is not taken to depend
+    // on the loads still travelling into the others; each holds a pair of the largest tiles (bf16, D = 128)
+    __shared__ __align__(16) uint8_t lds0[4 * T * 128 * 2], lds1[4 * T * 128 * 2], lds2[4 * T * 128 * 2], lds3[4 * T * 128 * 2];
+    if (d.dtype == PKV_BF16) {
+        if (d.D == 128) prefill_group<128, PKV_BF16>(d, lds0, lds1, lds2, lds3);
+        else prefill_group<64, PKV_BF16>(d, lds0, lds1, lds2, lds3);
+    } else {
+        if (d.D == 128) prefill_group<128, PKV_E4M3>(d, lds0, lds1, lds2, lds3);
+        else prefill_group<64, PKV_E4M3>(d, lds0, lds1, lds2, lds3);
+    }
+}
+
 // Read ceilings for comparison.  granule == 0: plain streaming read of the buffer,
 // 16 bytes per lane.  granule > 0 (a power-of-two number of KiB): each wave reads
 // whole granules of that size picked in a scrambled order, which is the access pattern
@@ -984,6 +1193,12 @@ hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t 
     if (e != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
     return hipSuccess;
+}
+
+hipError_t pkv_launch_prefill(const AttnDesc &d, int n_groups, hipStream_t s) {
+    if (n_groups == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_prefill, dim3((unsigned)(n_groups * d.Hkv)), dim3(64 * PF_WAVES), 0, s, d);
+    return hipGetLastError();
 }
 
 hipError_t pkv_launch_stream_read(const void *src, size_t bytes, size_t granule_bytes, uint32_t *sink, hipStream_t s) {
