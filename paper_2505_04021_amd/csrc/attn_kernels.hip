@@ -226,13 +226,12 @@ __device__ __forceinline__ void split_p(const float *p, u32x2 &hi, u32x2 &lo) {
 
 // One online-softmax step over the 32 tokens of a page pair.  valid_a is 1..16,
 // valid_b 0..16 (0: the pair has no second page; its registers hold zeros).
-template <int D, int DT>
+template <int D, int DT, bool CAUSAL>
 __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D, DT> &r, const bf16x8 *qf,
-                                             float scale_log2, int valid_a, int valid_b, int G, int lim_a, bool causal) {
+                                             float scale_log2, int valid_a, int valid_b, int G, int lim_a = 0,
+                                             bool causal = false) {
     using TL = Tile<D, DT>;
-    // lim_a: how many tokens of page a this lane's column may see (any integer; page b: lim_a - 16);
-    // causal: some column's limit falls inside the pair (wave-uniform)
-    const bool tail = valid_a < T || valid_b < T || causal;
+    const bool tail = valid_a < T || valid_b < T || (CAUSAL && causal);
     f32x4 sa = qk_page<D, DT>(r.a, qf);
     f32x4 sb = qk_page<D, DT>(r.b, qf);
     const float sca = DT == PKV_E4M3 ? scale_log2 * r.a.sk : scale_log2;
@@ -243,7 +242,8 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
         s[i] = sa[i] * sca;
         s[4 + i] = sb[i] * scb;
         if (tail) {                                        // select, so a NaN logit of a dead token cannot leak
-            const int la = lim_a < valid_a ? lim_a : valid_a, lb = lim_a - T < valid_b ? lim_a - T : valid_b;
+            const int la = CAUSAL && lim_a < valid_a ? lim_a : valid_a;
+            const int lb = CAUSAL && lim_a - T < valid_b ? lim_a - T : valid_b;
             if (4 * G + i >= la) s[i] = -INFINITY;
             if (4 * G + i >= lb) s[4 + i] = -INFINITY;
         }
@@ -253,14 +253,14 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
     const float m_new = fmaxf(st.m, mx);
     if (__any(m_new > st.m)) {            // wave-uniform: rescale only when some column's max moved
         // a column that has seen no token yet (prefill tiles only) has m = -inf on both sides
-        const float alpha = m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
+        const float alpha = CAUSAL && m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
         st.l *= alpha;
 #pragma unroll
         for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] *= alpha;
         st.m = m_new;
     }
     float p[8];
-    const float m_ref = st.m == -INFINITY ? 0.f : st.m;     // then every s is -inf and every p is 0
+    const float m_ref = CAUSAL && st.m == -INFINITY ? 0.f : st.m;     // then every s is -inf and every p is 0
 #pragma unroll
     for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
     st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
@@ -344,16 +344,8 @@ __device__ __forceinline__ RowInfo row_info_uniform(const AttnDesc &d, int row) 
                    __builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, v)[2]), __builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, v)[3])};
 }
 
-// Pages the work split plans for a row: the tokens its last query sees, rounded up to
-// pages, never beyond what the sequence's table row holds.
-__device__ __forceinline__ int ctx_clamped(const AttnDesc &d, int row) {
-    int seq = row, back = 0;
-    if (d.vmap) {
-        const int4 v = d.vmap[row];
-        seq = v.x;
-        back = v.z;
-    }
-    int L = PKV_CONST(int32_t, d.ctx_lens)[seq] - back;
+__device__ __forceinline__ int ctx_clamped(const AttnDesc &d, int seq) {
+    int L = PKV_CONST(int32_t, d.ctx_lens)[seq];
     const int cap = (d.row_len ? PKV_CONST(int32_t, d.row_len)[seq] : d.row_stride) * T;
     return L < 0 ? 0 : (L > cap ? cap : L);
 }
@@ -811,8 +803,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                     const int pa = cur.pb + i;                                  // absolute page of the pair's first half
                     const int va = pa == cur.n_pages - 1 ? last_valid : T;
                     const int vb = i + 1 < n_live ? (pa + 1 == cur.n_pages - 1 ? last_valid : T) : 0;
-                    process_pair<D, DT>(st, ring[r], qf, d.scale_log2, va, vb, G, col_lim - pa * T,
-                                        (pa + 2) * T > causal_from);
+                    process_pair<D, DT, false>(st, ring[r], qf, d.scale_log2, va, vb, G);
 #if PKV_PRIO
                     prio_done += 2;
 #endif
@@ -1095,7 +1086,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
 #pragma unroll
         for (int u = 0; u < NT; ++u)
             if (mine[u])
-                process_pair<D, DT>(st[u], r, qf[u], d.scale_log2, va, vb, G, col_lim[u] - pa * T, (pa + 2) * T > causal_from);
+                process_pair<D, DT, true>(st[u], r, qf[u], d.scale_log2, va, vb, G, col_lim[u] - pa * T, (pa + 2) * T > causal_from);
         // the next pair must have landed before anybody reads it; pairs requested after it may still travel
         const int newest = p + PF_BUFS - 1 < n_pairs - 1 ? p + PF_BUFS - 1 : n_pairs - 1;
         landed(newest - (p + 1));

@@ -74,8 +74,8 @@ struct AttnDesc {
     const int32_t *table;       // [B][row_stride]
     const int32_t *ctx_lens;    // [B]
     const int32_t *row_len;     // library table: [max_seqs] blocks reserved per row; NULL for a caller's table
-    const int4 *vmap;           // NULL: row r of the launch is sequence r with one query token (decode);
-                                // else [batch] {sequence, first q/out row, chunk tokens after the tile, tokens in the tile}
+    const int4 *vmap;           // prefill launches only: [groups] {sequence, first q/out row, chunk tokens after the
+                                // group, tokens in the group}
     float *out;                 // [B][Hq][D]
     float *ws;                  // split-K partials: two per work item (uncached memory)
     uint32_t *cnt;              // [B][Hkv] arrival counters of the split-K merge, zero between launches
