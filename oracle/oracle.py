@@ -54,6 +54,7 @@ def _load():
         "orc_e4m3_decode": (C.c_double, [C.c_uint8]),
         "orc_e4m3_encode": (C.c_uint8, [C.c_float]),
         "orc_kv_append": (i, [i, i, vp, vp, vp]),
+        "orc_kv_append_chunk": (i, [i, i, vp, vp, vp, vp]),
         "orc_kv_read": (i, [i, i, i, i, vp, vp, vp, vp]),
         "orc_prefill_attention": (i, [i, i, vp, vp, vp, i, vp, vp]),
         "orc_num_threads": (i, []),
@@ -146,6 +147,14 @@ class Oracle:
         ctx_lens = _arr(ctx_lens, np.int32)
         assert k_new.shape == v_new.shape == (ctx_lens.size, hkv, d)
         return self.lib.orc_kv_append(model, ctx_lens.size, _ptr(k_new), _ptr(v_new), _ptr(ctx_lens))
+
+    def kv_append_chunk(self, model, k_new, v_new, q_lens, ctx_lens):
+        """k_new, v_new: uint16 [sum q_lens][Hkv][D]; sequence s writes tokens ctx_lens[s] - q_lens[s] .. ctx_lens[s] - 1."""
+        _, hkv, d, _ = self._shape[model]
+        k_new, v_new = _arr(k_new, np.uint16), _arr(v_new, np.uint16)
+        q_lens, ctx_lens = _arr(q_lens, np.int32), _arr(ctx_lens, np.int32)
+        assert k_new.shape == v_new.shape == (int(q_lens.sum()), hkv, d)
+        return self.lib.orc_kv_append_chunk(model, ctx_lens.size, _ptr(k_new), _ptr(v_new), _ptr(q_lens), _ptr(ctx_lens))
 
     def kv_read(self, model, seq, tok_begin, n_tok):
         """-> (code, k, v, k_scale, v_scale): elements [n_tok][Hkv][D], scales [n_tok][Hkv] (None for bf16)."""

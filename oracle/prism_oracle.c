@@ -483,6 +483,23 @@ static void append_row_e4m3(const model_t *m, const pool_t *p, uint8_t *blk, int
     }
 }
 
+/* one token of sequence s at index tok; kx, vx: [Hkv][D] */
+static void append_token(const model_t *m, const pool_t *p, int s, int tok, const uint16_t *kx, const uint16_t *vx) {
+    int slot = tok % p->T;
+    int32_t id = m->rows[(size_t)s * m->max_blocks + tok / p->T];
+    uint8_t *blk = p->mem + block_addr(m, p, id);
+    for (int h = 0; h < m->Hkv; ++h) {
+        const uint16_t *kh = kx + (size_t)h * m->D, *vh = vx + (size_t)h * m->D;
+        if (m->dtype == ORC_BF16) {
+            memcpy(blk + elem_index(m, p, h, 0, slot, 0) * 2, kh, (size_t)m->D * 2);
+            memcpy(blk + elem_index(m, p, h, 1, slot, 0) * 2, vh, (size_t)m->D * 2);
+        } else {
+            append_row_e4m3(m, p, blk, h, 0, slot, kh);
+            append_row_e4m3(m, p, blk, h, 1, slot, vh);
+        }
+    }
+}
+
 int orc_kv_append(int model, int batch, const uint16_t *k_new, const uint16_t *v_new, const int32_t *ctx_lens) {
     model_t *m = get_model(model);
     if (!m) return ORC_E_HANDLE;
@@ -492,23 +509,34 @@ int orc_kv_append(int model, int batch, const uint16_t *k_new, const uint16_t *v
     pool_t *p = &g_pools[m->pool];
     for (int s = 0; s < batch; ++s)
         if (ctx_lens[s] < 1 || blocks_for(p, ctx_lens[s]) > m->row_len[s]) return ORC_E_RANGE;
-    for (int s = 0; s < batch; ++s) {
-        int tok = ctx_lens[s] - 1, slot = tok % p->T;
-        int32_t id = m->rows[(size_t)s * m->max_blocks + tok / p->T];
-        uint8_t *blk = p->mem + block_addr(m, p, id);
-        for (int h = 0; h < m->Hkv; ++h) {
-            const uint16_t *kx = k_new + ((size_t)s * m->Hkv + h) * m->D;
-            const uint16_t *vx = v_new + ((size_t)s * m->Hkv + h) * m->D;
-            if (m->dtype == ORC_BF16) {
-                memcpy(blk + elem_index(m, p, h, 0, slot, 0) * 2, kx, (size_t)m->D * 2);
-                memcpy(blk + elem_index(m, p, h, 1, slot, 0) * 2, vx, (size_t)m->D * 2);
-            } else {
-                append_row_e4m3(m, p, blk, h, 0, slot, kx);
-                append_row_e4m3(m, p, blk, h, 1, slot, vx);
-            }
-        }
-    }
+    for (int s = 0; s < batch; ++s)
+        append_token(m, p, s, ctx_lens[s] - 1, k_new + (size_t)s * m->Hkv * m->D, v_new + (size_t)s * m->Hkv * m->D);
     return batch;
+}
+
+/* The write path of a prefill chunk: sequence s appends its q_lens[s] new tokens, packed one
+ * sequence after the other in k_new, v_new [sum q_lens][Hkv][D], at the indices
+ * ctx_lens[s] - q_lens[s] .. ctx_lens[s] - 1.  Defined as orc_kv_append applied token by
+ * token in order, so a cache filled in chunks equals one filled a token at a time. */
+int orc_kv_append_chunk(int model, int batch, const uint16_t *k_new, const uint16_t *v_new, const int32_t *q_lens,
+                        const int32_t *ctx_lens) {
+    model_t *m = get_model(model);
+    if (!m) return ORC_E_HANDLE;
+    if (batch < 0 || batch > m->max_seqs) return ORC_E_RANGE;
+    if (batch == 0) return 0;
+    if (!k_new || !v_new || !q_lens || !ctx_lens) return ORC_E_ARG;
+    pool_t *p = &g_pools[m->pool];
+    long total = 0;
+    for (int s = 0; s < batch; ++s) {
+        if (q_lens[s] < 0) return ORC_E_ARG;
+        if (q_lens[s] > 0 && (ctx_lens[s] < q_lens[s] || blocks_for(p, ctx_lens[s]) > m->row_len[s])) return ORC_E_RANGE;
+        total += q_lens[s];
+    }
+    size_t row = 0;
+    for (int s = 0; s < batch; ++s)
+        for (int i = 0; i < q_lens[s]; ++i, ++row)
+            append_token(m, p, s, ctx_lens[s] - q_lens[s] + i, k_new + row * m->Hkv * m->D, v_new + row * m->Hkv * m->D);
+    return (int)total;
 }
 
 /* Read tokens back in the logical layout of orc_kv_write: k_out, v_out [n_tok][Hkv][D]

@@ -70,6 +70,10 @@ int orc_kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, co
  * s < batch; k_new, v_new bf16 bit patterns [batch][Hkv][D].  e4m3 models quantise
  * with a running per-(block, kv head) scale (rule stated at the definition). */
 int orc_kv_append(int model, int batch, const uint16_t *k_new, const uint16_t *v_new, const int32_t *ctx_lens);
+/* a prefill chunk: q_lens[s] tokens per sequence, packed [sum q_lens][Hkv][D], written at
+ * ctx_lens[s] - q_lens[s] .. ctx_lens[s] - 1; equals orc_kv_append token by token. */
+int orc_kv_append_chunk(int model, int batch, const uint16_t *k_new, const uint16_t *v_new, const int32_t *q_lens,
+                        const int32_t *ctx_lens);
 
 /* tokens back in the logical layout of orc_kv_write; e4m3 only: scales per token
  * [n_tok][Hkv] (the scale of the token's block). */

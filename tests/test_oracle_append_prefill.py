@@ -208,3 +208,49 @@ def test_prefill_matches_dense_causal_attention(oracle, dtype):
     # a chunk longer than the cache is refused
     assert o.prefill_attention(m, q, [4, 7, 1], ctx)[0] < 0
     drop(o, pool, m, 3)
+
+
+@pytest.mark.parametrize("dtype", [BF16, E4M3])
+def test_chunk_append_equals_token_by_token(oracle, dtype):
+    """Two models on one pool get the same tokens, one in chunks, one a token at a time through
+    kv_append (pinned above); a second sequence in the chunk calls checks the packing."""
+    o = oracle
+    T, hq, hkv, d = 4, 4, 2, 8
+    block = 2 * T * hkv * d * (2 if dtype == BF16 else 1) + (128 if dtype == E4M3 else 0)
+    pool = o.pool_create(1 << 20, T, 4 * block)
+    ma = o.model_register(pool, hq, hkv, d, dtype, 2, 16)
+    mb = o.model_register(pool, hq, hkv, d, dtype, 1, 16)
+    mc = o.model_register(pool, hq, hkv, d, dtype, 1, 16)
+    for m in (ma, mb, mc):
+        assert o.balloon_resize(m, 16) == 16
+    g = gen.generator(41, dtype)
+    ctx = np.zeros(2, dtype=np.int32)
+    for ql in ([3, 0], [6, 5], [1, 9], [0, 2]):
+        ql = np.array(ql, dtype=np.int32)
+        n = int(ql.sum())
+        mag = torch.exp(torch.randn((n, 1, 1), generator=g))
+        kx = gen.to_bf16_bits(torch.randn((n, hkv, d), generator=g) * mag)
+        vx = gen.to_bf16_bits(torch.randn((n, hkv, d), generator=g) * mag)
+        new_ctx = ctx + ql
+        for s in range(2):
+            assert o.seq_reserve(ma, s, int(new_ctx[s])) >= 0
+        assert o.seq_reserve(mb, 0, int(new_ctx[0])) >= 0 and o.seq_reserve(mc, 0, int(new_ctx[1])) >= 0
+        assert o.kv_append_chunk(ma, kx, vx, ql, new_ctx) == n
+        row = 0
+        for s, m1 in ((0, mb), (1, mc)):                 # sequence s of the chunked model = the one sequence of m1
+            for i in range(int(ql[s])):
+                assert o.kv_append(m1, kx[row:row + 1], vx[row:row + 1], [int(ctx[s]) + i + 1]) == 1
+                row += 1
+        ctx = new_ctx
+        for s, m1 in ((0, mb), (1, mc)):
+            if ctx[s]:
+                a, b = o.kv_read(ma, s, 0, int(ctx[s])), o.kv_read(m1, 0, 0, int(ctx[s]))
+                assert np.array_equal(a[1], b[1]) and np.array_equal(a[2], b[2])
+                if dtype == E4M3:
+                    assert np.array_equal(a[3], b[3]) and np.array_equal(a[4], b[4])
+    assert o.kv_append_chunk(ma, kx[:1], vx[:1], [1, 0], [0, 5]) < 0          # a chunk longer than the cache
+    for m, n_seq in ((ma, 2), (mb, 1), (mc, 1)):
+        for s in range(n_seq):
+            o.seq_release(m, s)
+        assert o.balloon_resize(m, 0) == 0 and o.model_unregister(m) == 0
+    assert o.pool_destroy(pool) == 0
