@@ -153,6 +153,16 @@ int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const 
  * rows.  Enqueues only. */
 int kv_append(int model, int batch, const void *k_new, const void *v_new, const int32_t *ctx_lens);
 
+/* The write path of a prefill chunk: sequence s < batch appends its q_lens[s] new tokens,
+ * packed one sequence after the other in k_new, v_new (dev, bf16 [sum q_lens][kv_heads]
+ * [head_dim]), at the indices ctx_lens[s] - q_lens[s] .. ctx_lens[s] - 1.  The result is that
+ * of kv_append applied token by token in order (so a cache filled in chunks equals one
+ * filled a token at a time, e4m3 codes and scales included).  q_lens: HOST int32 [batch];
+ * ctx_lens: dev int32 [batch].  Returns sum q_lens.  Enqueues only (plus a small
+ * host-to-device copy of the chunk list); errors as kv_append. */
+int kv_append_chunk(int model, int batch, const void *k_new, const void *v_new, const int32_t *q_lens,
+                    const int32_t *ctx_lens);
+
 /* Tokens [tok_begin, tok_begin + n_tok) of a sequence back in the logical layout of
  * kv_write: k_out, v_out dev [n_tok][kv_heads][head_dim] (bf16 values or e4m3 codes);
  * e4m3 only: k_scale_out, v_scale_out dev fp32 [n_tok][kv_heads], the scale of the

@@ -56,6 +56,7 @@ def _load():
         "model_block_table": (vp, [i, C.POINTER(i)]),
         "kv_write": (i, [i, i, i, i, vp, vp, vp, vp]),
         "kv_append": (i, [i, i, vp, vp, vp]),
+        "kv_append_chunk": (i, [i, i, vp, vp, vp, vp]),
         "kv_read": (i, [i, i, i, i, vp, vp, vp, vp]),
         "model_set_batch": (i, [i, i, i]),
         "decode_attention": (i, [i, vp, vp, vp, vp]),
@@ -77,7 +78,7 @@ EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_spl
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
-           "seq_release", "model_block_table", "kv_write", "kv_append", "kv_read", "model_set_batch", "decode_attention",
+           "seq_release", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
            "decode_attention_ex", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats"]
 
 
@@ -244,6 +245,22 @@ class PrismKV:
         ctx = self._dev(np.ascontiguousarray(ctx_lens, dtype=np.int32))
         assert tuple(k_new.shape) == (ctx.numel(), hkv, d) and k_new.shape == v_new.shape
         rc = self.kv_append_dev(model, k_new, v_new, ctx)
+        self.torch.cuda.current_stream(self.device).synchronize()
+        return rc
+
+    def kv_append_chunk_dev(self, model, k_new, v_new, q_lens, ctx_lens):
+        """k_new, v_new, ctx_lens: device tensors; q_lens: host int32 numpy array.  Only enqueues."""
+        q_lens = np.ascontiguousarray(q_lens, dtype=np.int32)
+        return self.lib.kv_append_chunk(model, q_lens.size, self._p(k_new), self._p(v_new),
+                                        q_lens.ctypes.data_as(C.c_void_p), self._p(ctx_lens))
+
+    def kv_append_chunk(self, model, k_new, v_new, q_lens, ctx_lens):
+        _, hkv, d, _ = self._shape[model]
+        q_lens = np.ascontiguousarray(q_lens, dtype=np.int32)
+        k_new, v_new = self._dev(np.ascontiguousarray(k_new)), self._dev(np.ascontiguousarray(v_new))
+        ctx = self._dev(np.ascontiguousarray(ctx_lens, dtype=np.int32))
+        assert tuple(k_new.shape) == (int(q_lens.sum()), hkv, d) and k_new.shape == v_new.shape
+        rc = self.kv_append_chunk_dev(model, k_new, v_new, q_lens, ctx)
         self.torch.cuda.current_stream(self.device).synchronize()
         return rc
 

@@ -693,6 +693,41 @@ int kv_read(int model, int seq, int tok_begin, int n_tok, void *k_out, void *v_o
     return n_tok;
 }
 
+int kv_append_chunk(int model, int batch, const void *k_new, const void *v_new, const int32_t *q_lens,
+                    const int32_t *ctx_lens) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (batch < 0 || batch > m->dev.max_seqs) return PKV_E_RANGE;
+    if (batch == 0) return 0;
+    if (!k_new || !v_new || !q_lens || !ctx_lens) return PKV_E_ARG;
+    std::vector<int4> rows((size_t)batch);
+    int64_t first = 0;
+    for (int s = 0; s < batch; ++s) {
+        if (q_lens[s] < 0) return PKV_E_ARG;
+        rows[s] = make_int4((int)first, q_lens[s], 0, 0);
+        first += q_lens[s];
+        if (first > (int64_t)1 << 24) return PKV_E_RANGE;
+    }
+    if (first == 0) return 0;
+    if (rows.size() > m->vmap_cap) {
+        HIP_TRY(hipStreamSynchronize(g_stream));
+        (void)hipFree(m->vmap);
+        m->vmap = nullptr;
+        m->vmap_cap = 0;
+        HIP_TRY(hipMalloc((void **)&m->vmap, rows.size() * 2 * sizeof(int4)));
+        m->vmap_cap = rows.size() * 2;
+    }
+    // pageable source: the copy has read `rows` when the call returns, and runs in stream order
+    HIP_TRY(hipMemcpyAsync(m->vmap, rows.data(), rows.size() * sizeof(int4), hipMemcpyHostToDevice, g_stream));
+    AttnDesc d{};
+    fill_addressing(d, *m);
+    d.batch = batch;
+    d.ctx_lens = ctx_lens;
+    d.vmap = m->vmap;
+    HIP_TRY(pkv_launch_kv_append(d, k_new, v_new, g_stream));
+    return (int)first;
+}
+
 int kv_append(int model, int batch, const void *k_new, const void *v_new, const int32_t *ctx_lens) {
     Model *m = get_model(model);
     if (!m) return PKV_E_HANDLE;

@@ -155,43 +155,60 @@ __device__ __forceinline__ void append_row_e4m3(uint8_t *tile, float *scale_p, i
     }
 }
 
-// kv_append: one wave per (sequence, kv head) writes token ctx_lens[seq] - 1.
-// k_new, v_new: bf16 [batch][Hkv][D].  A context length outside 1 .. what the row holds
-// is skipped and reported through the device error flags (bit 1).
+// kv_append: one wave per (sequence, kv head).  Without a chunk list it writes the token with
+// index ctx_lens[seq] - 1 from row `seq` of k_new / v_new (bf16 [batch][Hkv][D]).  With one
+// (d.vmap: per sequence {first row, tokens, -, -}) it writes the sequence's `tokens` new tokens
+// at indices ctx_lens[seq] - tokens .. ctx_lens[seq] - 1 from consecutive rows, in order, each
+// exactly as a single append would (the e4m3 scale rule is sequential by definition).
+// A context length outside what the row holds is skipped and reported through the device
+// error flags (bit 1).
 template <int DT>
 __global__ __launch_bounds__(64) void k_kv_append(AttnDesc d, const uint16_t *k_new, const uint16_t *v_new) {
     const int lane = threadIdx.x;
     const int seq = blockIdx.x / d.Hkv, h = blockIdx.x - seq * d.Hkv;
     const int D = d.D;
+    int first_row = seq, n_new = 1;
+    if (d.vmap) {
+        const int4 e = d.vmap[seq];
+        first_row = e.x;
+        n_new = e.y;
+        if (n_new == 0) return;
+    }
     const int ctx = d.ctx_lens[seq];
     const int cap = d.row_len[seq] * PKV_T;
-    if (ctx < 1 || ctx > cap) {
+    if (ctx < n_new || ctx < 1 || ctx > cap) {
         if (lane == 0) atomicOr(d.err, 2u);
         return;
     }
-    const int tok = ctx - 1, page = tok / PKV_T, slot = tok % PKV_T;
-    const uint32_t id = (uint32_t)d.table[(size_t)seq * d.row_stride + page];
-    if (id >= d.max_block_id) {
-        if (lane == 0) atomicOr(d.err, 1u);
-        return;
-    }
-    uint8_t *blk = block_ptr(d, id);
-    const uint16_t *kx = k_new + ((size_t)seq * d.Hkv + h) * D;
-    const uint16_t *vx = v_new + ((size_t)seq * d.Hkv + h) * D;
-    if (DT == PKV_BF16) {
-        const size_t tile = (size_t)PKV_T * D * 2;
-        uint16_t *kt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile);
-        uint16_t *vt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile + tile);
-        for (int dd = lane; dd < D; dd += 64) {
-            kt[k_elem_off<PKV_BF16>(slot, dd)] = kx[dd];
-            vt[v_elem_off<PKV_BF16>(slot, dd)] = vx[dd];
+    for (int i = 0; i < n_new; ++i) {
+        const int tok = ctx - n_new + i, page = tok / PKV_T, slot = tok % PKV_T;
+        const uint32_t id = (uint32_t)d.table[(size_t)seq * d.row_stride + page];
+        if (id >= d.max_block_id) {
+            if (lane == 0) atomicOr(d.err, 1u);
+            return;
         }
-    } else {
-        float *hdr = reinterpret_cast<float *>(blk);
-        const size_t tile = (size_t)PKV_T * D;
-        uint8_t *kt = blk + PKV_FP8_HEADER + (size_t)h * 2 * tile, *vt = kt + tile;
-        append_row_e4m3<false>(kt, hdr + h, slot, D, kx, lane);
-        append_row_e4m3<true>(vt, hdr + d.Hkv + h, slot, D, vx, lane);
+        uint8_t *blk = block_ptr(d, id);
+        const uint16_t *kx = k_new + ((size_t)(first_row + i) * d.Hkv + h) * D;
+        const uint16_t *vx = v_new + ((size_t)(first_row + i) * d.Hkv + h) * D;
+        if (DT == PKV_BF16) {
+            const size_t tile = (size_t)PKV_T * D * 2;
+            uint16_t *kt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile);
+            uint16_t *vt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile + tile);
+            for (int dd = lane; dd < D; dd += 64) {
+                kt[k_elem_off<PKV_BF16>(slot, dd)] = kx[dd];
+                vt[v_elem_off<PKV_BF16>(slot, dd)] = vx[dd];
+            }
+        } else {
+            float *hdr = reinterpret_cast<float *>(blk);
+            const size_t tile = (size_t)PKV_T * D;
+            uint8_t *kt = blk + PKV_FP8_HEADER + (size_t)h * 2 * tile, *vt = kt + tile;
+            append_row_e4m3<false>(kt, hdr + h, slot, D, kx, lane);
+            append_row_e4m3<true>(vt, hdr + d.Hkv + h, slot, D, vx, lane);
+            // the next token of the chunk may read this block's codes and scale (written by other lanes)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
     }
 }
 

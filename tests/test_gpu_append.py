@@ -140,3 +140,36 @@ def test_append_bad_context_is_reported_not_written(gpu, oracle):
     assert np.array_equal(before[1], after[1]) and np.array_equal(before[2], after[2])
     assert oracle.kv_append(t.models[1], kx, kx, np.array([0, 33], dtype=np.int32)) < 0
     t.close()
+
+
+@pytest.mark.parametrize("hq,hkv,d,dtype", [(32, 8, 128, BF16), (32, 8, 128, E4M3), (12, 4, 64, E4M3)])
+def test_chunk_append_then_prefill(gpu, oracle, hq, hkv, d, dtype):
+    """Prefill chunks are written with kv_append_chunk (stored values, e4m3 codes and scales equal the
+    oracle's bit for bit), attended with prefill_attention, then a decode step follows."""
+    start = [0, 7, 16, 40]
+    chunks = [[33, 0, 16, 5], [1, 20, 31, 0]]
+    t = Twin(gpu, oracle, hq, hkv, d, dtype, start, [c + 70 for c in start])
+    g = gen.generator(57, d, dtype)
+    for ql in chunks:
+        ql = np.array(ql, dtype=np.int32)
+        n = int(ql.sum())
+        mag = torch.exp(torch.randn((n, 1, 1), generator=g))
+        kx = gen.to_bf16_bits(torch.randn((n, hkv, d), generator=g) * mag)
+        vx = gen.to_bf16_bits(torch.randn((n, hkv, d), generator=g) * mag)
+        t.ctx += ql
+        for be, m in zip(t.be, t.models):
+            assert be.kv_append_chunk(m, kx, vx, ql, t.ctx) == n
+        t.compare_cache()
+        q = gen.queries((57, n), n, hq, d)
+        rc_g, out_g = gpu.prefill_attention(t.models[0], q, ql, t.ctx)
+        rc_o, out_o = oracle.prefill_attention(t.models[1], q, ql, t.ctx)
+        assert rc_g == 0 and rc_o == 0 and row_rel_err(out_g, out_o) <= TOL[dtype]
+    q = gen.queries((57, 1), len(start), hq, d)
+    rc_g, out_g = gpu.decode_attention(t.models[0], q, t.ctx)
+    rc_o, out_o = oracle.decode_attention(t.models[1], q, t.ctx)
+    assert rc_g == 0 and rc_o == 0 and row_rel_err(out_g, out_o) <= TOL[dtype]
+    assert gpu.device_errors() == 0
+    # a chunk longer than the cache is reported and skipped
+    assert gpu.kv_append_chunk(t.models[0], kx[:3], vx[:3], [3, 0, 0, 0], np.array([2, 9, 9, 9], dtype=np.int32)) == 3
+    assert gpu.device_errors() == 2
+    t.close()
