@@ -226,12 +226,15 @@ __device__ __forceinline__ void split_p(const float *p, u32x2 &hi, u32x2 &lo) {
 
 // One online-softmax step over the 32 tokens of a page pair.  valid_a is 1..16,
 // valid_b 0..16 (0: the pair has no second page; its registers hold zeros).
-template <int D, int DT, bool CAUSAL>
+// TAIL: 0 = whether the pair needs masks is decided at run time inside (one code path with
+// selects: right for the memory-bound decode kernel), 1 = the caller knows it needs none,
+// 2 = the caller knows it needs them (the prefill kernel branches, its bound is vector ALU work).
+template <int D, int DT, bool CAUSAL, int TAIL = 0>
 __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D, DT> &r, const bf16x8 *qf,
                                              float scale_log2, int valid_a, int valid_b, int G, int lim_a = 0,
                                              bool causal = false) {
     using TL = Tile<D, DT>;
-    const bool tail = valid_a < T || valid_b < T || (CAUSAL && causal);
+    const bool tail = TAIL == 1 ? false : (TAIL == 2 ? true : (valid_a < T || valid_b < T || (CAUSAL && causal)));
     f32x4 sa = qk_page<D, DT>(r.a, qf);
     f32x4 sb = qk_page<D, DT>(r.b, qf);
     const float sca = DT == PKV_E4M3 ? scale_log2 * r.a.sk : scale_log2;
@@ -253,14 +256,15 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
     const float m_new = fmaxf(st.m, mx);
     if (__any(m_new > st.m)) {            // wave-uniform: rescale only when some column's max moved
         // a column that has seen no token yet (prefill tiles only) has m = -inf on both sides
-        const float alpha = CAUSAL && m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
+        const float alpha = CAUSAL && TAIL != 1 && m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
         st.l *= alpha;
 #pragma unroll
         for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] *= alpha;
         st.m = m_new;
     }
     float p[8];
-    const float m_ref = CAUSAL && st.m == -INFINITY ? 0.f : st.m;     // then every s is -inf and every p is 0
+    // (a pair without masks leaves every column with a finite maximum)
+    const float m_ref = CAUSAL && TAIL != 1 && st.m == -INFINITY ? 0.f : st.m;     // then every s is -inf and every p is 0
 #pragma unroll
     for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - m_ref);
     st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
@@ -1083,10 +1087,15 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         }
         const int va = pa == n_pages - 1 ? last_valid : T;
         const int vb = pa + 1 < n_pages ? (pa + 1 == n_pages - 1 ? last_valid : T) : 0;
+        const bool pair_tail = va < T || vb < T || (pa + 2) * T > causal_from;       // wave-uniform
 #pragma unroll
         for (int u = 0; u < NT; ++u)
-            if (mine[u])
-                process_pair<D, DT, true>(st[u], r, qf[u], d.scale_log2, va, vb, G, col_lim[u] - pa * T, (pa + 2) * T > causal_from);
+            if (mine[u]) {
+                if (pair_tail)
+                    process_pair<D, DT, true, 2>(st[u], r, qf[u], d.scale_log2, va, vb, G, col_lim[u] - pa * T, true);
+                else
+                    process_pair<D, DT, true, 1>(st[u], r, qf[u], d.scale_log2, va, vb, G);
+            }
         // the next pair must have landed before anybody reads it; pairs requested after it may still travel
         const int newest = p + PF_BUFS - 1 < n_pairs - 1 ? p + PF_BUFS - 1 : n_pairs - 1;
         landed(newest - (p + 1));
