@@ -817,6 +817,7 @@ int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens
     d.vmap = m->vmap;
     d.cols = tile * m->g;
     d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m->D));
+    d.trace = g_trace;
     HIP_TRY(pkv_launch_prefill(d, (int)rows.size(), g_stream));
     return PKV_OK;
 }

@@ -301,6 +301,66 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
     }
 }
 
+// The two halves of process_pair for a pair that needs no masks, for callers that work on
+// several tiles of queries at once (prefill): with the halves of all tiles in one straight
+// line of code the scheduler can overlap the matrix instructions of one tile with the
+// softmax arithmetic of another.
+template <int D, int DT>
+__device__ __forceinline__ void pair_scores(State<D, DT> &st, const PairRegs<D, DT> &r, const bf16x8 *qf, float scale_log2,
+                                            bf16x8 &phv, bf16x8 &plv) {
+    using TL = Tile<D, DT>;
+    f32x4 sa = qk_page<D, DT>(r.a, qf);
+    f32x4 sb = qk_page<D, DT>(r.b, qf);
+    const float sca = DT == PKV_E4M3 ? scale_log2 * r.a.sk : scale_log2;
+    const float scb = DT == PKV_E4M3 ? scale_log2 * r.b.sk : scale_log2;
+    float s[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        s[i] = sa[i] * sca;
+        s[4 + i] = sb[i] * scb;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+    mx = rows_max(mx);
+    const float m_new = fmaxf(st.m, mx);
+    if (__any(m_new > st.m)) {
+        const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+        st.l *= alpha;
+#pragma unroll
+        for (int jt = 0; jt < TL::NV; ++jt) st.acc[jt] *= alpha;
+        st.m = m_new;
+    }
+    float p[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - st.m);
+    st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+    if (DT == PKV_E4M3) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            p[i] *= r.a.sv;
+            p[4 + i] *= r.b.sv;
+        }
+    }
+    u32x2 ha, la, hb, lb;
+    split_p(p, ha, la);
+    split_p(p + 4, hb, lb);
+    u32x4 ph = mk4(ha.x, ha.y, hb.x, hb.y), pl = mk4(la.x, la.y, lb.x, lb.y);
+    phv = *reinterpret_cast<bf16x8 *>(&ph);
+    plv = *reinterpret_cast<bf16x8 *>(&pl);
+}
+
+template <int D, int DT>
+__device__ __forceinline__ void pair_accumulate(State<D, DT> &st, const PairRegs<D, DT> &r, bf16x8 phv, bf16x8 plv) {
+    using TL = Tile<D, DT>;
+#pragma unroll
+    for (int jt = 0; jt < TL::NV; ++jt) {
+        const u32x2 va = v_half<D, DT>(r.a, jt), vb = v_half<D, DT>(r.b, jt);
+        u32x4 vv = mk4(va.x, va.y, vb.x, vb.y);
+        const bf16x8 av = *reinterpret_cast<bf16x8 *>(&vv);
+        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phv, st.acc[jt], 0, 0, 0);
+        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
+    }
+}
+
 // Floats per split-K partial: g rows of D accumulators, then g maxima, then g sums.
 __host__ __device__ inline int partial_floats(int g, int D) { return g * (D + 2); }
 
@@ -1021,11 +1081,19 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     // wave 3: V of page b.  Every request issues exactly NL loads per lane (a page past the end is
     // replaced by the last one, and masked later), so the number of loads in flight tells which
     // pairs have landed.
-    auto fetch = [&](int pair, uint8_t *buf) {
+    // The block id of a request is read through the scalar cache one request early (next_id), so
+    // that the dependent chain table -> address -> load never waits inside a step.
+    auto table_id = [&](int pair) {
         int page = 2 * pair + (w >> 1);
         page = page < n_pages ? page : n_pages - 1;
+        page = page > 0 ? page : 0;
         const int last = d.row_stride - 1;
-        uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[page < last ? page : last]);
+        return (uint32_t)PKV_CONST(int32_t, row)[page < last ? page : last];
+    };
+    uint32_t next_id = table_id(0);
+    auto fetch = [&](int pair, uint8_t *buf) {
+        uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane((int)next_id);
+        next_id = table_id(pair + 1);
         if (id >= d.max_block_id) {
             bad |= 1u;
             id = 0;
@@ -1043,8 +1111,14 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TL::NL) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
+#if defined(PKV_TRACE)
+    uint64_t tr_read = 0, tr_math = 0, tr_sync = 0, tr_steps = 0;
+#endif
     auto step = [&](int p, const uint8_t *buf, uint8_t *refill) {
         const int pa = 2 * p;
+#if defined(PKV_TRACE)
+        const uint64_t tr0 = __builtin_readcyclecounter();
+#endif
         // wave-uniform: does any token of the pair lie before what this wave's tiles see
         bool mine[NT];
         bool any_mine = false;
@@ -1053,8 +1127,6 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
             mine[u] = ri[u].ntok > 0 && pa * T < tile_lim[u];
             any_mine |= mine[u];
         }
-        // the buffer worked on in the last step is free (barrier): the pair NBUF - 1 ahead goes there
-        if (p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
         PairRegs<D, DT> r;
         if (any_mine) {
             const uint8_t *src = buf + lane * 16;
@@ -1085,21 +1157,50 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
                 }
             }
         }
+        // the buffer worked on in the last step is free (barrier): the pair NBUF - 1 ahead goes there;
+        // issued after this step's LDS reads so that those are already on their way
+        if (p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
+#if defined(PKV_TRACE)
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const uint64_t tr1 = __builtin_readcyclecounter();
+#endif
         const int va = pa == n_pages - 1 ? last_valid : T;
         const int vb = pa + 1 < n_pages ? (pa + 1 == n_pages - 1 ? last_valid : T) : 0;
         const bool pair_tail = va < T || vb < T || (pa + 2) * T > causal_from;       // wave-uniform
+        bool all_mine = true;
 #pragma unroll
-        for (int u = 0; u < NT; ++u)
-            if (mine[u]) {
-                if (pair_tail)
-                    process_pair<D, DT, true, 2>(st[u], r, qf[u], d.scale_log2, va, vb, G, col_lim[u] - pa * T, true);
-                else
-                    process_pair<D, DT, true, 1>(st[u], r, qf[u], d.scale_log2, va, vb, G);
-            }
+        for (int u = 0; u < NT; ++u) all_mine &= mine[u];
+        if (all_mine && !pair_tail) {
+            // the common case in one straight line: scores of every tile, then the accumulation of every tile
+            bf16x8 phv[NT], plv[NT];
+#pragma unroll
+            for (int u = 0; u < NT; ++u) pair_scores<D, DT>(st[u], r, qf[u], d.scale_log2, phv[u], plv[u]);
+#pragma unroll
+            for (int u = 0; u < NT; ++u) pair_accumulate<D, DT>(st[u], r, phv[u], plv[u]);
+        } else {
+#pragma unroll
+            for (int u = 0; u < NT; ++u)
+                if (mine[u]) {
+                    if (pair_tail)
+                        process_pair<D, DT, true, 2>(st[u], r, qf[u], d.scale_log2, va, vb, G, col_lim[u] - pa * T, true);
+                    else
+                        process_pair<D, DT, true, 1>(st[u], r, qf[u], d.scale_log2, va, vb, G);
+                }
+        }
+#if defined(PKV_TRACE)
+        const uint64_t tr2 = __builtin_readcyclecounter();
+#endif
         // the next pair must have landed before anybody reads it; pairs requested after it may still travel
         const int newest = p + PF_BUFS - 1 < n_pairs - 1 ? p + PF_BUFS - 1 : n_pairs - 1;
         landed(newest - (p + 1));
         __builtin_amdgcn_s_barrier();      // every read of this step's buffer has been consumed by then
+#if defined(PKV_TRACE)
+        const uint64_t tr3 = __builtin_readcyclecounter();
+        tr_read += tr1 - tr0;
+        tr_math += tr2 - tr1;
+        tr_sync += tr3 - tr2;
+        tr_steps += 1;
+#endif
     };
 
     // prologue: the first NBUF - 1 pairs
@@ -1129,6 +1230,12 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         }
     }
     if (bad && lane == 0) atomicOr(d.err, 1u);
+#if defined(PKV_TRACE)
+    if (lane == 0 && d.trace && blockIdx.x < 4096) {
+        uint64_t *t = d.trace + ((size_t)blockIdx.x * 4 + w) * 4;
+        t[0] = tr_read; t[1] = tr_math; t[2] = tr_sync; t[3] = tr_steps;
+    }
+#endif
 }
 
 __global__ __launch_bounds__(64 * PF_WAVES, 2) void k_prefill(const AttnDesc d) {
