@@ -97,10 +97,26 @@ def balloon_latency(gpu, torch):
         t_inf.append(t1 - t0); t_res.append(t2 - t1); t_rel.append((t3 - t2) / 32); t_def.append(t4 - t3)
     gpu.model_unregister(m)
     gpu.pool_destroy(pool)
-    med = lambda x: float(np.median(x) * 1e6)
-    return {"inflate_176_frames_us": med(t_inf), "deflate_176_frames_us": med(t_def),
-            "reserve_batch_5632_blocks_us": med(t_res), "release_176_blocks_us": med(t_rel),
-            "kind": "host wall clock per call, median of 50"}
+    med = lambda x: round(float(np.median(x) * 1e6), 2)
+    res = {"inflate_176_frames_us": med(t_inf), "deflate_176_frames_us": med(t_def),
+           "reserve_batch_5632_blocks_us": med(t_res), "release_176_blocks_us": med(t_rel),
+           "kind": "host wall clock per call, median of 50"}
+    # the same balloon on an elastic pool: frames are mapped when acquired and unmapped when given back
+    for name, spare in (("elastic", 0), ("elastic_prealloc_176", 176)):
+        pool = gpu.pool_create_elastic(8 << 30, 16, 2 << 20)
+        assert pool >= 0, gpu.last_error()
+        assert gpu.pool_set_prealloc(pool, spare) == spare
+        m = gpu.model_register(pool, 32, 8, 128, 0, 32, 512)
+        t_inf, t_def = [], []
+        for _ in range(12):
+            t0 = time.perf_counter(); assert gpu.balloon_resize(m, 176) == 176; t1 = time.perf_counter()
+            assert gpu.balloon_resize(m, 0) == 0; t2 = time.perf_counter()
+            t_inf.append(t1 - t0); t_def.append(t2 - t1)
+        gpu.model_unregister(m)
+        gpu.pool_destroy(pool)
+        res[name + "_inflate_176_frames_us"] = med(t_inf[2:])
+        res[name + "_deflate_176_frames_us"] = med(t_def[2:])
+    return res
 
 
 def append_latency(gpu, torch, rep, inputs):

@@ -60,6 +60,8 @@ typedef struct pkv_stats {
     int64_t n_frames, n_free;   /* pool */
     int64_t owned[64];          /* frames per model id (0 for ids not in this pool) */
     int64_t used_blocks[64];    /* reserved blocks per model id */
+    int64_t mapped_bytes;       /* pool bytes backed by device memory (all of it unless the pool is elastic) */
+    int64_t spare_frames;       /* elastic pools: frames of memory held ready to be mapped */
 } pkv_stats;
 
 /* ---- library ------------------------------------------------------------ */
@@ -85,6 +87,18 @@ int pool_create(size_t bytes, int page_tokens);
  * (device_base, dev, at least bytes long, 256-byte aligned; NULL = allocate). */
 int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *device_base);
 /* Fails with PKV_E_BUSY while any model is registered in the pool. */
+/* A pool whose memory is elastic (paper Sec. 4.2, D1 / D3: the balloon driver hands physical
+ * pages out lazily and takes them back, so that what one model gives up can serve another
+ * model or its weights).  The pool is a reserved range of device addresses; a frame is backed
+ * by device memory exactly while a model owns it: balloon_resize maps the frames an inflate
+ * acquires and unmaps the frames a deflate gives back (HIP virtual memory management).
+ * frame_bytes must be a multiple of the device's allocation granularity (PKV_E_SHAPE).
+ * Everything else behaves like pool_create_ex; pool_stats reports mapped_bytes.
+ * pool_set_prealloc keeps up to `frames` frames of memory created but unmapped (the paper's
+ * pre-allocation buffer): an inflate takes from it before it asks the driver, a deflate refills
+ * it before it releases; it returns the number held now. */
+int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes);
+int pool_set_prealloc(int pool, long frames);
 int pool_destroy(int pool);
 /* Set the order in which a still-untouched pool hands out frames: perm (host,
  * n = number of frames) is a permutation of the frame ids, perm[0] first. */

@@ -65,6 +65,8 @@ def _load():
         "prefill_attention": (i, [i, i, vp, vp, vp, vp]),
         "pool_export_state": (l, [i, vp, sz]),
         "pool_stats": (i, [i, vp]),
+        "pool_create_elastic": (i, [sz, i, sz]),
+        "pool_set_prealloc": (i, [i, l]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -76,7 +78,7 @@ def _load():
 EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_set_page_cost", "pkv_debug_fastdiv",
            "pkv_set_xcd_weights", "pkv_get_xcd_weights", "pkv_tune_xcd", "pkv_set_segment_cost",
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
-           "pool_create", "pool_create_ex", "pool_destroy", "pool_seed_free_order", "model_register",
+           "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
            "seq_release", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
            "decode_attention_ex", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats"]
@@ -336,6 +338,22 @@ class PrismKV:
         cp = (C.c_void_p * n)(*[c.data_ptr() for c in ctxs])
         op = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
         return self.lib.decode_attention_multi(n, ids, bs, qp, cp, op)
+
+    def pool_create_elastic(self, nbytes, page_tokens, frame_bytes=2 << 20):
+        return self.lib.pool_create_elastic(nbytes, page_tokens, frame_bytes)
+
+    def pool_set_prealloc(self, pool, frames):
+        return self.lib.pool_set_prealloc(pool, frames)
+
+    def pool_stats(self, pool):
+        """-> dict(n_frames, n_free, owned[64], used_blocks[64], mapped_bytes, spare_frames)"""
+        buf = (C.c_int64 * (2 + 64 + 64 + 2))()
+        rc = self.lib.pool_stats(pool, C.cast(buf, C.c_void_p))
+        if rc:
+            raise RuntimeError(f"pool_stats: {rc} {self.last_error()}")
+        v = list(buf)
+        return {"n_frames": v[0], "n_free": v[1], "owned": v[2:66], "used_blocks": v[66:130], "mapped_bytes": v[130],
+                "spare_frames": v[131]}
 
     # ---- state
     def pool_export_state(self, pool):

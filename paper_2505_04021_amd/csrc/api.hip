@@ -23,6 +23,14 @@ struct Pool {
     uint8_t *base = nullptr;
     bool own_base = false;
     PoolDev dev{};
+    int64_t n_free = 0;                     // shadow of the device counter
+    // elastic pools: `base` is a reserved address range; a frame is backed by memory only while a model owns it
+    bool elastic = false;
+    std::vector<hipMemGenericAllocationHandle_t> handle;   // per frame, valid while mapped[f]
+    std::vector<uint8_t> mapped;
+    std::vector<hipMemGenericAllocationHandle_t> spare;    // created, unmapped: the pre-allocation buffer (paper D3)
+    size_t spare_cap = 0;
+    int64_t mapped_frames = 0;
 };
 
 struct Model {
@@ -79,6 +87,7 @@ hipStream_t g_stream = nullptr;
 BookResult *g_res = nullptr;       // pinned host
 int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
 uint32_t *g_err = nullptr;         // device error flags
+void *g_safe = nullptr;            // 16 KiB of zeros: what kernels read instead of a block they must not touch
 uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
 int g_items = 0, g_min_share = 0, g_seg_cost = -1;
 // How a block of eight shares is cut among the XCDs: weights (mean 1), and the state of a
@@ -111,6 +120,8 @@ int lib_init() {
     HIP_TRY(hipHostMalloc((void **)&g_ops, sizeof(int32_t) * 2 * PKV_MAX_BATCH_OPS, hipHostMallocDefault));
     HIP_TRY(hipMalloc((void **)&g_err, sizeof(uint32_t)));
     HIP_TRY(hipMemset(g_err, 0, sizeof(uint32_t)));
+    HIP_TRY(hipMalloc(&g_safe, 16384));
+    HIP_TRY(hipMemset(g_safe, 0, 16384));
     return PKV_OK;
 }
 
@@ -176,6 +187,7 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.row_len = own ? m.dev.row_len : nullptr;
     d.out = out;
     d.err = g_err;
+    d.safe = g_safe;
     d.trace = g_trace;
     d.frame_bytes = p.frame_bytes;
     d.block_bytes = m.block_bytes;
@@ -456,9 +468,109 @@ int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *devi
         return fail_hip(e, "pool_create");
     }
     p.live = true;
+    p.n_free = n_frames;
     g_pools[id] = p;
     g_last_pool = id;
     return id;
+}
+
+/* ------------------------------------------------------------ elastic pools */
+
+hipMemAllocationProp device_memory_prop() {
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    prop.location.id = dev;
+    return prop;
+}
+
+// back frame f of an elastic pool with memory (a spare handle if there is one)
+int elastic_map(Pool &p, uint32_t f) {
+    if (f >= (uint64_t)p.n_frames || p.mapped[f]) return PKV_E_INTERNAL;
+    hipMemGenericAllocationHandle_t h;
+    if (!p.spare.empty()) {
+        h = p.spare.back();
+        p.spare.pop_back();
+    } else {
+        const hipMemAllocationProp prop = device_memory_prop();
+        hipError_t e = hipMemCreate(&h, p.frame_bytes, &prop, 0);
+        if (e != hipSuccess) { fail_hip(e, "hipMemCreate(frame)"); return PKV_E_NOMEM; }
+    }
+    void *at = p.base + (size_t)f * p.frame_bytes;
+    hipError_t e = hipMemMap(at, p.frame_bytes, 0, h, 0);
+    if (e == hipSuccess) {
+        hipMemAccessDesc acc = {};
+        acc.location = device_memory_prop().location;
+        acc.flags = hipMemAccessFlagsProtReadWrite;
+        e = hipMemSetAccess(at, p.frame_bytes, &acc, 1);
+        if (e != hipSuccess) (void)hipMemUnmap(at, p.frame_bytes);
+    }
+    if (e != hipSuccess) {
+        (void)hipMemRelease(h);
+        fail_hip(e, "hipMemMap(frame)");
+        return PKV_E_DEVICE;
+    }
+    p.handle[f] = h;
+    p.mapped[f] = 1;
+    p.mapped_frames++;
+    return PKV_OK;
+}
+
+int elastic_unmap(Pool &p, uint32_t f) {
+    if (f >= (uint64_t)p.n_frames || !p.mapped[f]) return PKV_E_INTERNAL;
+    hipError_t e = hipMemUnmap(p.base + (size_t)f * p.frame_bytes, p.frame_bytes);
+    if (e != hipSuccess) return fail_hip(e, "hipMemUnmap(frame)");
+    if (p.spare.size() < p.spare_cap) p.spare.push_back(p.handle[f]);
+    else (void)hipMemRelease(p.handle[f]);
+    p.mapped[f] = 0;
+    p.mapped_frames--;
+    return PKV_OK;
+}
+
+int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes) {
+    if (page_tokens <= 0 || frame_bytes == 0 || bytes < frame_bytes) return PKV_E_ARG;
+    int rc = lib_init();
+    if (rc) return rc;
+    const hipMemAllocationProp prop = device_memory_prop();
+    size_t gran = 0;
+    hipError_t e = hipMemGetAllocationGranularity(&gran, &prop, hipMemAllocationGranularityMinimum);
+    if (e != hipSuccess) { fail_hip(e, "hipMemGetAllocationGranularity"); return PKV_E_UNSUPPORTED; }
+    if (gran == 0 || frame_bytes % gran != 0 || frame_bytes % 256 != 0) return PKV_E_SHAPE;
+    const int64_t n_frames = (int64_t)(bytes / frame_bytes);
+    void *va = nullptr;
+    e = hipMemAddressReserve(&va, (size_t)n_frames * frame_bytes, 0, nullptr, 0);
+    if (e != hipSuccess) { fail_hip(e, "hipMemAddressReserve"); return PKV_E_NOMEM; }
+    const int id = pool_create_ex((size_t)n_frames * frame_bytes, page_tokens, frame_bytes, va);
+    if (id < 0) {
+        (void)hipMemAddressFree(va, (size_t)n_frames * frame_bytes);
+        return id;
+    }
+    Pool &p = g_pools[id];
+    p.elastic = true;
+    p.handle.assign((size_t)n_frames, hipMemGenericAllocationHandle_t{});
+    p.mapped.assign((size_t)n_frames, 0);
+    return id;
+}
+
+int pool_set_prealloc(int pool, long frames) {
+    Pool *p = get_pool(pool);
+    if (!p) return PKV_E_HANDLE;
+    if (!p->elastic || frames < 0 || frames > p->n_frames) return PKV_E_ARG;
+    p->spare_cap = (size_t)frames;
+    const hipMemAllocationProp prop = device_memory_prop();
+    while (p->spare.size() < p->spare_cap) {
+        hipMemGenericAllocationHandle_t h;
+        hipError_t e = hipMemCreate(&h, p->frame_bytes, &prop, 0);
+        if (e != hipSuccess) { fail_hip(e, "hipMemCreate(spare)"); return PKV_E_NOMEM; }
+        p->spare.push_back(h);
+    }
+    while (p->spare.size() > p->spare_cap) {
+        (void)hipMemRelease(p->spare.back());
+        p->spare.pop_back();
+    }
+    return (int)p->spare.size();
 }
 
 int pool_create(size_t bytes, int page_tokens) {
@@ -473,6 +585,13 @@ int pool_destroy(int pool) {
     HIP_TRY(hipStreamSynchronize(g_stream));
     (void)hipFree(p->dev.owner); (void)hipFree(p->dev.free_stack); (void)hipFree(p->dev.pos); (void)hipFree(p->dev.n_free);
     if (p->own_base) (void)hipFree(p->base);
+    if (p->elastic) {
+        p->spare_cap = 0;
+        for (int64_t f = 0; f < p->n_frames; ++f)
+            if (p->mapped[(size_t)f]) (void)elastic_unmap(*p, (uint32_t)f);
+        for (auto h : p->spare) (void)hipMemRelease(h);
+        (void)hipMemAddressFree(p->base, (size_t)p->n_frames * p->frame_bytes);
+    }
     *p = Pool{};
     if (g_last_pool == pool) g_last_pool = -1;
     return PKV_OK;
@@ -582,10 +701,33 @@ long balloon_resize(int model, long pages) {
     Pool &p = g_pools[m->pool];
     if (pages > p.n_frames) return PKV_E_NOMEM;
     int64_t r;
+    const int64_t before = m->owned;
     if (pages > m->owned) {
         r = book_call([&] { return pkv_launch_inflate(p.dev, m->dev, pages, g_res, g_stream); });
+        if (r >= 0 && p.elastic && r > before) {
+            // the kernel chose the frames (top of the free stack); back them with memory before anyone
+            // can place a block there: they are the new tail of the model's frame list
+            std::vector<uint32_t> got((size_t)(r - before));
+            HIP_TRY(hipMemcpy(got.data(), m->dev.frames + before, got.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+            for (uint32_t f : got) {
+                const int rc = elastic_map(p, f);
+                if (rc) return rc;
+            }
+        }
+        if (r >= 0) p.n_free -= r - before;
     } else if (pages < m->owned) {
         r = book_call([&] { return pkv_launch_deflate(p.dev, m->dev, pages, g_res, g_stream); });
+        if (r >= 0 && p.elastic && r < before) {
+            // the frames given back are the new top of the free stack; nothing refers to them any more
+            // (they held no block) and the stream is idle (the call above waited for its result)
+            std::vector<uint32_t> gone((size_t)(before - r));
+            HIP_TRY(hipMemcpy(gone.data(), p.dev.free_stack + p.n_free, gone.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+            for (uint32_t f : gone) {
+                const int rc = elastic_unmap(p, f);
+                if (rc) return rc;
+            }
+        }
+        if (r >= 0) p.n_free += before - r;
     } else {
         return (long)m->owned;
     }
@@ -670,6 +812,7 @@ static void fill_addressing(AttnDesc &d, const Model &m) {
     d.row_stride = m.dev.max_blocks;
     d.row_len = m.dev.row_len;
     d.err = g_err;
+    d.safe = g_safe;
     d.frame_bytes = p.frame_bytes;
     d.block_bytes = m.block_bytes;
     d.slots_div = fastdiv_make((uint32_t)m.slots);
@@ -955,6 +1098,8 @@ int pool_stats(int pool, pkv_stats *out) {
         out->owned[id] = cnt[0];
         out->used_blocks[id] = cnt[0] * m.slots - cnt[1];
     }
+    out->mapped_bytes = p->elastic ? p->mapped_frames * (int64_t)p->frame_bytes : p->n_frames * (int64_t)p->frame_bytes;
+    out->spare_frames = (int64_t)p->spare.size();
     return PKV_OK;
 }
 

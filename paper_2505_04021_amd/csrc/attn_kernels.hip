@@ -121,15 +121,19 @@ __device__ __forceinline__ void load_page(PageRegs<D, DT> &r, const AttnDesc &d,
     if (id >= d.max_block_id) {          // never dereference an id outside the pool
         bad |= live ? 1u : 0u;           // reported once, after the last load (no store inside the loop)
         id = 0;
+        live = false;                    // the page is skipped: frame 0 need not even be backed by memory
     }
     const uint32_t f = fastdiv_div(id, d.slots_div);
     const uint32_t s = id - f * d.slots_div.d;
     const uint8_t *blk = d.pool_base + (uint64_t)f * d.frame_bytes + (uint64_t)s * d.block_bytes;
     if (DT == PKV_E4M3) {
-        const float *hdr = reinterpret_cast<const float *>(blk);
+        // A dead page's id is whatever the table holds past the row's end: possibly a block of a
+        // frame that was given back and, in an elastic pool, is no longer backed by memory.
+        // Its header must not be read (the tile loads below are harmless: zero records).
+        const float *hdr = reinterpret_cast<const float *>(live ? blk : reinterpret_cast<const uint8_t *>(d.safe));
         r.sk = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[kvh])));
         r.sv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[d.Hkv + kvh])));
-        if (!live) r.sk = r.sv = 0.f;      // a dead page may sit on a block that was never written
+        if (!live) r.sk = r.sv = 0.f;
         blk += PKV_FP8_HEADER;
     }
     const uint8_t *tiles = blk + (size_t)kvh * 2 * TL::TILE_BYTES;
@@ -1094,7 +1098,8 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     auto fetch = [&](int pair, uint8_t *buf) {
         uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane((int)next_id);
         next_id = table_id(pair + 1);
-        if (id >= d.max_block_id) {
+        const bool ok = id < d.max_block_id;
+        if (!ok) {
             bad |= 1u;
             id = 0;
         }
@@ -1102,7 +1107,8 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         const uint32_t sl = id - f * d.slots_div.d;
         const uint8_t *blk = d.pool_base + (uint64_t)f * d.frame_bytes + (uint64_t)sl * d.block_bytes +
                              (DT == PKV_E4M3 ? PKV_FP8_HEADER : 0);
-        const uint8_t *src = blk + ((size_t)kvh * 2 + (w & 1)) * TL::TILE_BYTES + lane * 16;
+        // an id outside the pool is never dereferenced: the same number of loads goes to a zeroed spare tile
+        const uint8_t *src = (ok ? blk + ((size_t)kvh * 2 + (w & 1)) * TL::TILE_BYTES : reinterpret_cast<const uint8_t *>(d.safe)) + lane * 16;
         lds_fill<TL::NL>(src, buf + (size_t)w * TL::TILE_BYTES);
     };
     // wait until the loads of all but the `ahead` most recent requests have landed
@@ -1143,13 +1149,15 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     const int page = pa + h;
-                    const bool live = page < n_pages;
                     uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[page < last ? page : last]);
-                    if (id >= d.max_block_id) id = 0;
+                    // past the end of the context, or an id outside the pool: no header is read
+                    const bool live = page < n_pages && id < d.max_block_id;
+                    if (!live) id = 0;
                     const uint32_t f = fastdiv_div(id, d.slots_div);
                     const uint32_t sl = id - f * d.slots_div.d;
-                    const float *hdr = reinterpret_cast<const float *>(d.pool_base + (uint64_t)f * d.frame_bytes +
-                                                                       (uint64_t)sl * d.block_bytes);
+                    const float *hdr = live ? reinterpret_cast<const float *>(d.pool_base + (uint64_t)f * d.frame_bytes +
+                                                                              (uint64_t)sl * d.block_bytes)
+                                            : reinterpret_cast<const float *>(d.safe);
                     float sk = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[kvh])));
                     float sv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[d.Hkv + kvh])));
                     if (!live) sk = sv = 0.f;

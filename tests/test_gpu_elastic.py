@@ -1,0 +1,140 @@
+"""GPU tests of elastic pools: a pool whose frames are backed by device memory only while a model
+owns them (HIP virtual memory management behind balloon_resize).  The bookkeeping state and the
+attention results must be what they are with an ordinary pool — the oracle knows no difference —
+and the memory mapped must be exactly the frames that are owned."""
+import numpy as np
+import pytest
+
+from parity import TOL, assert_same_state, row_rel_err, run_pair
+from state_image import parse
+from workloads import gen
+from workloads.scenarios import Runner, make_config
+
+pytestmark = pytest.mark.gpu
+
+BF16, E4M3 = 0, 1
+
+
+class Elastic:
+    """The GPU backend with every pool created elastic."""
+
+    def __init__(self, gpu):
+        self._gpu = gpu
+        self.name = "gpu-elastic"
+
+    def __getattr__(self, k):
+        return getattr(self._gpu, k)
+
+    def pool_create(self, nbytes, page_tokens, frame_bytes=None, storage=None):
+        assert storage is None
+        return self._gpu.pool_create_elastic(nbytes, page_tokens, frame_bytes or (2 << 20))
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    from paper_2505_04021_amd import PrismKV
+    return PrismKV()
+
+
+def mapped_matches_owned(gpu, pool, frame_bytes):
+    st = gpu.pool_stats(pool)
+    assert st["mapped_bytes"] == (st["n_frames"] - st["n_free"]) * frame_bytes, st
+    return st
+
+
+def test_frames_are_mapped_while_owned(gpu, oracle):
+    """Inflate, fill, attend, release, deflate with a clamp, reuse by a second model."""
+    fb = 2 << 20
+    pools = [gpu.pool_create_elastic(64 * fb, 16, fb), oracle.pool_create(64 * fb, 16, fb)]
+    assert min(pools) >= 0
+    perm = gen.free_order(64, gen.generator(9))
+    bes = (gpu, oracle)
+    for be, pool in zip(bes, pools):
+        assert be.pool_seed_free_order(pool, perm) == 0
+    assert gpu.pool_stats(pools[0])["mapped_bytes"] == 0
+    ms = [be.model_register(pool, 32, 8, 128, BF16, 4, 64) for be, pool in zip(bes, pools)]
+    m2 = [be.model_register(pool, 12, 4, 64, E4M3, 4, 64) for be, pool in zip(bes, pools)]
+    ctx = np.array([300, 17, 1000, 64], dtype=np.int32)
+    for be, m in zip(bes, ms):
+        assert be.balloon_resize(m, 5) == 5
+        assert be.seq_reserve_batch(m, [0, 1, 2, 3], ctx) >= 0
+    mapped_matches_owned(gpu, pools[0], fb)
+    for s, c in enumerate(ctx):
+        kv = gen.seq_kv((9, s), int(c), 8, 128, BF16, 16)
+        for be, m in zip(bes, ms):
+            assert be.kv_write(m, s, 0, kv["k"], kv["v"]) == c
+    q = gen.queries((9, 9), 4, 32, 128)
+    out_g, out_o = gpu.decode_attention(ms[0], q, ctx), oracle.decode_attention(ms[1], q, ctx)
+    assert out_g[0] == 0 and out_o[0] == 0 and row_rel_err(out_g[1], out_o[1]) <= TOL[BF16]
+    # the second model grows while the first still holds its frames
+    for be, m in zip(bes, m2):
+        assert be.balloon_resize(m, 20) == 20
+    assert mapped_matches_owned(gpu, pools[0], fb)["mapped_bytes"] == 25 * fb
+    # the first gives back what it can: sequences 0 and 2 leave, the deflate clamps at the frames still in use
+    for be, m in zip(bes, ms):
+        assert be.seq_release(m, 0) > 0 and be.seq_release(m, 2) > 0
+    r = [be.balloon_resize(m, 0) for be, m in zip(bes, ms)]
+    assert r[0] == r[1] and 0 < r[0] < 5
+    assert_same_state(gpu, oracle, pools[0], pools[1])
+    mapped_matches_owned(gpu, pools[0], fb)
+    sel = [1, 3]
+    q2 = gen.queries((9, 10), 4, 32, 128)
+    ctx2 = ctx.copy()
+    ctx2[[0, 2]] = 0
+    out_g, out_o = gpu.decode_attention(ms[0], q2, ctx2), oracle.decode_attention(ms[1], q2, ctx2)
+    assert out_g[0] == 0 and out_o[0] == 0 and row_rel_err(out_g[1], out_o[1]) <= TOL[BF16]
+    assert gpu.device_errors() == 0
+    for be, m, mm in zip(bes, ms, m2):
+        for s in range(4):
+            be.seq_release(m, s)
+        assert be.balloon_resize(m, 0) == 0 and be.balloon_resize(mm, 0) == 0
+        assert be.model_unregister(m) == 0 and be.model_unregister(mm) == 0
+    assert gpu.pool_stats(pools[0])["mapped_bytes"] == 0
+    for be, pool in zip(bes, pools):
+        assert be.pool_destroy(pool) == 0
+
+
+def test_prealloc_buffer(gpu):
+    fb = 2 << 20
+    pool = gpu.pool_create_elastic(32 * fb, 16, fb)
+    assert pool >= 0
+    assert gpu.pool_set_prealloc(pool, 6) == 6
+    m = gpu.model_register(pool, 32, 8, 128, BF16, 2, 64)
+    assert gpu.balloon_resize(m, 4) == 4
+    st = gpu.pool_stats(pool)
+    assert st["spare_frames"] == 2 and st["mapped_bytes"] == 4 * fb
+    assert gpu.balloon_resize(m, 10) == 10                   # 2 from the buffer, 4 from the driver
+    assert gpu.pool_stats(pool)["spare_frames"] == 0
+    assert gpu.balloon_resize(m, 1) == 1                     # 9 come back: 6 refill the buffer, 3 are released
+    st = gpu.pool_stats(pool)
+    assert st["spare_frames"] == 6 and st["mapped_bytes"] == fb
+    assert gpu.balloon_resize(m, 0) == 0 and gpu.model_unregister(m) == 0 and gpu.pool_destroy(pool) == 0
+    assert gpu.pool_create_elastic(32 * fb, 16, fb + 512) < 0          # not a multiple of the granularity
+
+
+@pytest.mark.parametrize("cfg_id", [3, 5])
+def test_dynamic_scenarios_on_an_elastic_pool(gpu, oracle, cfg_id):
+    """cfg 3 (models switching on and off) and cfg 5 (release, deflate, re-inflate every tenth step)
+    at the small sizes, the GPU side on an elastic pool: state bit-exact after every step, attention
+    within tolerance, mapped memory equal to the frames owned."""
+    cfg = make_config(cfg_id, "small")
+    eg = Elastic(gpu)
+    rg, ro = Runner(eg, cfg).setup(), Runner(oracle, cfg).setup()
+    try:
+        for t in range(cfg.steps):
+            rg.step(t)
+            ro.step(t)
+            assert rg.log == ro.log
+            assert_same_state(gpu, oracle, rg.pool, ro.pool, f"step {t}")
+            mapped_matches_owned(gpu, rg.pool, cfg.frame_bytes)
+            if t % 7 == 0:
+                for mi in rg.active_models():
+                    q = rg.queries(t, mi)
+                    rc_g, out_g = gpu.decode_attention(rg.models[mi], q, rg.ctx[mi])
+                    rc_o, out_o = oracle.decode_attention(ro.models[mi], q, ro.ctx[mi])
+                    assert rc_g == 0 and rc_o == 0
+                    assert row_rel_err(out_g, out_o) <= TOL[cfg.models[mi].dtype]
+        assert gpu.device_errors() == 0
+    finally:
+        rg.teardown()
+        ro.teardown()
