@@ -116,6 +116,7 @@ def balloon_latency(gpu, torch):
         gpu.pool_destroy(pool)
         res[name + "_inflate_176_frames_us"] = med(t_inf[2:])
         res[name + "_deflate_176_frames_us"] = med(t_def[2:])
+        res[name + "_first_inflate_us"] = round(t_inf[0] * 1e6, 2)
     return res
 
 

@@ -62,6 +62,7 @@ typedef struct pkv_stats {
     int64_t used_blocks[64];    /* reserved blocks per model id */
     int64_t mapped_bytes;       /* pool bytes backed by device memory (all of it unless the pool is elastic) */
     int64_t spare_frames;       /* elastic pools: frames of memory held ready to be mapped */
+    int64_t idle_frames;        /* elastic pools: frames no model owns that were left mapped in place */
 } pkv_stats;
 
 /* ---- library ------------------------------------------------------------ */
@@ -94,9 +95,12 @@ int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *devi
  * acquires and unmaps the frames a deflate gives back (HIP virtual memory management).
  * frame_bytes must be a multiple of the device's allocation granularity (PKV_E_SHAPE).
  * Everything else behaves like pool_create_ex; pool_stats reports mapped_bytes.
- * pool_set_prealloc keeps up to `frames` frames of memory created but unmapped (the paper's
- * pre-allocation buffer): an inflate takes from it before it asks the driver, a deflate refills
- * it before it releases; it returns the number held now. */
+ * pool_set_prealloc sets the size of the pre-allocation buffer (paper D3): up to `frames` frames
+ * of memory that no model owns are kept, either created and unmapped, or — when a deflate gave
+ * them back — still mapped where they were.  An inflate that takes such a frame again (the free
+ * stack hands the latest frames out first) costs no mapping at all; other inflates take a
+ * prepared handle before they ask the driver.  Shrinking the buffer unmaps and releases what
+ * exceeds it, oldest first.  Returns the frames held now; synchronises the stream. */
 int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes);
 int pool_set_prealloc(int pool, long frames);
 int pool_destroy(int pool);

@@ -346,14 +346,14 @@ class PrismKV:
         return self.lib.pool_set_prealloc(pool, frames)
 
     def pool_stats(self, pool):
-        """-> dict(n_frames, n_free, owned[64], used_blocks[64], mapped_bytes, spare_frames)"""
-        buf = (C.c_int64 * (2 + 64 + 64 + 2))()
+        """-> dict(n_frames, n_free, owned[64], used_blocks[64], mapped_bytes, spare_frames, idle_frames)"""
+        buf = (C.c_int64 * (2 + 64 + 64 + 3))()
         rc = self.lib.pool_stats(pool, C.cast(buf, C.c_void_p))
         if rc:
             raise RuntimeError(f"pool_stats: {rc} {self.last_error()}")
         v = list(buf)
         return {"n_frames": v[0], "n_free": v[1], "owned": v[2:66], "used_blocks": v[66:130], "mapped_bytes": v[130],
-                "spare_frames": v[131]}
+                "spare_frames": v[131], "idle_frames": v[132]}
 
     # ---- state
     def pool_export_state(self, pool):

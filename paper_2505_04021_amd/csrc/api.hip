@@ -28,7 +28,11 @@ struct Pool {
     bool elastic = false;
     std::vector<hipMemGenericAllocationHandle_t> handle;   // per frame, valid while mapped[f]
     std::vector<uint8_t> mapped;
-    std::vector<hipMemGenericAllocationHandle_t> spare;    // created, unmapped: the pre-allocation buffer (paper D3)
+    // the pre-allocation buffer (paper D3), at most spare_cap frames of memory in two forms:
+    std::vector<hipMemGenericAllocationHandle_t> spare;    //   created but unmapped
+    std::vector<uint8_t> idle;                              //   per frame: given back by a deflate, left mapped in place
+    std::vector<uint32_t> idle_fifo;                        //   the same frames, oldest first (entries may be stale)
+    int64_t n_idle = 0;
     size_t spare_cap = 0;
     int64_t mapped_frames = 0;
 };
@@ -486,9 +490,16 @@ hipMemAllocationProp device_memory_prop() {
     return prop;
 }
 
-// back frame f of an elastic pool with memory (a spare handle if there is one)
+// back frame f of an elastic pool with memory: as it is if a deflate left it mapped, else with a
+// spare handle if there is one, else with newly created memory
 int elastic_map(Pool &p, uint32_t f) {
-    if (f >= (uint64_t)p.n_frames || p.mapped[f]) return PKV_E_INTERNAL;
+    if (f >= (uint64_t)p.n_frames) return PKV_E_INTERNAL;
+    if (p.idle[f]) {                       // re-acquired before it was trimmed: nothing to do
+        p.idle[f] = 0;
+        p.n_idle--;
+        return PKV_OK;
+    }
+    if (p.mapped[f]) return PKV_E_INTERNAL;
     hipMemGenericAllocationHandle_t h;
     if (!p.spare.empty()) {
         h = p.spare.back();
@@ -520,12 +531,54 @@ int elastic_map(Pool &p, uint32_t f) {
 
 int elastic_unmap(Pool &p, uint32_t f) {
     if (f >= (uint64_t)p.n_frames || !p.mapped[f]) return PKV_E_INTERNAL;
+    if (p.idle[f]) {
+        p.idle[f] = 0;
+        p.n_idle--;
+    }
     hipError_t e = hipMemUnmap(p.base + (size_t)f * p.frame_bytes, p.frame_bytes);
     if (e != hipSuccess) return fail_hip(e, "hipMemUnmap(frame)");
-    if (p.spare.size() < p.spare_cap) p.spare.push_back(p.handle[f]);
+    if (p.spare.size() + (size_t)p.n_idle < p.spare_cap) p.spare.push_back(p.handle[f]);
     else (void)hipMemRelease(p.handle[f]);
     p.mapped[f] = 0;
     p.mapped_frames--;
+    return PKV_OK;
+}
+
+// a deflate gave frame f back: leave it mapped where it is while the buffer has room (an inflate
+// that takes it again — the free stack hands the latest frames out first — then costs nothing),
+// else unmap it
+int elastic_give_back(Pool &p, uint32_t f) {
+    if (f >= (uint64_t)p.n_frames || !p.mapped[f] || p.idle[f]) return PKV_E_INTERNAL;
+    if (p.spare.size() + (size_t)p.n_idle < p.spare_cap) {
+        p.idle[f] = 1;
+        p.n_idle++;
+        p.idle_fifo.push_back(f);
+        return PKV_OK;
+    }
+    return elastic_unmap(p, f);
+}
+
+// shrink the buffer to its cap: spare handles first, then the idle frames that have waited longest
+int elastic_trim(Pool &p) {
+    while (p.spare.size() + (size_t)p.n_idle > p.spare_cap && !p.spare.empty()) {
+        (void)hipMemRelease(p.spare.back());
+        p.spare.pop_back();
+    }
+    size_t head = 0;
+    while ((size_t)p.n_idle > p.spare_cap && head < p.idle_fifo.size()) {
+        const uint32_t f = p.idle_fifo[head++];
+        if (!p.idle[f]) continue;              // taken again meanwhile
+        const size_t cap = p.spare_cap;
+        p.spare_cap = 0;                        // really release it
+        const int rc = elastic_unmap(p, f);
+        p.spare_cap = cap;
+        if (rc) return rc;
+    }
+    // drop the stale prefix of the queue
+    std::vector<uint32_t> rest;
+    for (size_t i = head; i < p.idle_fifo.size(); ++i)
+        if (p.idle[p.idle_fifo[i]]) rest.push_back(p.idle_fifo[i]);
+    p.idle_fifo.swap(rest);
     return PKV_OK;
 }
 
@@ -551,6 +604,7 @@ int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes) {
     p.elastic = true;
     p.handle.assign((size_t)n_frames, hipMemGenericAllocationHandle_t{});
     p.mapped.assign((size_t)n_frames, 0);
+    p.idle.assign((size_t)n_frames, 0);
     return id;
 }
 
@@ -558,19 +612,18 @@ int pool_set_prealloc(int pool, long frames) {
     Pool *p = get_pool(pool);
     if (!p) return PKV_E_HANDLE;
     if (!p->elastic || frames < 0 || frames > p->n_frames) return PKV_E_ARG;
+    HIP_TRY(hipStreamSynchronize(g_stream));
     p->spare_cap = (size_t)frames;
+    const int rc = elastic_trim(*p);
+    if (rc) return rc;
     const hipMemAllocationProp prop = device_memory_prop();
-    while (p->spare.size() < p->spare_cap) {
+    while (p->spare.size() + (size_t)p->n_idle < p->spare_cap) {
         hipMemGenericAllocationHandle_t h;
         hipError_t e = hipMemCreate(&h, p->frame_bytes, &prop, 0);
         if (e != hipSuccess) { fail_hip(e, "hipMemCreate(spare)"); return PKV_E_NOMEM; }
         p->spare.push_back(h);
     }
-    while (p->spare.size() > p->spare_cap) {
-        (void)hipMemRelease(p->spare.back());
-        p->spare.pop_back();
-    }
-    return (int)p->spare.size();
+    return (int)(p->spare.size() + (size_t)p->n_idle);
 }
 
 int pool_create(size_t bytes, int page_tokens) {
@@ -722,8 +775,10 @@ long balloon_resize(int model, long pages) {
             // (they held no block) and the stream is idle (the call above waited for its result)
             std::vector<uint32_t> gone((size_t)(before - r));
             HIP_TRY(hipMemcpy(gone.data(), p.dev.free_stack + p.n_free, gone.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
-            for (uint32_t f : gone) {
-                const int rc = elastic_unmap(p, f);
+            // top of the stack first: those are the frames the next inflate takes, so they are the
+            // ones worth leaving mapped while the buffer has room
+            for (auto it = gone.rbegin(); it != gone.rend(); ++it) {
+                const int rc = elastic_give_back(p, *it);
                 if (rc) return rc;
             }
         }
@@ -1100,6 +1155,7 @@ int pool_stats(int pool, pkv_stats *out) {
     }
     out->mapped_bytes = p->elastic ? p->mapped_frames * (int64_t)p->frame_bytes : p->n_frames * (int64_t)p->frame_bytes;
     out->spare_frames = (int64_t)p->spare.size();
+    out->idle_frames = p->n_idle;
     return PKV_OK;
 }
 

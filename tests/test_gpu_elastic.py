@@ -38,7 +38,7 @@ def gpu():
 
 def mapped_matches_owned(gpu, pool, frame_bytes):
     st = gpu.pool_stats(pool)
-    assert st["mapped_bytes"] == (st["n_frames"] - st["n_free"]) * frame_bytes, st
+    assert st["mapped_bytes"] == (st["n_frames"] - st["n_free"] + st["idle_frames"]) * frame_bytes, st
     return st
 
 
@@ -105,10 +105,18 @@ def test_prealloc_buffer(gpu):
     assert st["spare_frames"] == 2 and st["mapped_bytes"] == 4 * fb
     assert gpu.balloon_resize(m, 10) == 10                   # 2 from the buffer, 4 from the driver
     assert gpu.pool_stats(pool)["spare_frames"] == 0
-    assert gpu.balloon_resize(m, 1) == 1                     # 9 come back: 6 refill the buffer, 3 are released
+    assert gpu.balloon_resize(m, 1) == 1                     # 9 come back: 6 stay mapped in place, 3 are released
     st = gpu.pool_stats(pool)
-    assert st["spare_frames"] == 6 and st["mapped_bytes"] == fb
-    assert gpu.balloon_resize(m, 0) == 0 and gpu.model_unregister(m) == 0 and gpu.pool_destroy(pool) == 0
+    assert st["idle_frames"] == 6 and st["spare_frames"] == 0 and st["mapped_bytes"] == 7 * fb
+    assert gpu.balloon_resize(m, 5) == 5                     # the free stack hands the latest frames out first,
+    st = gpu.pool_stats(pool)                                # and those are the ones that were left mapped
+    assert st["idle_frames"] == 2 and st["mapped_bytes"] == 7 * fb
+    assert gpu.pool_set_prealloc(pool, 0) == 0               # trim: only what is owned stays mapped
+    st = gpu.pool_stats(pool)
+    assert st["idle_frames"] == 0 and st["spare_frames"] == 0 and st["mapped_bytes"] == 5 * fb
+    assert gpu.balloon_resize(m, 0) == 0 and gpu.model_unregister(m) == 0
+    assert gpu.pool_stats(pool)["mapped_bytes"] == 0
+    assert gpu.pool_destroy(pool) == 0
     assert gpu.pool_create_elastic(32 * fb, 16, fb + 512) < 0          # not a multiple of the granularity
 
 
@@ -120,6 +128,7 @@ def test_dynamic_scenarios_on_an_elastic_pool(gpu, oracle, cfg_id):
     cfg = make_config(cfg_id, "small")
     eg = Elastic(gpu)
     rg, ro = Runner(eg, cfg).setup(), Runner(oracle, cfg).setup()
+    assert gpu.pool_set_prealloc(rg.pool, 16) == 16
     try:
         for t in range(cfg.steps):
             rg.step(t)
