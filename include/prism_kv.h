@@ -242,6 +242,33 @@ int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens
 long pool_export_state(int pool, void *host_buf, size_t cap);
 int pool_stats(int pool, pkv_stats *out);
 
+/* ---- policies that drive the balloons (host only; no stream, no device) ---------------- */
+
+/* Slack-aware request arbitration on one GPU (paper Sec. 5.2, Alg. 2: the Moore-Hodgson rule on
+ * prefill deadlines).  Request i waits since arrival[i], must finish its prefill by arrival[i] +
+ * ttft_slo[i], and its prefill takes prompt_len[i] / prefill_speed[i].  Requests are taken in
+ * order of deadline (equal deadlines: lower index first), appended to the schedule S, and
+ * whenever the newcomer would finish after its deadline the request of S with the longest
+ * prefill is dropped (equal lengths: the one earliest in S).  accepted (out, int32 [n], host)
+ * receives the indices of S in dispatch order; returns their number, which is the largest
+ * number of requests that can all meet their deadlines.  All arrays are host arrays. */
+int arbitrate_requests(int n, const double *arrival, const double *ttft_slo, const double *prompt_len,
+                       const double *prefill_speed, double now, int32_t *accepted);
+
+/* Model placement by KV pressure ratio (paper Sec. 5.1, Alg. 1).  Model j asks for memory at
+ * the SLO-weighted rate token_rate[j] * token_size[j] / slo[j] and occupies weight[j] bytes; a
+ * GPU's KV pressure ratio is the summed rate of its models over capacity minus their weights
+ * (infinite once nothing is left).  Models are taken by falling rate (equal: lower index
+ * first); each goes to the GPU of lowest ratio (equal: lower index) unless it already sits on
+ * a GPU (current_gpu[j] >= 0) whose ratio is not more than tau above that: then it stays.
+ * tp_group (NULL or int32 [n_models]): models with the same id >= 0 are parts of one
+ * tensor-parallel model and never share a GPU (PKV_E_RANGE if there are more parts than GPUs);
+ * the caller splits weight and rate among the parts.  gpu_out (int32 [n_models]) receives the
+ * placement; returns n_models.  All arrays are host arrays; current_gpu may be NULL. */
+int place_models(int n_gpus, double capacity, double tau, int n_models, const double *token_rate,
+                 const double *token_size, const double *slo, const double *weight,
+                 const int32_t *current_gpu, const int32_t *tp_group, int32_t *gpu_out);
+
 /* Per-kernel timing for measurements: with every = n > 0, every n-th decode_attention*
  * call brackets its attention kernel with HIP events on the library's stream (at most
  * 8192 calls are recorded); 0 switches it off.  pkv_timing_read waits for the stream,

@@ -66,6 +66,8 @@ def _load():
         "pool_export_state": (l, [i, vp, sz]),
         "pool_stats": (i, [i, vp]),
         "pool_create_elastic": (i, [sz, i, sz]),
+        "arbitrate_requests": (i, [i, vp, vp, vp, vp, C.c_double, vp]),
+        "place_models": (i, [i, C.c_double, C.c_double, i, vp, vp, vp, vp, vp, vp, vp]),
         "pool_set_prealloc": (i, [i, l]),
     }
     for name, (res, args) in sig.items():
@@ -81,7 +83,38 @@ EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_spl
            "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
            "seq_release", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
-           "decode_attention_ex", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats"]
+           "decode_attention_ex", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats",
+           "arbitrate_requests", "place_models"]
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def arbitrate_requests(arrival, ttft_slo, prompt_len, prefill_speed, now, lib=None):
+    """Host-only policy call (needs no GPU): -> list of accepted request indices in dispatch order."""
+    lib = lib or _load()
+    a, s, p, c = _f64(arrival), _f64(ttft_slo), _f64(prompt_len), _f64(prefill_speed)
+    out = np.zeros(max(a.size, 1), dtype=np.int32)
+    ptr = lambda x: x.ctypes.data_as(C.c_void_p)
+    m = lib.arbitrate_requests(a.size, ptr(a), ptr(s), ptr(p), ptr(c), float(now), ptr(out))
+    if m < 0:
+        raise ValueError(f"arbitrate_requests: {m}")
+    return out[:m].tolist()
+
+
+def place_models(n_gpus, capacity, tau, token_rate, token_size, slo, weight, current_gpu=None, tp_group=None, lib=None):
+    """Host-only policy call (needs no GPU): -> list of GPU indices, one per model."""
+    lib = lib or _load()
+    t, z, s, w = _f64(token_rate), _f64(token_size), _f64(slo), _f64(weight)
+    ptr = lambda x: None if x is None else x.ctypes.data_as(C.c_void_p)
+    cur = None if current_gpu is None else np.ascontiguousarray(current_gpu, dtype=np.int32)
+    tp = None if tp_group is None else np.ascontiguousarray(tp_group, dtype=np.int32)
+    out = np.full(max(t.size, 1), -1, dtype=np.int32)
+    rc = lib.place_models(int(n_gpus), float(capacity), float(tau), t.size, ptr(t), ptr(z), ptr(s), ptr(w), ptr(cur), ptr(tp), ptr(out))
+    if rc < 0:
+        raise ValueError(f"place_models: {rc}")
+    return out[:t.size].tolist()
 
 
 class PrismKV:

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprismkv.so")
-SOURCES = ["api.hip", "pool_kernels.hip", "attn_kernels.hip", "kv_kernels.hip"]
+SOURCES = ["api.hip", "pool_kernels.hip", "attn_kernels.hip", "kv_kernels.hip", "policy.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", 
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          # keep single-lane atomics as written: the optimiser would broadcast their result at once,
