@@ -189,6 +189,28 @@ def prefill_leg(gpu, torch):
             "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tf / 2500.0, 4)}}
 
 
+def policy_leg():
+    """Host time of the two policy calls at serving-loop sizes (no GPU work)."""
+    import numpy as np
+    from paper_2505_04021_amd import binding
+    rng = np.random.default_rng(7)
+    n = 1000
+    arrival, slo = rng.uniform(0, 5, n), rng.choice([0.5, 1.0, 2.0, 4.0], n)
+    p, c = rng.integers(1, 64, n) * 32.0, rng.choice([256.0, 512.0, 1024.0], n)
+    t0 = time.perf_counter()
+    for _ in range(50):
+        acc = binding.arbitrate_requests(arrival, slo, p, c, 2.5)
+    t1 = time.perf_counter()
+    M = 64
+    rate, size, s_, w = rng.uniform(1, 100, M), np.ones(M), rng.choice([0.05, 0.1], M), rng.uniform(1, 20, M)
+    cur = rng.integers(-1, 8, M).astype(np.int32)
+    for _ in range(50):
+        binding.place_models(8, 288.0, 0.05, rate, size, s_, w, cur)
+    t2 = time.perf_counter()
+    return {"arbitrate_1000_requests_us": round((t1 - t0) / 50 * 1e6, 1), "accepted": len(acc),
+            "place_64_models_8_gpus_us": round((t2 - t1) / 50 * 1e6, 1), "kind": "host wall clock per call through the binding"}
+
+
 def cpu_baseline(rep, seconds):
     """The oracle, as it stands, on the same workload: the same bookkeeping calls and
     KV, decode attention of every model's batch on all host cores, repeated with the
@@ -317,6 +339,7 @@ def main():
         result["balloon_resize"] = balloon_latency(gpu, torch)
         result["kv_append"] = append_latency(gpu, torch, reps[0], inputs[0])
         result["prefill_attention"] = prefill_leg(gpu, torch)
+        result["policies"] = policy_leg()
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(reps[0], args.cpu_seconds)
     for rep in reps:
