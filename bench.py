@@ -9,7 +9,10 @@ default workload is cfg 2 (two co-located models, lognormal context lengths); th
 independently seeded replicas are rotated so that a step never re-reads what the
 previous step left in the 256 MB Infinity Cache.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: the headline metric (KV bytes read per second by a decode step), `roofline`
+(the attention kernel against the HBM peak, with its measured traffic), `cpu_baseline` (the CPU
+oracle timed on the host cores), the measured read ceilings, and secondary legs: balloon_resize
+latency (ordinary and elastic pools), kv_append, chunked-prefill attention, the host policies.
 """
 import argparse
 import json

@@ -399,12 +399,6 @@ struct RowInfo {
     int seq, q0, back, ntok;
 };
 
-__device__ __forceinline__ RowInfo row_info(const AttnDesc &d, int row) {
-    if (!d.vmap) return RowInfo{row, row, 0, 1};
-    const int4 v = d.vmap[row];
-    return RowInfo{v.x, v.y, v.z, v.w};
-}
-
 __device__ __forceinline__ RowInfo row_info_uniform(const AttnDesc &d, int row) {
     if (!d.vmap) return RowInfo{row, row, 0, 1};
     const int32_t *v = reinterpret_cast<const int32_t *>(d.vmap + row);
@@ -919,7 +913,6 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                         w[g * D + g + n] = l;
                     }
                 }
-#if !defined(PKV_EXP_NO_MERGE)
                 // The partials and the arrival counters live in uncached device memory, so every
                 // access goes to memory itself and is visible to all XCDs without flushing an L2.
                 // Order is all that is left to enforce: the partial must have landed before the
@@ -934,7 +927,6 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                 pd.k0 = k0;
                 pd.k1 = k1;
                 pd.arrived = arrived;
-#endif
             }
         }
         cur = nxt;
