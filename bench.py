@@ -13,6 +13,10 @@ Prints ONE JSON line: the headline metric (KV bytes read per second by a decode 
 (the attention kernel against the HBM peak, with its measured traffic), `cpu_baseline` (the CPU
 oracle timed on the host cores), the measured read ceilings, and secondary legs: balloon_resize
 latency (ordinary and elastic pools), kv_append, chunked-prefill attention, the host policies.
+
+`--config 3` runs the bursty scenario instead (bookkeeping events between the decode launches,
+a model mix that changes from step to step); `--frame-bytes` overrides a workload's frame size
+(65536 = one or two blocks per frame: the most scattered pool).
 """
 import argparse
 import json
@@ -31,7 +35,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 4, 5])
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="3 = the bursty scenario: bookkeeping events and decode of the active models, step by step")
+    ap.add_argument("--frame-bytes", type=int, default=0, help="override the workload's frame size (0 = as configured)")
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--replicas", type=int, default=3)
     ap.add_argument("--items", type=int, default=0, help="work items (waves) per attention launch (0 = automatic)")
@@ -57,13 +63,15 @@ def profiled_traffic(workload, size):
     return int(m.group(1)) if m else None
 
 
-def build_replicas(gpu, cfg_id, size, n):
+def build_replicas(gpu, cfg_id, size, n, frame_bytes=0):
     import copy
     from workloads.scenarios import Runner, make_config
     reps = []
     for r in range(n):
         cfg = copy.deepcopy(make_config(cfg_id, size))
         cfg.seed += 17 * r
+        if frame_bytes:
+            cfg.frame_bytes = frame_bytes
         t0 = time.time()
         reps.append(Runner(gpu, cfg).setup())
         print(f"[bench] replica {r}: pool {cfg.pool_bytes >> 20} MiB, KV {reps[-1].kv_bytes_step() / 1e9:.3f} GB, "
@@ -240,6 +248,77 @@ def cpu_baseline(rep, seconds):
                       f"{t_total:.1f} s in total, fp64, {orc.num_threads()} OpenMP threads)"}
 
 
+def bursty_run(gpu, torch, args):
+    """The bursty scenario (models switch on and off by a two-state Markov chain): each
+    step first applies its bookkeeping events (release + deflate of a model that went idle,
+    inflate + admission of one that woke up), then decodes every active model in one
+    launch.  The KV cache keeps whatever the pool memory holds (the values do not change
+    the time), queries are drawn once per model.  `value` counts the KV bytes of the
+    decoded steps over the whole wall time, events included."""
+    import numpy as np
+    from workloads.scenarios import Runner, make_config
+    cfg = make_config(3, args.size)
+    if args.frame_bytes:
+        cfg.frame_bytes = args.frame_bytes
+    total = args.warmup + args.steps
+    if total > cfg.steps:
+        print(f"bench.py: the scenario has {cfg.steps} steps; --warmup + --steps is {total}", file=sys.stderr)
+        sys.exit(2)
+    r = Runner(gpu, cfg, write_kv=False).setup()
+    qs = [torch.from_numpy(r.queries(0, mi).view(np.int16)).cuda() for mi in range(len(cfg.models))]
+    outs = [torch.empty((s.batch, s.q_heads, s.head_dim), dtype=torch.float32, device="cuda") for s in cfg.models]
+    ctxs = [torch.zeros(s.batch, dtype=torch.int32, device="cuda") for s in cfg.models]
+    uids = [None] * len(cfg.models)
+
+    def step(t):
+        r.step(t)
+        act = r.active_models()
+        for mi in act:
+            if uids[mi] is None or not np.array_equal(uids[mi], r.uid[mi]):    # a new batch was admitted
+                ctxs[mi].copy_(torch.from_numpy(r.ctx[mi]))
+                uids[mi] = r.uid[mi].copy()
+        if act:
+            rc = gpu.decode_attention_multi_dev([r.models[mi] for mi in act], [qs[mi] for mi in act],
+                                                [ctxs[mi] for mi in act], [outs[mi] for mi in act])
+            assert rc == 0, (rc, gpu.last_error())
+        return r.kv_bytes_step() if act else 0, len(act)
+
+    gpu.tune_xcd(min(args.tune, args.warmup))
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    n_events0 = len(r.log)
+    gpu.timing_enable(1)
+    kv, active, launches = 0, 0, 0
+    t0 = time.perf_counter()
+    for t in range(args.warmup, total):
+        b, a = step(t)
+        kv += b
+        active += a
+        launches += 1 if a else 0
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    n_rec, attn_ms = gpu.timing_read()
+    gpu.timing_enable(False)
+    assert gpu.device_errors() == 0 and n_rec == launches
+    attn_gbps = kv / (attn_ms * 1e-3) / 1e9 if n_rec else 0.0
+    result = {
+        "metric": "kv_read_gbps_multi_model_paged_decode", "value": round(kv / wall / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "cfg": 3, "size": args.size, "frame_bytes": cfg.frame_bytes,
+                   "pool_bytes": cfg.pool_bytes, "models": len(cfg.models),
+                   "mean_active_models": round(active / args.steps, 2), "decode_launches": launches,
+                   "bookkeeping_calls": len(r.log) - n_events0,
+                   "kv_bytes_per_launch": int(kv / max(launches, 1))},
+        "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "avg_launch_us": round(attn_ms / max(n_rec, 1) * 1e3, 2), "launches": n_rec},
+    }
+    r.teardown()
+    print(json.dumps(result), flush=True)
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -254,7 +333,9 @@ def main():
     if args.page_cost >= 0:
         gpu.set_page_cost(args.page_cost)
     gpu.set_segment_cost(args.seg_cost)
-    reps = build_replicas(gpu, args.config, args.size, args.replicas)
+    if args.config == 3:
+        return bursty_run(gpu, torch, args)
+    reps = build_replicas(gpu, args.config, args.size, args.replicas, args.frame_bytes)
     inputs = [device_inputs(torch, rep, 0) for rep in reps]
     kv_per_rep = [rep.kv_bytes_step() for rep in reps]
 
@@ -324,6 +405,7 @@ def main():
         "dtype": "bf16" if args.config != 5 else "fp8_e4m3",
         "data": "synthetic",
         "config": {"workload": reps[0].cfg.name, "cfg": args.config, "size": args.size,
+                   "frame_bytes": reps[0].cfg.frame_bytes,
                    "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
                    "work_items": args.items or "auto", "xcd_tune_launches": args.tune,
                    "xcd_weights": [round(x, 3) for x in gpu.get_xcd_weights()]},
@@ -332,7 +414,7 @@ def main():
         "device_ms_per_step": round(dev_ms / args.steps, 5),
         "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": profiled_traffic(reps[0].cfg.name, args.size),
+                     "traffic": None if args.frame_bytes else profiled_traffic(reps[0].cfg.name, args.size),
                      "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": n_rec},
     }
     result["read_ceiling_gbps"] = {"stream": round(gpu.stream_read_probe(4 << 30, 0, 10), 1),
