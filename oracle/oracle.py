@@ -34,6 +34,9 @@ def _load():
         "orc_pool_seed_free_order": (i, [i, vp, sz]),
         "orc_model_register": (i, [i, i, i, i, i]),
         "orc_model_register_ex": (i, [i, i, i, i, i, i, i]),
+        "orc_model_register_layers": (i, [i, i, i, i, i, i, i, i]),
+        "orc_set_layer": (i, [i, i]),
+        "orc_model_layers": (i, [i]),
         "orc_model_unregister": (i, [i]),
         "orc_balloon_resize": (l, [i, l]),
         "orc_seq_reserve": (i, [i, i, i]),
@@ -100,8 +103,11 @@ class Oracle:
         return self.lib.orc_pool_seed_free_order(pool, _ptr(perm), perm.size)
 
     # ---- models
-    def model_register(self, pool, q_heads, kv_heads, head_dim, dtype, max_seqs=None, max_blocks=None):
-        if max_seqs is None and max_blocks is None:
+    def model_register(self, pool, q_heads, kv_heads, head_dim, dtype, max_seqs=None, max_blocks=None, n_layers=1):
+        if n_layers != 1:
+            m = self.lib.orc_model_register_layers(pool, q_heads, kv_heads, head_dim, dtype,
+                                                   max_seqs or 256, max_blocks or 2048, n_layers)
+        elif max_seqs is None and max_blocks is None:
             m = self.lib.orc_model_register(pool, q_heads, kv_heads, head_dim, dtype)
         else:
             m = self.lib.orc_model_register_ex(pool, q_heads, kv_heads, head_dim, dtype,
@@ -109,6 +115,9 @@ class Oracle:
         if m >= 0:
             self._shape[m] = (q_heads, kv_heads, head_dim, dtype)
         return m
+
+    def set_layer(self, model, layer):
+        return self.lib.orc_set_layer(model, layer)
 
     def model_unregister(self, model):
         return self.lib.orc_model_unregister(model)

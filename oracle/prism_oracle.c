@@ -57,7 +57,9 @@ typedef struct {
     int live;
     int pool;
     int Hq, Hkv, D, dtype, g;
-    size_t block_bytes;
+    int L, layer;       /* layers sharing one block table; the layer the KV calls address */
+    size_t layer_bytes; /* one layer's part of a block */
+    size_t block_bytes; /* all layers: L * layer_bytes */
     int slots;          /* blocks per frame */
     long owned;
     uint32_t *frames;   /* acquisition order */
@@ -148,11 +150,16 @@ int orc_pool_seed_free_order(int pool, const uint32_t *perm, size_t n) {
 
 /* ----------------------------------------------------------------- model */
 
-int orc_model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
-                          int max_seqs, int max_blocks_per_seq) {
+/* Sec. 4.2, D3 (first optimisation): a model of L layers keeps the K and V of all its
+ * layers for one token block side by side, so one block id, one slot and one block-table
+ * row serve every layer, and a reserve is one allocation instead of 2L.  Here a block is
+ * L consecutive layer parts; the part of layer l starts l * layer_bytes into the block. */
+int orc_model_register_layers(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
+                              int max_seqs, int max_blocks_per_seq, int n_layers) {
     pool_t *p = get_pool(pool);
     if (!p) return ORC_E_HANDLE;
-    if (q_heads <= 0 || kv_heads <= 0 || head_dim <= 0 || max_seqs <= 0 || max_blocks_per_seq <= 0)
+    if (q_heads <= 0 || kv_heads <= 0 || head_dim <= 0 || max_seqs <= 0 || max_blocks_per_seq <= 0 ||
+        n_layers <= 0)
         return ORC_E_ARG;
     if (dtype != ORC_BF16 && dtype != ORC_E4M3) return ORC_E_ARG;
     if (q_heads % kv_heads != 0) return ORC_E_SHAPE;
@@ -162,6 +169,8 @@ int orc_model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int
         if ((size_t)kv_heads * 2 * sizeof(float) > ORC_FP8_HEADER) return ORC_E_SHAPE;
         block_bytes += ORC_FP8_HEADER;
     }
+    const size_t layer_bytes = block_bytes;
+    block_bytes *= (size_t)n_layers;
     size_t slots = p->frame_bytes / block_bytes;
     if (slots == 0) return ORC_E_SHAPE;
     int id = -1;
@@ -173,6 +182,9 @@ int orc_model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int
     m->pool = pool;
     m->Hq = q_heads; m->Hkv = kv_heads; m->D = head_dim; m->dtype = dtype;
     m->g = q_heads / kv_heads;
+    m->L = n_layers;
+    m->layer = 0;
+    m->layer_bytes = layer_bytes;
     m->block_bytes = block_bytes;
     m->slots = (int)slots;
     m->max_seqs = max_seqs;
@@ -182,6 +194,20 @@ int orc_model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int
     if (!m->rows || !m->row_len) { free(m->rows); free(m->row_len); return ORC_E_NOMEM; }
     m->live = 1;
     return id;
+}
+
+int orc_model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
+                          int max_seqs, int max_blocks_per_seq) {
+    return orc_model_register_layers(pool, q_heads, kv_heads, head_dim, dtype, max_seqs, max_blocks_per_seq, 1);
+}
+
+/* the layer that kv_write / kv_append / kv_read and the attention calls address from now on */
+int orc_set_layer(int model, int layer) {
+    model_t *m = get_model(model);
+    if (!m) return ORC_E_HANDLE;
+    if (layer < 0 || layer >= m->L) return ORC_E_ARG;
+    m->layer = layer;
+    return ORC_OK;
 }
 
 int orc_model_register(int pool, int q_heads, int kv_heads, int head_dim, int dtype) {
@@ -346,10 +372,11 @@ int orc_seq_release(int model, int seq) {
 
 /* -------------------------------------------------------- addressing, KV */
 
-/* byte offset of a block inside the pool */
+/* byte offset, inside the pool, of the current layer's part of a block */
 static size_t block_addr(const model_t *m, const pool_t *p, int32_t block_id) {
     return (size_t)(block_id / m->slots) * p->frame_bytes +
-           (size_t)(block_id % m->slots) * m->block_bytes;
+           (size_t)(block_id % m->slots) * m->block_bytes +
+           (size_t)m->layer * m->layer_bytes;
 }
 
 /* in-block layout: [e4m3 only: 128 B header] then [kvh][K|V][token slot][d] */
@@ -775,6 +802,7 @@ long orc_pool_n_free(int pool) { pool_t *p = get_pool(pool); return p ? p->n_fre
 long orc_model_owned(int model) { model_t *m = get_model(model); return m ? m->owned : ORC_E_HANDLE; }
 int orc_model_slots(int model) { model_t *m = get_model(model); return m ? m->slots : ORC_E_HANDLE; }
 long orc_model_block_bytes(int model) { model_t *m = get_model(model); return m ? (long)m->block_bytes : ORC_E_HANDLE; }
+int orc_model_layers(int model) { model_t *m = get_model(model); return m ? m->L : ORC_E_HANDLE; }
 long orc_block_address(int model, int block_id) {
     model_t *m = get_model(model);
     if (!m) return ORC_E_HANDLE;

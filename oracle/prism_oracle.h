@@ -53,6 +53,12 @@ int orc_pool_seed_free_order(int pool, const uint32_t *perm, size_t n);
 int orc_model_register(int pool, int q_heads, int kv_heads, int head_dim, int dtype);
 int orc_model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
                           int max_seqs, int max_blocks_per_seq);
+/* a model of n_layers layers: every block holds all layers' K and V (Sec. 4.2, D3), one
+ * block table serves them all; orc_set_layer picks the layer the KV and attention calls address */
+int orc_model_register_layers(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
+                              int max_seqs, int max_blocks_per_seq, int n_layers);
+int orc_set_layer(int model, int layer);
+int orc_model_layers(int model);
 int orc_model_unregister(int model);
 
 long orc_balloon_resize(int model, long frames);
