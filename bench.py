@@ -38,6 +38,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="3 = the bursty scenario: bookkeeping events and decode of the active models, step by step")
     ap.add_argument("--frame-bytes", type=int, default=0, help="override the workload's frame size (0 = as configured)")
+    ap.add_argument("--layers", type=int, default=1,
+                    help="layers per model sharing its block table; step i attends to layer i mod layers of every model")
     ap.add_argument("--size", default="full", choices=["full", "small"])
     ap.add_argument("--replicas", type=int, default=3)
     ap.add_argument("--items", type=int, default=0, help="work items (waves) per attention launch (0 = automatic)")
@@ -63,7 +65,7 @@ def profiled_traffic(workload, size):
     return int(m.group(1)) if m else None
 
 
-def build_replicas(gpu, cfg_id, size, n, frame_bytes=0):
+def build_replicas(gpu, cfg_id, size, n, frame_bytes=0, layers=1):
     import copy
     from workloads.scenarios import Runner, make_config
     reps = []
@@ -72,6 +74,8 @@ def build_replicas(gpu, cfg_id, size, n, frame_bytes=0):
         cfg.seed += 17 * r
         if frame_bytes:
             cfg.frame_bytes = frame_bytes
+        for spec in cfg.models:
+            spec.layers = layers
         t0 = time.time()
         reps.append(Runner(gpu, cfg).setup())
         print(f"[bench] replica {r}: pool {cfg.pool_bytes >> 20} MiB, KV {reps[-1].kv_bytes_step() / 1e9:.3f} GB, "
@@ -335,12 +339,15 @@ def main():
     gpu.set_segment_cost(args.seg_cost)
     if args.config == 3:
         return bursty_run(gpu, torch, args)
-    reps = build_replicas(gpu, args.config, args.size, args.replicas, args.frame_bytes)
+    reps = build_replicas(gpu, args.config, args.size, args.replicas, args.frame_bytes, args.layers)
     inputs = [device_inputs(torch, rep, 0) for rep in reps]
     kv_per_rep = [rep.kv_bytes_step() for rep in reps]
 
     def step(i):
         mids, qs, ctxs, outs = inputs[i % len(reps)]
+        if args.layers > 1:
+            for m in mids:
+                gpu.set_layer(m, (i // len(reps)) % args.layers)
         rc = gpu.decode_attention_multi_dev(mids, qs, ctxs, outs)
         assert rc == 0, (rc, gpu.last_error())
 
@@ -405,7 +412,7 @@ def main():
         "dtype": "bf16" if args.config != 5 else "fp8_e4m3",
         "data": "synthetic",
         "config": {"workload": reps[0].cfg.name, "cfg": args.config, "size": args.size,
-                   "frame_bytes": reps[0].cfg.frame_bytes,
+                   "frame_bytes": reps[0].cfg.frame_bytes, "layers": args.layers,
                    "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
                    "work_items": args.items or "auto", "xcd_tune_launches": args.tune,
                    "xcd_weights": [round(x, 3) for x in gpu.get_xcd_weights()]},
@@ -414,7 +421,7 @@ def main():
         "device_ms_per_step": round(dev_ms / args.steps, 5),
         "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None if args.frame_bytes else profiled_traffic(reps[0].cfg.name, args.size),
+                     "traffic": None if args.frame_bytes or args.layers > 1 else profiled_traffic(reps[0].cfg.name, args.size),
                      "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": n_rec},
     }
     result["read_ceiling_gbps"] = {"stream": round(gpu.stream_read_probe(4 << 30, 0, 10), 1),

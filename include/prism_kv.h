@@ -116,6 +116,18 @@ int pool_seed_free_order(int pool, const uint32_t *perm, size_t n);
 int model_register(int q_heads, int kv_heads, int head_dim, int dtype);
 int model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
                       int max_seqs, int max_blocks_per_seq);
+/* A model of n_layers layers (paper Sec. 4.2, D3, first optimisation: the K and V of all
+ * layers of a token block lie side by side, so one allocation serves every layer instead of
+ * 2L).  A block is n_layers consecutive one-layer blocks (each laid out as for a one-layer
+ * model, the e4m3 header included); block ids, slots, the block table and every bookkeeping
+ * call are shared by the layers, frames hold frame_bytes / (n_layers * layer bytes) blocks
+ * (PKV_E_SHAPE if that is zero).  pkv_set_layer picks the layer (0 at registration) that
+ * kv_write, kv_append, kv_append_chunk, kv_read, decode_attention, decode_attention_multi
+ * and prefill_attention address from then on; it is host state only (no device work,
+ * PKV_E_ARG outside 0..n_layers-1) and takes effect for calls enqueued after it. */
+int model_register_layers(int pool, int q_heads, int kv_heads, int head_dim, int dtype,
+                          int max_seqs, int max_blocks_per_seq, int n_layers);
+int pkv_set_layer(int model, int layer);
 /* The model must own no frames (PKV_E_BUSY otherwise). */
 int model_unregister(int model);
 

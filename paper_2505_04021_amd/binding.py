@@ -48,6 +48,8 @@ def _load():
         "pool_seed_free_order": (i, [i, vp, sz]),
         "model_register": (i, [i, i, i, i]),
         "model_register_ex": (i, [i, i, i, i, i, i, i]),
+        "model_register_layers": (i, [i, i, i, i, i, i, i, i]),
+        "pkv_set_layer": (i, [i, i]),
         "model_unregister": (i, [i]),
         "balloon_resize": (l, [i, l]),
         "seq_reserve": (i, [i, i, i]),
@@ -81,7 +83,7 @@ EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_spl
            "pkv_set_xcd_weights", "pkv_get_xcd_weights", "pkv_tune_xcd", "pkv_set_segment_cost",
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_destroy", "pool_seed_free_order", "model_register",
-           "model_register_ex", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
+           "model_register_ex", "model_register_layers", "pkv_set_layer", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
            "seq_release", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
            "decode_attention_ex", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats",
            "arbitrate_requests", "place_models"]
@@ -228,11 +230,15 @@ class PrismKV:
         return self.lib.pool_seed_free_order(pool, perm.ctypes.data_as(C.c_void_p), perm.size)
 
     # ---- models
-    def model_register(self, pool, q_heads, kv_heads, head_dim, dtype, max_seqs=None, max_blocks=None):
-        m = self.lib.model_register_ex(pool, q_heads, kv_heads, head_dim, dtype, max_seqs or 256, max_blocks or 2048)
+    def model_register(self, pool, q_heads, kv_heads, head_dim, dtype, max_seqs=None, max_blocks=None, n_layers=1):
+        m = self.lib.model_register_layers(pool, q_heads, kv_heads, head_dim, dtype, max_seqs or 256,
+                                           max_blocks or 2048, n_layers)
         if m >= 0:
             self._shape[m] = (q_heads, kv_heads, head_dim, dtype)
         return m
+
+    def set_layer(self, model, layer):
+        return self.lib.pkv_set_layer(model, layer)
 
     def model_unregister(self, model):
         return self.lib.model_unregister(model)

@@ -41,7 +41,9 @@ struct Model {
     bool live = false;
     int pool = -1;
     int Hq = 0, Hkv = 0, D = 0, dtype = 0, g = 0;
-    size_t block_bytes = 0;
+    int L = 1, layer = 0;                   // layers sharing the block table; the layer the KV calls address
+    size_t layer_bytes = 0;                 // one layer's part of a block
+    size_t block_bytes = 0;                 // all layers: L * layer_bytes
     int slots = 0;
     int batch = 0, row_stride = 0;          // model_set_batch
     int64_t owned = 0;                      // shadow of the device counter
@@ -173,7 +175,7 @@ constexpr int kDefaultSegCost = 6;
 // page, so a model of small pages needs more waves than its bytes alone suggest.
 double est_bytes(const Model &m, bool own, int batch, int row_stride) {
     const double blocks = own ? (double)m.used_blocks : (double)batch * row_stride;
-    const double page_kib = (double)m.block_bytes / m.Hkv / 1024.0;
+    const double page_kib = (double)m.layer_bytes / m.Hkv / 1024.0;
     return blocks * m.Hkv * (g_page_cost + 0.1 * page_kib);
 }
 
@@ -183,7 +185,7 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
               const int32_t *ctx_lens, float *out, double share_of_launch, int cols = 0, double units_hint = 0.0) {
     Pool &p = g_pools[m.pool];
     const bool own = table == nullptr;
-    d.pool_base = p.base;
+    d.pool_base = p.base + (size_t)m.layer * m.layer_bytes;      // the layer's part of every block
     d.q = (const uint16_t *)q;
     d.table = own ? m.dev.rows : table;
     d.row_stride = own ? m.dev.max_blocks : row_stride;
@@ -675,9 +677,23 @@ int pool_seed_free_order(int pool, const uint32_t *perm, size_t n) {
 
 int model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dtype, int max_seqs,
                       int max_blocks_per_seq) {
+    return model_register_layers(pool, q_heads, kv_heads, head_dim, dtype, max_seqs, max_blocks_per_seq, 1);
+}
+
+int pkv_set_layer(int model, int layer) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (layer < 0 || layer >= m->L) return PKV_E_ARG;
+    m->layer = layer;
+    return PKV_OK;
+}
+
+int model_register_layers(int pool, int q_heads, int kv_heads, int head_dim, int dtype, int max_seqs,
+                          int max_blocks_per_seq, int n_layers) {
     Pool *p = get_pool(pool);
     if (!p) return PKV_E_HANDLE;
-    if (q_heads <= 0 || kv_heads <= 0 || head_dim <= 0 || max_seqs <= 0 || max_blocks_per_seq <= 0)
+    if (q_heads <= 0 || kv_heads <= 0 || head_dim <= 0 || max_seqs <= 0 || max_blocks_per_seq <= 0 ||
+        n_layers <= 0)
         return PKV_E_ARG;
     if (dtype != PKV_BF16 && dtype != PKV_E4M3) return PKV_E_ARG;
     if (max_seqs > PKV_MAX_SEQS) return PKV_E_ARG;
@@ -688,6 +704,8 @@ int model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dty
         if ((size_t)kv_heads * 2 * sizeof(float) > PKV_FP8_HEADER) return PKV_E_SHAPE;
         block_bytes += PKV_FP8_HEADER;
     }
+    const size_t layer_bytes = block_bytes;
+    block_bytes *= (size_t)n_layers;
     const size_t slots = p->frame_bytes / block_bytes;
     if (slots == 0) return PKV_E_SHAPE;
     // what the gfx950 kernels are built for
@@ -699,6 +717,8 @@ int model_register_ex(int pool, int q_heads, int kv_heads, int head_dim, int dty
     Model m;
     m.pool = pool;
     m.Hq = q_heads; m.Hkv = kv_heads; m.D = head_dim; m.dtype = dtype; m.g = q_heads / kv_heads;
+    m.L = n_layers;
+    m.layer_bytes = layer_bytes;
     m.block_bytes = block_bytes;
     m.slots = (int)slots;
     m.row_len.assign(max_seqs, 0);
@@ -848,7 +868,7 @@ int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const 
     Pool &p = g_pools[m->pool];
     if (((int64_t)tok_begin + n_tok + p.T - 1) / p.T > m->row_len[seq]) return PKV_E_RANGE;
     AttnDesc d{};
-    d.pool_base = p.base;
+    d.pool_base = p.base + (size_t)m->layer * m->layer_bytes;
     d.table = m->dev.rows;
     d.row_stride = m->dev.max_blocks;
     d.frame_bytes = p.frame_bytes;
@@ -862,7 +882,7 @@ int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const 
 // the part of a descriptor that addressing a model's own blocks needs
 static void fill_addressing(AttnDesc &d, const Model &m) {
     const Pool &p = g_pools[m.pool];
-    d.pool_base = p.base;
+    d.pool_base = p.base + (size_t)m.layer * m.layer_bytes;
     d.table = m.dev.rows;
     d.row_stride = m.dev.max_blocks;
     d.row_len = m.dev.row_len;

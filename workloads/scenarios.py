@@ -33,6 +33,7 @@ class ModelSpec:
     head_dim: int
     dtype: int
     batch: int
+    layers: int = 1               # layers sharing the model's block table (one block holds them all)
 
 
 @dataclass
@@ -62,7 +63,7 @@ class Config:
 
 def block_bytes(spec: ModelSpec, page_tokens: int) -> int:
     e = 2 if spec.dtype == gen.BF16 else 1
-    return 2 * page_tokens * spec.kv_heads * spec.head_dim * e + (128 if spec.dtype == gen.E4M3 else 0)
+    return spec.layers * (2 * page_tokens * spec.kv_heads * spec.head_dim * e + (128 if spec.dtype == gen.E4M3 else 0))
 
 
 def make_config(cfg: int, size: str = "full") -> Config:
@@ -140,6 +141,7 @@ class Runner:
         self.next_uid = [0] * n
         self.active = [False] * n
         self.blocks = [0] * n         # blocks currently reserved per model
+        self.layer = [0] * n          # current layer per model
         self.slots: List[int] = []
         self.activity = None
 
@@ -200,10 +202,24 @@ class Runner:
             self.ctx[mi][s] = n_tok
             self.blocks[mi] += int(self._blocks(n_tok))
             if self.write_kv and self._wants(mi, u):
-                kv = gen.seq_kv((c.seed, 13, mi, u), int(n_tok), spec.kv_heads, spec.head_dim,
-                                spec.dtype, c.page_tokens, c.peak_frac)
-                self._need("kv_write", self.be.kv_write(m, int(s), 0, kv["k"], kv["v"],
-                                                        kv["k_scale"], kv["v_scale"]))
+                for layer in range(spec.layers):
+                    kv = gen.seq_kv(self.kv_key(mi, u, layer), int(n_tok), spec.kv_heads, spec.head_dim,
+                                    spec.dtype, c.page_tokens, c.peak_frac)
+                    if spec.layers > 1:
+                        self._need("set_layer", self.be.set_layer(m, layer))
+                    self._need("kv_write", self.be.kv_write(m, int(s), 0, kv["k"], kv["v"],
+                                                            kv["k_scale"], kv["v_scale"]))
+        if spec.layers > 1:
+            self.set_layer(mi, self.layer[mi])
+
+    def kv_key(self, mi, uid, layer=0):
+        """Seed key of the KV of sequence uid of model mi at a layer."""
+        return (self.cfg.seed, 13, mi, int(uid)) + ((layer,) if layer else ())
+
+    def set_layer(self, mi, layer):
+        """The layer of model mi that attention and KV calls address from now on."""
+        self.layer[mi] = layer
+        return self._need("set_layer", self.be.set_layer(self.models[mi], layer))
 
     def _release(self, mi, seqs):
         for s in seqs:
@@ -223,9 +239,10 @@ class Runner:
         perm = gen.free_order(n_frames, gen.generator(c.seed, 1))
         self._need("pool_seed_free_order", be.pool_seed_free_order(self.pool, perm))
         for spec in c.models:
+            more = {"n_layers": spec.layers} if spec.layers > 1 else {}
             m = self._need("model_register", be.model_register(
                 self.pool, spec.q_heads, spec.kv_heads, spec.head_dim, spec.dtype,
-                c.max_seqs, c.max_blocks))
+                c.max_seqs, c.max_blocks, **more))
             self.models.append(m)
             self.slots.append(c.frame_bytes // block_bytes(spec, c.page_tokens))
         if c.cfg == 3:
