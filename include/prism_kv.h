@@ -15,6 +15,8 @@
  *           paper's token block / KV block, Background "KV cache and
  *           PagedAttention").  block_bytes = 2*page_tokens*kv_heads*head_dim*e,
  *           e = 2 for bf16 and 1 for e4m3, plus a 128-byte scale header for e4m3.
+ *           A model registered with several layers keeps all of them in the block
+ *           (n_layers times those bytes, see model_register_layers).
  *   slot    place for one block inside a frame; slots = frame_bytes / block_bytes.
  *   block id = frame * slots + slot  (what block tables hold).
  *
