@@ -310,11 +310,15 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
 // line of code the scheduler can overlap the matrix instructions of one tile with the
 // softmax arithmetic of another.
 template <int D, int DT>
-__device__ __forceinline__ void pair_scores(State<D, DT> &st, const PairRegs<D, DT> &r, const bf16x8 *qf, float scale_log2,
-                                            bf16x8 &phv, bf16x8 &plv) {
+__device__ __forceinline__ void pair_qk(const PairRegs<D, DT> &r, const bf16x8 *qf, f32x4 &sa, f32x4 &sb) {
+    sa = qk_page<D, DT>(r.a, qf);
+    sb = qk_page<D, DT>(r.b, qf);
+}
+
+template <int D, int DT>
+__device__ __forceinline__ void pair_softmax(State<D, DT> &st, const PairRegs<D, DT> &r, f32x4 sa, f32x4 sb, float scale_log2,
+                                             bf16x8 &phv, bf16x8 &plv) {
     using TL = Tile<D, DT>;
-    f32x4 sa = qk_page<D, DT>(r.a, qf);
-    f32x4 sb = qk_page<D, DT>(r.b, qf);
     const float sca = DT == PKV_E4M3 ? scale_log2 * r.a.sk : scale_log2;
     const float scb = DT == PKV_E4M3 ? scale_log2 * r.b.sk : scale_log2;
     float s[8];
@@ -1112,72 +1116,102 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
 #if defined(PKV_TRACE)
     uint64_t tr_read = 0, tr_math = 0, tr_sync = 0, tr_steps = 0;
 #endif
-    auto step = [&](int p, const uint8_t *buf, uint8_t *refill) {
+    // Operand registers of the pair being worked on.  The K tiles are read from LDS one step
+    // ahead, right after the scores of the current pair have been issued (the registers are free
+    // from then on), so that a step starts its matrix work without waiting for LDS; the V tiles
+    // are read at the same point and arrive while the softmax arithmetic runs.
+    PairRegs<D, DT> r;
+    r.a.sk = r.a.sv = r.b.sk = r.b.sv = 1.f;
+    // wave-uniform: does any token of pair p lie before what tile u sees
+    auto sees = [&](int u, int p) { return ri[u].ntok > 0 && 2 * p * T < tile_lim[u]; };
+    auto any_sees = [&](int p) {
+        bool a = false;
+#pragma unroll
+        for (int u = 0; u < NT; ++u) a |= sees(u, p);
+        return a && p < n_pairs;
+    };
+    auto read_k = [&](const uint8_t *buf) {
+        const uint8_t *src = buf + lane * 16;
+#pragma unroll
+        for (int j = 0; j < TL::NL; ++j) {
+            r.a.k[j] = *reinterpret_cast<const u32x4 *>(src + 0 * TL::TILE_BYTES + j * 1024);
+            r.b.k[j] = *reinterpret_cast<const u32x4 *>(src + 2 * TL::TILE_BYTES + j * 1024);
+        }
+    };
+    auto read_v = [&](const uint8_t *buf) {
+        const uint8_t *src = buf + lane * 16;
+#pragma unroll
+        for (int j = 0; j < TL::NL; ++j) {
+            r.a.v[j] = *reinterpret_cast<const u32x4 *>(src + 1 * TL::TILE_BYTES + j * 1024);
+            r.b.v[j] = *reinterpret_cast<const u32x4 *>(src + 3 * TL::TILE_BYTES + j * 1024);
+        }
+    };
+    // step p works on pair p (K already in registers, V in buf), reads the K tiles of pair p + 1
+    // from buf_next, and sends the pair NBUF - 1 ahead into the buffer that pair p - 1 occupied
+    auto step = [&](int p, const uint8_t *buf, const uint8_t *buf_next, uint8_t *refill) {
         const int pa = 2 * p;
 #if defined(PKV_TRACE)
         const uint64_t tr0 = __builtin_readcyclecounter();
 #endif
-        // wave-uniform: does any token of the pair lie before what this wave's tiles see
         bool mine[NT];
-        bool any_mine = false;
+        bool any_mine = false, all_mine = true;
 #pragma unroll
         for (int u = 0; u < NT; ++u) {
-            mine[u] = ri[u].ntok > 0 && pa * T < tile_lim[u];
+            mine[u] = sees(u, p);
             any_mine |= mine[u];
+            all_mine &= mine[u];
         }
-        PairRegs<D, DT> r;
-        if (any_mine) {
-            const uint8_t *src = buf + lane * 16;
-#pragma unroll
-            for (int j = 0; j < TL::NL; ++j) {
-                r.a.k[j] = *reinterpret_cast<const u32x4 *>(src + 0 * TL::TILE_BYTES + j * 1024);
-                r.a.v[j] = *reinterpret_cast<const u32x4 *>(src + 1 * TL::TILE_BYTES + j * 1024);
-                r.b.k[j] = *reinterpret_cast<const u32x4 *>(src + 2 * TL::TILE_BYTES + j * 1024);
-                r.b.v[j] = *reinterpret_cast<const u32x4 *>(src + 3 * TL::TILE_BYTES + j * 1024);
-            }
-            r.a.sk = r.a.sv = r.b.sk = r.b.sv = 1.f;
-            if (DT == PKV_E4M3) {
-                const int last = d.row_stride - 1;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int page = pa + h;
-                    uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[page < last ? page : last]);
-                    // past the end of the context, or an id outside the pool: no header is read
-                    const bool live = page < n_pages && id < d.max_block_id;
-                    if (!live) id = 0;
-                    const uint32_t f = fastdiv_div(id, d.slots_div);
-                    const uint32_t sl = id - f * d.slots_div.d;
-                    const float *hdr = live ? reinterpret_cast<const float *>(d.pool_base + (uint64_t)f * d.frame_bytes +
-                                                                              (uint64_t)sl * d.block_bytes)
-                                            : reinterpret_cast<const float *>(d.safe);
-                    float sk = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[kvh])));
-                    float sv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[d.Hkv + kvh])));
-                    if (!live) sk = sv = 0.f;
-                    if (h == 0) { r.a.sk = sk; r.a.sv = sv; } else { r.b.sk = sk; r.b.sv = sv; }
-                }
-            }
-        }
-        // the buffer worked on in the last step is free (barrier): the pair NBUF - 1 ahead goes there;
-        // issued after this step's LDS reads so that those are already on their way
-        if (p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
-#if defined(PKV_TRACE)
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        const uint64_t tr1 = __builtin_readcyclecounter();
-#endif
+        const bool next_mine = any_sees(p + 1);
         const int va = pa == n_pages - 1 ? last_valid : T;
         const int vb = pa + 1 < n_pages ? (pa + 1 == n_pages - 1 ? last_valid : T) : 0;
         const bool pair_tail = va < T || vb < T || (pa + 2) * T > causal_from;       // wave-uniform
-        bool all_mine = true;
+        const bool fast = all_mine && !pair_tail;
+        // Every wave has finished with pair p - 1 (barrier): its buffer takes the pair NBUF - 1 ahead.
+        // All waves of a CU reach this point together and the requests queue up behind each other;
+        // on the common path they are therefore issued further down, behind the first matrix
+        // instructions, which then run while the wave waits for its turn.
+        if (!fast && p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
+        if (DT == PKV_E4M3 && any_mine) {
+            const int last = d.row_stride - 1;
 #pragma unroll
-        for (int u = 0; u < NT; ++u) all_mine &= mine[u];
-        if (all_mine && !pair_tail) {
-            // the common case in one straight line: scores of every tile, then the accumulation of every tile
+            for (int h = 0; h < 2; ++h) {
+                const int page = pa + h;
+                uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane(PKV_CONST(int32_t, row)[page < last ? page : last]);
+                // past the end of the context, or an id outside the pool: no header is read
+                const bool live = page < n_pages && id < d.max_block_id;
+                if (!live) id = 0;
+                const uint32_t f = fastdiv_div(id, d.slots_div);
+                const uint32_t sl = id - f * d.slots_div.d;
+                const float *hdr = live ? reinterpret_cast<const float *>(d.pool_base + (uint64_t)f * d.frame_bytes +
+                                                                          (uint64_t)sl * d.block_bytes)
+                                        : reinterpret_cast<const float *>(d.safe);
+                float sk = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[kvh])));
+                float sv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(PKV_CONST(float, hdr)[d.Hkv + kvh])));
+                if (!live) sk = sv = 0.f;
+                if (h == 0) { r.a.sk = sk; r.a.sv = sv; } else { r.b.sk = sk; r.b.sv = sv; }
+            }
+        }
+#if defined(PKV_TRACE)
+        const uint64_t tr1 = __builtin_readcyclecounter();
+#endif
+        if (fast) {
+            // the common case in one straight line: the score matrices of every tile, the operand
+            // reads, the softmax of every tile, the accumulation of every tile
+            f32x4 sa[NT], sb[NT];
             bf16x8 phv[NT], plv[NT];
 #pragma unroll
-            for (int u = 0; u < NT; ++u) pair_scores<D, DT>(st[u], r, qf[u], d.scale_log2, phv[u], plv[u]);
+            for (int u = 0; u < NT; ++u) pair_qk<D, DT>(r, qf[u], sa[u], sb[u]);
+            __builtin_amdgcn_sched_barrier(0);        // the K registers are rewritten below: not before their last use is issued
+            read_v(buf);
+            if (next_mine) read_k(buf_next);
+            if (p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < NT; ++u) pair_softmax<D, DT>(st[u], r, sa[u], sb[u], d.scale_log2, phv[u], plv[u]);
 #pragma unroll
             for (int u = 0; u < NT; ++u) pair_accumulate<D, DT>(st[u], r, phv[u], plv[u]);
         } else {
+            if (any_mine) read_v(buf);
 #pragma unroll
             for (int u = 0; u < NT; ++u)
                 if (mine[u]) {
@@ -1186,13 +1220,16 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
                     else
                         process_pair<D, DT, true, 1>(st[u], r, qf[u], d.scale_log2, va, vb, G);
                 }
+            __builtin_amdgcn_sched_barrier(0);
+            if (next_mine) read_k(buf_next);
         }
 #if defined(PKV_TRACE)
         const uint64_t tr2 = __builtin_readcyclecounter();
 #endif
-        // the next pair must have landed before anybody reads it; pairs requested after it may still travel
+        // pair p + 2 must have landed before anybody reads its K tiles in the next step; the pair
+        // requested in this step may still travel
         const int newest = p + PF_BUFS - 1 < n_pairs - 1 ? p + PF_BUFS - 1 : n_pairs - 1;
-        landed(newest - (p + 1));
+        landed(newest - (p + 2));
         __builtin_amdgcn_s_barrier();      // every read of this step's buffer has been consumed by then
 #if defined(PKV_TRACE)
         const uint64_t tr3 = __builtin_readcyclecounter();
@@ -1203,17 +1240,18 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
 #endif
     };
 
-    // prologue: the first NBUF - 1 pairs
+    // prologue: the first NBUF - 1 pairs are requested, the first two must have landed
     if (n_pairs > 0) fetch(0, lds0);
     if (n_pairs > 1) fetch(1, lds1);
     if (n_pairs > 2) fetch(2, lds2);
-    landed((n_pairs < PF_BUFS - 1 ? n_pairs : PF_BUFS - 1) - 1);
+    landed((n_pairs < PF_BUFS - 1 ? n_pairs : PF_BUFS - 1) - 2);
     __builtin_amdgcn_s_barrier();
+    if (any_sees(0)) read_k(lds0);
     for (int p = 0; p < n_pairs; p += PF_BUFS) {
-        step(p, lds0, lds3);
-        if (p + 1 < n_pairs) step(p + 1, lds1, lds0);
-        if (p + 2 < n_pairs) step(p + 2, lds2, lds1);
-        if (p + 3 < n_pairs) step(p + 3, lds3, lds2);
+        step(p, lds0, lds1, lds3);
+        if (p + 1 < n_pairs) step(p + 1, lds1, lds2, lds0);
+        if (p + 2 < n_pairs) step(p + 2, lds2, lds3, lds1);
+        if (p + 3 < n_pairs) step(p + 3, lds3, lds0, lds2);
     }
 
 #pragma unroll
