@@ -322,12 +322,24 @@ __device__ __forceinline__ void pair_softmax(State<D, DT> &st, const PairRegs<D,
     const float sca = DT == PKV_E4M3 ? scale_log2 * r.a.sk : scale_log2;
     const float scb = DT == PKV_E4M3 ? scale_log2 * r.b.sk : scale_log2;
     float s[8];
+    float mx;
+    if (DT == PKV_E4M3) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        s[i] = sa[i] * sca;
-        s[4 + i] = sb[i] * scb;
+        for (int i = 0; i < 4; ++i) {
+            s[i] = sa[i] * sca;
+            s[4 + i] = sb[i] * scb;
+        }
+        mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+    } else {
+        // one positive scale for all: the maximum is taken on the raw scores and scaled once, and the
+        // scale of each score is folded into the argument of its exponential below
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            s[i] = sa[i];
+            s[4 + i] = sb[i];
+        }
+        mx = scale_log2 * fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
     }
-    float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
     mx = rows_max(mx);
     const float m_new = fmaxf(st.m, mx);
     if (__any(m_new > st.m)) {
@@ -339,7 +351,8 @@ __device__ __forceinline__ void pair_softmax(State<D, DT> &st, const PairRegs<D,
     }
     float p[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) p[i] = __builtin_amdgcn_exp2f(s[i] - st.m);
+    for (int i = 0; i < 8; ++i)
+        p[i] = __builtin_amdgcn_exp2f(DT == PKV_E4M3 ? s[i] - st.m : __builtin_fmaf(s[i], scale_log2, -st.m));
     st.l += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
     if (DT == PKV_E4M3) {
 #pragma unroll
@@ -363,6 +376,20 @@ __device__ __forceinline__ void pair_accumulate(State<D, DT> &st, const PairRegs
     for (int jt = 0; jt < TL::NV; ++jt) {
         const u32x2 va = v_half<D, DT>(r.a, jt), vb = v_half<D, DT>(r.b, jt);
         u32x4 vv = mk4(va.x, va.y, vb.x, vb.y);
+        const bf16x8 av = *reinterpret_cast<bf16x8 *>(&vv);
+        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phv, st.acc[jt], 0, 0, 0);
+        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
+    }
+}
+
+// The same with the operands of the accumulation already assembled (bf16 tiles read from LDS in
+// halves: vop[jt] = the V half of page a and the V half of page b for output tile jt).
+template <int D, int DT>
+__device__ __forceinline__ void pair_accumulate_ops(State<D, DT> &st, const u32x4 *vop, bf16x8 phv, bf16x8 plv) {
+    using TL = Tile<D, DT>;
+#pragma unroll
+    for (int jt = 0; jt < TL::NV; ++jt) {
+        u32x4 vv = vop[jt];
         const bf16x8 av = *reinterpret_cast<bf16x8 *>(&vv);
         st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phv, st.acc[jt], 0, 0, 0);
         st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
@@ -1088,7 +1115,10 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         page = page < n_pages ? page : n_pages - 1;
         page = page > 0 ? page : 0;
         const int last = d.row_stride - 1;
-        return (uint32_t)PKV_CONST(int32_t, row)[page < last ? page : last];
+        // wave-uniform, and said to be: the id then comes through the scalar cache.  As a vector load
+        // it would share the counter of the requests in flight, and waiting for it would drain them all.
+        page = __builtin_amdgcn_readfirstlane(page < last ? page : last);
+        return (uint32_t)PKV_CONST(int32_t, row)[page];
     };
     uint32_t next_id = table_id(0);
     auto fetch = [&](int pair, uint8_t *buf) {
@@ -1138,12 +1168,36 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
             r.b.k[j] = *reinterpret_cast<const u32x4 *>(src + 2 * TL::TILE_BYTES + j * 1024);
         }
     };
+    // bf16: the two pages' halves of an accumulation operand are read side by side into the four
+    // registers of that operand (8-byte reads), so that no register moves are needed to join them
+    u32x4 vop[DT == PKV_BF16 ? TL::NV : 1];
     auto read_v = [&](const uint8_t *buf) {
         const uint8_t *src = buf + lane * 16;
+        if (DT == PKV_BF16) {
 #pragma unroll
-        for (int j = 0; j < TL::NL; ++j) {
-            r.a.v[j] = *reinterpret_cast<const u32x4 *>(src + 1 * TL::TILE_BYTES + j * 1024);
-            r.b.v[j] = *reinterpret_cast<const u32x4 *>(src + 3 * TL::TILE_BYTES + j * 1024);
+            for (int jt = 0; jt < TL::NV; ++jt) {
+                const int off = (jt >> 1) * 1024 + (jt & 1) * 8;
+                const u32x2 x = *reinterpret_cast<const u32x2 *>(src + 1 * TL::TILE_BYTES + off);
+                const u32x2 y = *reinterpret_cast<const u32x2 *>(src + 3 * TL::TILE_BYTES + off);
+                vop[DT == PKV_BF16 ? jt : 0] = mk4(x.x, x.y, y.x, y.y);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TL::NL; ++j) {
+                r.a.v[j] = *reinterpret_cast<const u32x4 *>(src + 1 * TL::TILE_BYTES + j * 1024);
+                r.b.v[j] = *reinterpret_cast<const u32x4 *>(src + 3 * TL::TILE_BYTES + j * 1024);
+            }
+        }
+    };
+    // the per-page form of the V tiles that the masked path works on
+    auto v_per_page = [&]() {
+        if (DT == PKV_BF16) {
+#pragma unroll
+            for (int j = 0; j < TL::NL; ++j) {
+                const u32x4 e = vop[DT == PKV_BF16 ? 2 * j : 0], o = vop[DT == PKV_BF16 ? 2 * j + 1 : 0];
+                r.a.v[j] = mk4(e.x, e.y, o.x, o.y);
+                r.b.v[j] = mk4(e.z, e.w, o.z, o.w);
+            }
         }
     };
     // step p works on pair p (K already in registers, V in buf), reads the K tiles of pair p + 1
@@ -1209,9 +1263,15 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
 #pragma unroll
             for (int u = 0; u < NT; ++u) pair_softmax<D, DT>(st[u], r, sa[u], sb[u], d.scale_log2, phv[u], plv[u]);
 #pragma unroll
-            for (int u = 0; u < NT; ++u) pair_accumulate<D, DT>(st[u], r, phv[u], plv[u]);
+            for (int u = 0; u < NT; ++u) {
+                if (DT == PKV_BF16) pair_accumulate_ops<D, DT>(st[u], vop, phv[u], plv[u]);
+                else pair_accumulate<D, DT>(st[u], r, phv[u], plv[u]);
+            }
         } else {
-            if (any_mine) read_v(buf);
+            if (any_mine) {
+                read_v(buf);
+                v_per_page();
+            }
 #pragma unroll
             for (int u = 0; u < NT; ++u)
                 if (mine[u]) {
@@ -1246,6 +1306,13 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     if (n_pairs > 2) fetch(2, lds2);
     landed((n_pairs < PF_BUFS - 1 ? n_pairs : PF_BUFS - 1) - 2);
     __builtin_amdgcn_s_barrier();
+    // The queries were fetched with ordinary loads, which the compiler waits for where they are
+    // first used.  That must not be inside the loop: the wait it would place there (it knows of
+    // no other load) would drain the pair requests in flight in every step.  Use them here.
+#pragma unroll
+    for (int u = 0; u < NT; ++u)
+#pragma unroll
+        for (int j = 0; j < TL::NK; ++j) asm volatile("" ::"v"(qf[u][j]));
     if (any_sees(0)) read_k(lds0);
     for (int p = 0; p < n_pairs; p += PF_BUFS) {
         step(p, lds0, lds1, lds3);
