@@ -192,6 +192,18 @@ def prefill_leg(gpu, torch):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / 20
+    # the chunk's write path: the same 8 x 512 tokens appended to the cache (they overwrite themselves)
+    kn = torch.randn((B * chunk, hkv, d), generator=g).to(torch.bfloat16).view(torch.int16).cuda()
+    vn = torch.randn((B * chunk, hkv, d), generator=g).to(torch.bfloat16).view(torch.int16).cuda()
+    for _ in range(2):
+        assert gpu.kv_append_chunk_dev(m, kn, vn, ql, ctxd) == B * chunk
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(20):
+        gpu.kv_append_chunk_dev(m, kn, vn, ql, ctxd)
+    e1.record()
+    torch.cuda.synchronize()
+    append_us = e0.elapsed_time(e1) / 20 * 1e3
     assert gpu.device_errors() == 0
     pairs = B * sum(prefix + i + 1 for i in range(chunk))
     flops = 4.0 * d * hq * pairs
@@ -201,6 +213,7 @@ def prefill_leg(gpu, torch):
     tf = flops / ms / 1e9
     return {"workload": "8 sequences x (2048 cached + 512 new tokens), 32 q heads / 8 kv heads / head dim 128, bf16 cache",
             "us_per_call": round(ms * 1e3, 1), "useful_tflops": round(tf, 1), "gflop_per_call": round(flops / 1e9, 1),
+            "kv_append_chunk_us": round(append_us, 1),
             "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tf / 2500.0, 4)}}
 
 
@@ -245,11 +258,23 @@ def cpu_baseline(rep, seconds):
             t_total += time.perf_counter() - t0
             assert rc == 0
         n += 1
+    threads = orc.num_threads()
+    # the same step on one thread (one step: a few seconds)
+    orc.set_num_threads(1)
+    t1 = 0.0
+    for mi in r.active_models():
+        q = r.queries(n, mi)
+        t0 = time.perf_counter()
+        rc, _ = orc.decode_attention(r.models[mi], q, r.ctx[mi])
+        t1 += time.perf_counter() - t0
+        assert rc == 0
+    orc.set_num_threads(threads)
     r.teardown()
-    return {"value": round(step_bytes * n / t_total / 1e9, 3), "unit": "GB/s", "cores": orc.num_threads(),
+    return {"value": round(step_bytes * n / t_total / 1e9, 3), "unit": "GB/s", "cores": threads,
             "kind": "oracle", "step_us": round(t_total / n * 1e6, 1),
+            "one_thread_gbps": round(step_bytes / t1 / 1e9, 3), "one_thread_step_us": round(t1 * 1e6, 1),
             "sample": f"{n} full decode steps of replica 0 ({step_bytes / 1e6:.1f} MB of KV each, "
-                      f"{t_total:.1f} s in total, fp64, {orc.num_threads()} OpenMP threads)"}
+                      f"{t_total:.1f} s in total, fp64, {threads} OpenMP threads), then one step on one thread"}
 
 
 def bursty_run(gpu, torch, args):

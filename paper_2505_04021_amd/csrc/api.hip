@@ -918,11 +918,16 @@ int kv_append_chunk(int model, int batch, const void *k_new, const void *v_new, 
     if (batch < 0 || batch > m->dev.max_seqs) return PKV_E_RANGE;
     if (batch == 0) return 0;
     if (!k_new || !v_new || !q_lens || !ctx_lens) return PKV_E_ARG;
-    std::vector<int4> rows((size_t)batch);
+    // one entry per (sequence, j-th page its chunk may touch): a chunk of n tokens that starts
+    // anywhere in a page touches at most ceil(n / T) + 1 pages
+    Pool &p = g_pools[m->pool];
+    std::vector<int4> rows;
     int64_t first = 0;
     for (int s = 0; s < batch; ++s) {
         if (q_lens[s] < 0) return PKV_E_ARG;
-        rows[s] = make_int4((int)first, q_lens[s], 0, 0);
+        if (q_lens[s] > 0)
+            for (int j = 0; j < (q_lens[s] + p.T - 1) / p.T + 1; ++j)
+                rows.push_back(make_int4((int)first, q_lens[s], s, j));
         first += q_lens[s];
         if (first > (int64_t)1 << 24) return PKV_E_RANGE;
     }
@@ -939,7 +944,7 @@ int kv_append_chunk(int model, int batch, const void *k_new, const void *v_new, 
     HIP_TRY(hipMemcpyAsync(m->vmap, rows.data(), rows.size() * sizeof(int4), hipMemcpyHostToDevice, g_stream));
     AttnDesc d{};
     fill_addressing(d, *m);
-    d.batch = batch;
+    d.batch = (int)rows.size();
     d.ctx_lens = ctx_lens;
     d.vmap = m->vmap;
     HIP_TRY(pkv_launch_kv_append(d, k_new, v_new, g_stream));

@@ -165,13 +165,21 @@ __device__ __forceinline__ void append_row_e4m3(uint8_t *tile, float *scale_p, i
 template <int DT>
 __global__ __launch_bounds__(64) void k_kv_append(AttnDesc d, const uint16_t *k_new, const uint16_t *v_new) {
     const int lane = threadIdx.x;
-    const int seq = blockIdx.x / d.Hkv, h = blockIdx.x - seq * d.Hkv;
+    const int unit = blockIdx.x / d.Hkv, h = blockIdx.x - unit * d.Hkv;
     const int D = d.D;
-    int first_row = seq, n_new = 1;
+    // decode step: one wave per (sequence, kv head), one token.  Chunk: one wave per (sequence, kv
+    // head, j-th page the chunk touches); where the chunk starts is known only here (ctx_lens is
+    // device data), so the host lists one page more than the chunk can touch and a wave whose page
+    // holds none of the chunk leaves.  Tokens of one page go in order (the e4m3 scale of a block
+    // runs over its tokens); pages do not depend on each other (a block's scale starts afresh at
+    // its first slot).
+    int seq = unit, first_row = unit, n_new = 1, j = 0;
     if (d.vmap) {
-        const int4 e = d.vmap[seq];
+        const int4 e = d.vmap[unit];
         first_row = e.x;
         n_new = e.y;
+        seq = e.z;
+        j = e.w;
         if (n_new == 0) return;
     }
     const int ctx = d.ctx_lens[seq];
@@ -180,8 +188,11 @@ __global__ __launch_bounds__(64) void k_kv_append(AttnDesc d, const uint16_t *k_
         if (lane == 0) atomicOr(d.err, 2u);
         return;
     }
-    for (int i = 0; i < n_new; ++i) {
-        const int tok = ctx - n_new + i, page = tok / PKV_T, slot = tok % PKV_T;
+    const int tok0 = ctx - n_new, page_j = tok0 / PKV_T + j;
+    const int lo = tok0 > page_j * PKV_T ? tok0 : page_j * PKV_T;
+    const int hi = ctx < (page_j + 1) * PKV_T ? ctx : (page_j + 1) * PKV_T;
+    for (int tok = lo; tok < hi; ++tok) {
+        const int i = tok - tok0, page = page_j, slot = tok % PKV_T;
         const uint32_t id = (uint32_t)d.table[(size_t)seq * d.row_stride + page];
         if (id >= d.max_block_id) {
             if (lane == 0) atomicOr(d.err, 1u);

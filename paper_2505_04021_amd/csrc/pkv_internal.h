@@ -74,8 +74,9 @@ struct AttnDesc {
     const int32_t *table;       // [B][row_stride]
     const int32_t *ctx_lens;    // [B]
     const int32_t *row_len;     // library table: [max_seqs] blocks reserved per row; NULL for a caller's table
-    const int4 *vmap;           // prefill launches only: [groups] {sequence, first q/out row, chunk tokens after the
-                                // group, tokens in the group}
+    const int4 *vmap;           // prefill launches: [groups] {sequence, first q/out row, chunk tokens after the
+                                // group, tokens in the group}; chunk append: [units] {first new row of the
+                                // sequence, its new tokens, sequence, which of the pages the chunk touches}
     float *out;                 // [B][Hq][D]
     float *ws;                  // split-K partials: two per work item (uncached memory)
     uint32_t *cnt;              // [B][Hkv] arrival counters of the split-K merge, zero between launches
