@@ -173,3 +173,26 @@ def test_chunk_append_then_prefill(gpu, oracle, hq, hkv, d, dtype):
     assert gpu.kv_append_chunk(t.models[0], kx[:3], vx[:3], [3, 0, 0, 0], np.array([2, 9, 9, 9], dtype=np.int32)) == 3
     assert gpu.device_errors() == 2
     t.close()
+
+
+@pytest.mark.parametrize("dtype", [BF16, E4M3])
+def test_long_chunk_over_many_pages(gpu, oracle, dtype):
+    """A chunk that starts inside a block and runs over more than a dozen pages (each page of the
+    chunk is written by a wave of its own): the cache equals the oracle's token-by-token result
+    bit for bit, codes and scales included, and a second chunk continues the last block's scale."""
+    hq, hkv, d = 16, 4, 128
+    start = [13, 0, 32]
+    t = Twin(gpu, oracle, hq, hkv, d, dtype, start, [c + 400 for c in start])
+    g = gen.generator(61, dtype)
+    for ql in ([200, 129, 1], [150, 17, 250]):
+        ql = np.array(ql, dtype=np.int32)
+        n = int(ql.sum())
+        mag = torch.exp(torch.randn((n, 1, 1), generator=g))
+        kx = gen.to_bf16_bits(torch.randn((n, hkv, d), generator=g) * mag)
+        vx = gen.to_bf16_bits(torch.randn((n, hkv, d), generator=g) * mag)
+        t.ctx += ql
+        for be, m in zip(t.be, t.models):
+            assert be.kv_append_chunk(m, kx, vx, ql, t.ctx) == n
+        t.compare_cache()
+    assert gpu.device_errors() == 0
+    t.close()
