@@ -56,6 +56,8 @@ struct Model {
     size_t cnt_cap = 0;
     int4 *vmap = nullptr;                   // device: the rows (query tiles) of the last prefill launch
     size_t vmap_cap = 0;
+    float *pf_ws = nullptr;                 // device: partial results of prefill groups whose context is split
+    size_t pf_ws_floats = 0;
 };
 
 // Uncached device memory for split-K partials and arrival counters.  Blocks are
@@ -154,6 +156,9 @@ void free_model_dev(Model &m) {
     (void)hipFree(m.vmap);
     m.vmap = nullptr;
     m.vmap_cap = 0;
+    (void)hipFree(m.pf_ws);
+    m.pf_ws = nullptr;
+    m.pf_ws_floats = 0;
     m.dev = ModelDev{};
     m.ws = nullptr;
     m.cnt = nullptr;
@@ -1009,18 +1014,38 @@ int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens
     const int tile = 16 / m->g > 0 ? 16 / m->g : 1;
     const int group = PKV_PREFILL_TILES * tile;
     std::vector<int4> rows;
-    int64_t first = 0;
+    int64_t first = 0, n_groups = 0;
     for (int s = 0; s < batch; ++s) {
         if (q_lens[s] < 0) return PKV_E_ARG;
-        // longest groups of a sequence first: they take the most pages
-        for (int t0 = ((q_lens[s] - 1) / group) * group; q_lens[s] > 0 && t0 >= 0; t0 -= group) {
-            const int n = q_lens[s] - t0 < group ? q_lens[s] - t0 : group;
-            rows.push_back(make_int4(s, (int)(first + t0), q_lens[s] - (t0 + n), n));
-        }
+        n_groups += (q_lens[s] + group - 1) / group;
         first += q_lens[s];
         if (first > (int64_t)1 << 24) return PKV_E_RANGE;
     }
-    if (rows.empty()) return PKV_OK;
+    if (n_groups == 0) return PKV_OK;
+    // Few groups in front of long contexts would leave most of the chip idle: then every group comes
+    // as several work-groups, each with a part of the context of at least kMinSplitPairs page pairs
+    // (as far as the host can tell: it knows the blocks a row holds, not its context length).
+    constexpr int kFillWorkGroups = 1024, kMinSplitPairs = 8, kMaxSplit = 64;
+    const int64_t plain = n_groups * m->Hkv;
+    const int want_split = plain >= kFillWorkGroups ? 1 : (int)((kFillWorkGroups + plain - 1) / plain);
+    bool any_split = false;
+    first = 0;
+    for (int s = 0; s < batch; ++s) {
+        const int est_pairs = (m->row_len[s] + 1) / 2;
+        int n_split = want_split;
+        if (n_split > est_pairs / kMinSplitPairs) n_split = est_pairs / kMinSplitPairs;
+        if (n_split > kMaxSplit) n_split = kMaxSplit;
+        if (n_split < 2) n_split = 0;
+        // longest groups of a sequence first: they take the most pages
+        for (int t0 = ((q_lens[s] - 1) / group) * group; q_lens[s] > 0 && t0 >= 0; t0 -= group) {
+            const int n = q_lens[s] - t0 < group ? q_lens[s] - t0 : group;
+            if (n_split == 0) rows.push_back(make_int4(s, (int)(first + t0), q_lens[s] - (t0 + n), n));
+            for (int k = 0; k < n_split; ++k)
+                rows.push_back(make_int4(s, (int)(first + t0), q_lens[s] - (t0 + n), n | (k << 8) | (n_split << 20)));
+            any_split |= n_split > 0;
+        }
+        first += q_lens[s];
+    }
     if (rows.size() > m->vmap_cap) {
         HIP_TRY(hipStreamSynchronize(g_stream));
         (void)hipFree(m->vmap);
@@ -1041,7 +1066,19 @@ int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens
     d.cols = tile * m->g;
     d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m->D));
     d.trace = g_trace;
-    HIP_TRY(pkv_launch_prefill(d, (int)rows.size(), g_stream));
+    if (any_split) {
+        const size_t need = rows.size() * m->Hkv * (PKV_PREFILL_TILES * 16) * (size_t)(m->D + 4);
+        if (need > m->pf_ws_floats) {
+            HIP_TRY(hipStreamSynchronize(g_stream));
+            (void)hipFree(m->pf_ws);
+            m->pf_ws = nullptr;
+            m->pf_ws_floats = 0;
+            HIP_TRY(hipMalloc((void **)&m->pf_ws, need * sizeof(float)));
+            m->pf_ws_floats = need;
+        }
+        d.ws = m->pf_ws;
+    }
+    HIP_TRY(pkv_launch_prefill(d, (int)rows.size(), any_split, g_stream));
     return PKV_OK;
 }
 

@@ -1063,7 +1063,11 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int G = lane >> 4, n = lane & 15;
     const int group = blockIdx.x / d.Hkv, kvh = blockIdx.x - group * d.Hkv;
-    const RowInfo gi = row_info_uniform(d, group);
+    RowInfo gi = row_info_uniform(d, group);
+    // a group of few query tokens in front of a long context comes as several work-groups, each with a
+    // part of the context; they leave partial results that k_prefill_merge joins
+    const int split = (gi.ntok >> 8) & 0xfff, n_split = gi.ntok >> 20;
+    gi.ntok &= 0xff;
     const int tile_tok = d.cols / d.g;                      // query tokens per tile
     const Column col = column_of(d, n);
     // tokens the group's last query sees, never beyond what the row holds
@@ -1074,6 +1078,10 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     const int n_pages = (L + T - 1) / T, n_pairs = (n_pages + 1) >> 1;
     const int last_valid = L - (n_pages - 1) * T;
     const int causal_from = L - (gi.ntok - 1);              // first token some column of the group may not see
+    // the pairs this work-group walks
+    const int per_split = n_split > 1 ? (n_pairs + n_split - 1) / n_split : n_pairs;
+    const int p_begin = n_split > 1 ? (split * per_split < n_pairs ? split * per_split : n_pairs) : 0;
+    const int p_end = p_begin + per_split < n_pairs ? p_begin + per_split : n_pairs;
 
     // this wave's tiles of the group: tile u covers the group's tokens [(w * NT + u) * tile_tok, ...)
     RowInfo ri[NT];
@@ -1120,7 +1128,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         page = __builtin_amdgcn_readfirstlane(page < last ? page : last);
         return (uint32_t)PKV_CONST(int32_t, row)[page];
     };
-    uint32_t next_id = table_id(0);
+    uint32_t next_id = table_id(p_begin);
     auto fetch = [&](int pair, uint8_t *buf) {
         uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane((int)next_id);
         next_id = table_id(pair + 1);
@@ -1158,7 +1166,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         bool a = false;
 #pragma unroll
         for (int u = 0; u < NT; ++u) a |= sees(u, p);
-        return a && p < n_pairs;
+        return a && p < p_end;
     };
     auto read_k = [&](const uint8_t *buf) {
         const uint8_t *src = buf + lane * 16;
@@ -1224,7 +1232,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         // All waves of a CU reach this point together and the requests queue up behind each other;
         // on the common path they are therefore issued further down, behind the first matrix
         // instructions, which then run while the wave waits for its turn.
-        if (!fast && p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
+        if (!fast && p + PF_BUFS - 1 < p_end) fetch(p + PF_BUFS - 1, refill);
         if (DT == PKV_E4M3 && any_mine) {
             const int last = d.row_stride - 1;
 #pragma unroll
@@ -1258,7 +1266,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
             __builtin_amdgcn_sched_barrier(0);        // the K registers are rewritten below: not before their last use is issued
             read_v(buf);
             if (next_mine) read_k(buf_next);
-            if (p + PF_BUFS - 1 < n_pairs) fetch(p + PF_BUFS - 1, refill);
+            if (p + PF_BUFS - 1 < p_end) fetch(p + PF_BUFS - 1, refill);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < NT; ++u) pair_softmax<D, DT>(st[u], r, sa[u], sb[u], d.scale_log2, phv[u], plv[u]);
@@ -1288,7 +1296,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
 #endif
         // pair p + 2 must have landed before anybody reads its K tiles in the next step; the pair
         // requested in this step may still travel
-        const int newest = p + PF_BUFS - 1 < n_pairs - 1 ? p + PF_BUFS - 1 : n_pairs - 1;
+        const int newest = p + PF_BUFS - 1 < p_end - 1 ? p + PF_BUFS - 1 : p_end - 1;
         landed(newest - (p + 2));
         __builtin_amdgcn_s_barrier();      // every read of this step's buffer has been consumed by then
 #if defined(PKV_TRACE)
@@ -1301,10 +1309,11 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     };
 
     // prologue: the first NBUF - 1 pairs are requested, the first two must have landed
-    if (n_pairs > 0) fetch(0, lds0);
-    if (n_pairs > 1) fetch(1, lds1);
-    if (n_pairs > 2) fetch(2, lds2);
-    landed((n_pairs < PF_BUFS - 1 ? n_pairs : PF_BUFS - 1) - 2);
+    const int my_pairs = p_end - p_begin;
+    if (my_pairs > 0) fetch(p_begin, lds0);
+    if (my_pairs > 1) fetch(p_begin + 1, lds1);
+    if (my_pairs > 2) fetch(p_begin + 2, lds2);
+    landed((my_pairs < PF_BUFS - 1 ? my_pairs : PF_BUFS - 1) - 2);
     __builtin_amdgcn_s_barrier();
     // The queries were fetched with ordinary loads, which the compiler waits for where they are
     // first used.  That must not be inside the loop: the wait it would place there (it knows of
@@ -1313,21 +1322,30 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     for (int u = 0; u < NT; ++u)
 #pragma unroll
         for (int j = 0; j < TL::NK; ++j) asm volatile("" ::"v"(qf[u][j]));
-    if (any_sees(0)) read_k(lds0);
-    for (int p = 0; p < n_pairs; p += PF_BUFS) {
+    if (any_sees(p_begin)) read_k(lds0);
+    for (int p = p_begin; p < p_end; p += PF_BUFS) {
         step(p, lds0, lds1, lds3);
-        if (p + 1 < n_pairs) step(p + 1, lds1, lds2, lds0);
-        if (p + 2 < n_pairs) step(p + 2, lds2, lds3, lds1);
-        if (p + 3 < n_pairs) step(p + 3, lds3, lds0, lds2);
+        if (p + 1 < p_end) step(p + 1, lds1, lds2, lds0);
+        if (p + 2 < p_end) step(p + 2, lds2, lds3, lds1);
+        if (p + 3 < p_end) step(p + 3, lds3, lds0, lds2);
     }
 
 #pragma unroll
     for (int u = 0; u < NT; ++u) {
-        if (col_live[u]) {
+        float l = st[u].l;
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (n_split > 1) {
+            // a part of the context: the unnormalised sums, the maximum and the denominator of every column
+            float *part = d.ws + (((size_t)group * d.Hkv + kvh) * (PKV_PREFILL_TILES * 16) + (w * NT + u) * 16 + n) * (D + 4);
+#pragma unroll
+            for (int jt = 0; jt < TL::NV; ++jt) *reinterpret_cast<f32x4 *>(part + 16 * jt + 4 * G) = st[u].acc[jt];
+            if (G == 0) {
+                part[D] = st[u].m;
+                part[D + 1] = l;
+            }
+        } else if (col_live[u]) {
             float *out_row = d.out + ((size_t)(ri[u].q0 + col.tok) * d.Hq + kvh * d.g + col.head) * D;
-            float l = st[u].l;
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
             const float inv = l > 0.f ? 1.0f / l : 0.f;          // no visible token: the row is defined as zero
 #pragma unroll
             for (int jt = 0; jt < TL::NV; ++jt)
@@ -1341,6 +1359,45 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         t[0] = tr_read; t[1] = tr_math; t[2] = tr_sync; t[3] = tr_steps;
     }
 #endif
+}
+
+// Joins the parts of a group whose context was walked by several work-groups of k_prefill: one
+// work-group per (first part of such a group, kv head, tile of 16 columns); the parts are consecutive
+// rows of d.vmap.  out = sum_i 2^(m_i - M) acc_i / sum_i 2^(m_i - M) l_i with M = max_i m_i, per column.
+__global__ __launch_bounds__(256) void k_prefill_merge(const AttnDesc d) {
+    const int tile = blockIdx.x % PKV_PREFILL_TILES, rk = blockIdx.x / PKV_PREFILL_TILES;
+    const int row = rk / d.Hkv, kvh = rk - row * d.Hkv;
+    const int4 e = d.vmap[row];
+    const int split = (e.w >> 8) & 0xfff, n_split = e.w >> 20, ntok = e.w & 0xff;
+    if (n_split <= 1 || split != 0) return;
+    const int D = d.D, tile_tok = d.cols / d.g, stride = D + 4;       // D sums, the maximum, the denominator, two unused (16-byte rows)
+    constexpr int NCOL = PKV_PREFILL_TILES * 16;
+    const int quads = D / 4;
+    for (int i = threadIdx.x; i < 16 * quads; i += blockDim.x) {
+        const int n = i / quads, dq = i - n * quads;
+        const int c = tile * 16 + n;
+        const int tok = n / d.g, head = n - tok * d.g;
+        const int t0 = tile * tile_tok;
+        if (n >= d.cols || t0 + tok >= ntok) continue;            // a column without a query
+        float M = -INFINITY;
+        for (int s = 0; s < n_split; ++s) {
+            const float *part = d.ws + (((size_t)(row + s) * d.Hkv + kvh) * NCOL + c) * stride;
+            M = fmaxf(M, part[D]);
+        }
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float den = 0.f;
+        for (int s = 0; s < n_split; ++s) {
+            const float *part = d.ws + (((size_t)(row + s) * d.Hkv + kvh) * NCOL + c) * stride;
+            const float m = part[D];
+            const float f = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - M);
+            den += f * part[D + 1];
+            // a part that saw no token holds no usable sums (its factor is 0, its sums may be anything finite)
+            if (f > 0.f) acc += *reinterpret_cast<const f32x4 *>(part + 4 * dq) * f;
+        }
+        const float inv = den > 0.f ? 1.0f / den : 0.f;
+        float *out_row = d.out + ((size_t)(e.y + t0 + tok) * d.Hq + kvh * d.g + head) * D;
+        *reinterpret_cast<f32x4 *>(out_row + 4 * dq) = acc * inv;
+    }
 }
 
 __global__ __launch_bounds__(64 * PF_WAVES, 2) void k_prefill(const AttnDesc d) {
@@ -1407,9 +1464,11 @@ hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t 
     return hipSuccess;
 }
 
-hipError_t pkv_launch_prefill(const AttnDesc &d, int n_groups, hipStream_t s) {
+hipError_t pkv_launch_prefill(const AttnDesc &d, int n_groups, bool any_split, hipStream_t s) {
     if (n_groups == 0) return hipSuccess;
     hipLaunchKernelGGL(k_prefill, dim3((unsigned)(n_groups * d.Hkv)), dim3(64 * PF_WAVES), 0, s, d);
+    if (any_split)
+        hipLaunchKernelGGL(k_prefill_merge, dim3((unsigned)(n_groups * d.Hkv * PKV_PREFILL_TILES)), dim3(256), 0, s, d);
     return hipGetLastError();
 }
 

@@ -123,3 +123,26 @@ def test_prefill_arguments(gpu, oracle):
     assert gpu.prefill_attention_dev(9999, qd, np.array([4, 4], dtype=np.int32), ctx, out) < 0
     assert gpu.prefill_attention_dev(t.models[0], qd, np.array([0, 0], dtype=np.int32), ctx, out) == 0
     t.close()
+
+
+LONG = [(1500, 3), (1024, 40), (2047, 1), (777, 16), (640, 0), (999, 33)]
+
+
+@pytest.mark.parametrize("hq,hkv,d,dtype", [(32, 8, 128, BF16), (16, 2, 64, BF16), (12, 4, 64, E4M3), (32, 8, 128, E4M3)])
+def test_few_queries_in_front_of_long_contexts(gpu, oracle, hq, hkv, d, dtype):
+    """Few query groups and long contexts: every group is walked by several work-groups, each with a
+    part of the context, and their partial results are joined.  The second call asks with shorter
+    contexts than the rows hold, so that the last parts of some groups see no token at all."""
+    ctx = [c for c, _ in LONG]
+    qlen = [q for _, q in LONG]
+    t = Twin(gpu, oracle, hq, hkv, d, dtype, ctx, max_blocks=128, pool_bytes=128 << 20)
+    q = gen.queries((19, d, hq), sum(qlen), hq, d)
+    for shrink in (0, 600):
+        c2 = [max(ql, c - shrink) for c, ql in LONG]
+        rc_o, out_o = oracle.prefill_attention(t.models[1], q, qlen, c2)
+        rc_g, out_g = gpu.prefill_attention(t.models[0], q, qlen, c2)
+        assert rc_o == 0 and rc_g == 0
+        err = row_rel_err(out_g, out_o)
+        assert err <= TOL[dtype], (shrink, err)
+    assert gpu.device_errors() == 0
+    t.close()
