@@ -157,9 +157,10 @@ __device__ __forceinline__ void append_row_e4m3(uint8_t *tile, float *scale_p, i
 
 // kv_append: one wave per (sequence, kv head).  Without a chunk list it writes the token with
 // index ctx_lens[seq] - 1 from row `seq` of k_new / v_new (bf16 [batch][Hkv][D]).  With one
-// (d.vmap: per sequence {first row, tokens, -, -}) it writes the sequence's `tokens` new tokens
-// at indices ctx_lens[seq] - tokens .. ctx_lens[seq] - 1 from consecutive rows, in order, each
-// exactly as a single append would (the e4m3 scale rule is sequential by definition).
+// (d.vmap: per unit {first row of the sequence's new tokens, their number, sequence, which of the
+// pages they touch}) it writes the sequence's new tokens at indices ctx_lens[seq] - tokens ..
+// ctx_lens[seq] - 1 from consecutive rows, each exactly as a single append would (the e4m3 scale
+// rule is sequential within a block by definition).
 // A context length outside what the row holds is skipped and reported through the device
 // error flags (bit 1).
 template <int DT>
@@ -191,25 +192,33 @@ __global__ __launch_bounds__(64) void k_kv_append(AttnDesc d, const uint16_t *k_
     const int tok0 = ctx - n_new, page_j = tok0 / PKV_T + j;
     const int lo = tok0 > page_j * PKV_T ? tok0 : page_j * PKV_T;
     const int hi = ctx < (page_j + 1) * PKV_T ? ctx : (page_j + 1) * PKV_T;
-    for (int tok = lo; tok < hi; ++tok) {
-        const int i = tok - tok0, page = page_j, slot = tok % PKV_T;
-        const uint32_t id = (uint32_t)d.table[(size_t)seq * d.row_stride + page];
-        if (id >= d.max_block_id) {
-            if (lane == 0) atomicOr(d.err, 1u);
-            return;
+    if (lo >= hi) return;
+    const uint32_t id = (uint32_t)d.table[(size_t)seq * d.row_stride + page_j];
+    if (id >= d.max_block_id) {
+        if (lane == 0) atomicOr(d.err, 1u);
+        return;
+    }
+    uint8_t *blk = block_ptr(d, id);
+    if (DT == PKV_BF16) {
+        // the elements of the page's new tokens do not depend on each other: all lanes, all tokens at once
+        const size_t tile = (size_t)PKV_T * D * 2;
+        uint16_t *kt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile);
+        uint16_t *vt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile + tile);
+        const int n_el = (hi - lo) * D;
+#pragma unroll 4
+        for (int e = lane; e < n_el; e += 64) {
+            const int t = e / D, dd = e - t * D, tok = lo + t;
+            const size_t src = ((size_t)(first_row + (tok - tok0)) * d.Hkv + h) * D + dd;
+            kt[k_elem_off<PKV_BF16>(tok % PKV_T, dd)] = k_new[src];
+            vt[v_elem_off<PKV_BF16>(tok % PKV_T, dd)] = v_new[src];
         }
-        uint8_t *blk = block_ptr(d, id);
+        return;
+    }
+    for (int tok = lo; tok < hi; ++tok) {
+        const int i = tok - tok0, slot = tok % PKV_T;
         const uint16_t *kx = k_new + ((size_t)(first_row + i) * d.Hkv + h) * D;
         const uint16_t *vx = v_new + ((size_t)(first_row + i) * d.Hkv + h) * D;
-        if (DT == PKV_BF16) {
-            const size_t tile = (size_t)PKV_T * D * 2;
-            uint16_t *kt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile);
-            uint16_t *vt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile + tile);
-            for (int dd = lane; dd < D; dd += 64) {
-                kt[k_elem_off<PKV_BF16>(slot, dd)] = kx[dd];
-                vt[v_elem_off<PKV_BF16>(slot, dd)] = vx[dd];
-            }
-        } else {
+        {
             float *hdr = reinterpret_cast<float *>(blk);
             const size_t tile = (size_t)PKV_T * D;
             uint8_t *kt = blk + PKV_FP8_HEADER + (size_t)h * 2 * tile, *vt = kt + tile;
