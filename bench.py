@@ -47,10 +47,25 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample (0 = skip)")
     ap.add_argument("--no-balloon", action="store_true")
     ap.add_argument("--seg-cost", type=int, default=-1, help="allowance per segment in the work split, pages (-1 = default)")
+    ap.add_argument("--condition-ms", type=int, default=1000,
+                    help="untimed launches for this long before the warm-up, so that the clocks have settled (0 = none)")
     ap.add_argument("--tune", type=int, default=48, help="untimed launches that tune the per-XCD share weights before the warm-up (0 = equal weights)")
     ap.add_argument("--page-cost", type=int, default=-1, help="fixed cost of a page in the wave-sharing model, per mille (-1 = default)")
     ap.add_argument("--sweep-items", default="", help="comma list of work-item counts to time before the main run (stderr)")
     return ap.parse_args()
+
+
+def condition(torch, fn, ms):
+    """Keeps the GPU busy with fn(i) for about ms milliseconds: a GPU that has idled (set-up on the host,
+    a previous leg's teardown) needs some hundred milliseconds of work before its clocks settle, and the
+    first launches after an idle phase run 2-20 % slower than the steady state a serving loop is in."""
+    t0, i = time.perf_counter(), 0
+    while (time.perf_counter() - t0) * 1e3 < ms:
+        for _ in range(64):
+            fn(i)
+            i += 1
+        torch.cuda.synchronize()
+    return i
 
 
 def profiled_traffic(workload, size):
@@ -161,7 +176,7 @@ def append_latency(gpu, torch, rep, inputs):
     return res
 
 
-def prefill_leg(gpu, torch):
+def prefill_leg(gpu, torch, condition_ms=1000):
     """Chunked prefill on one model of the headline workload's shape (32 q heads, 8 kv heads, head dim
     128, bf16 cache): 8 sequences with 2048 cached tokens each take a chunk of 512.  Reports device time
     per call and the rate of useful attention flops (4 * D * heads * visible (query, key) pairs)."""
@@ -185,6 +200,7 @@ def prefill_leg(gpu, torch):
     for _ in range(3):
         assert gpu.prefill_attention_dev(m, q, ql, ctxd, out) == 0
     torch.cuda.synchronize()
+    condition(torch, lambda i: gpu.prefill_attention_dev(m, q, ql, ctxd, out), condition_ms)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(20):
@@ -398,6 +414,7 @@ def main():
         for i in range(args.tune):
             step(i)
         torch.cuda.synchronize()
+    n_cond = condition(torch, step, args.condition_ms)
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -448,6 +465,7 @@ def main():
                    "frame_bytes": reps[0].cfg.frame_bytes, "layers": args.layers,
                    "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
                    "work_items": args.items or "auto", "xcd_tune_launches": args.tune,
+                   "conditioning_launches": n_cond,
                    "xcd_weights": [round(x, 3) for x in gpu.get_xcd_weights()]},
         "step_us": round(ms_per_step * 1e3, 2),
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
@@ -464,7 +482,7 @@ def main():
     if not args.no_balloon:
         result["balloon_resize"] = balloon_latency(gpu, torch)
         result["kv_append"] = append_latency(gpu, torch, reps[0], inputs[0])
-        result["prefill_attention"] = prefill_leg(gpu, torch)
+        result["prefill_attention"] = prefill_leg(gpu, torch, min(args.condition_ms, 1000))
         result["policies"] = policy_leg()
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(reps[0], args.cpu_seconds)
