@@ -239,7 +239,10 @@ int decode_attention_multi(int n_models, const int *models, const int *batches,
  * scheduler chose the chunk sizes); ctx_lens: dev int32 [batch].  The library's table is
  * used.  A sequence whose ctx_lens is below its q_lens gets zero rows for the queries
  * that would stand before position 0.  Enqueues only (a small host-to-device copy of the
- * row plan included). */
+ * row plan included); a call with few query tokens in front of long contexts splits the
+ * contexts over several work-groups and then keeps partial results in a per-model buffer
+ * that the library allocates, or enlarges after waiting for the stream, when it is first
+ * needed. */
 int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens,
                       const int32_t *ctx_lens, float *out);
 
