@@ -49,6 +49,8 @@ def parse_args():
     ap.add_argument("--seg-cost", type=int, default=-1, help="allowance per segment in the work split, pages (-1 = default)")
     ap.add_argument("--condition-ms", type=int, default=1000,
                     help="untimed launches for this long before the warm-up, so that the clocks have settled (0 = none)")
+    ap.add_argument("--kernel-form", type=int, default=-1, choices=[-1, 0, 1],
+                    help="decode kernel: 0 = two waves per SIMD, 1 = one wave with a deeper ring, -1 = chosen by the launch")
     ap.add_argument("--tune", type=int, default=48, help="untimed launches that tune the per-XCD share weights before the warm-up (0 = equal weights)")
     ap.add_argument("--page-cost", type=int, default=-1, help="fixed cost of a page in the wave-sharing model, per mille (-1 = default)")
     ap.add_argument("--sweep-items", default="", help="comma list of work-item counts to time before the main run (stderr)")
@@ -378,6 +380,7 @@ def main():
     if args.page_cost >= 0:
         gpu.set_page_cost(args.page_cost)
     gpu.set_segment_cost(args.seg_cost)
+    assert gpu.set_kernel_form(args.kernel_form) == 0
     if args.config == 3:
         return bursty_run(gpu, torch, args)
     reps = build_replicas(gpu, args.config, args.size, args.replicas, args.frame_bytes, args.layers)

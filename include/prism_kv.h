@@ -307,6 +307,11 @@ int pkv_set_split(int items, int min_share);
  * are cut into shares, in pages (0..256; -1 = the default).  A wave whose share holds
  * many short sequences then gets fewer pages than one inside a long sequence. */
 int pkv_set_segment_cost(int pages);
+/* Which form of the decode kernel a launch uses: 0 = two waves per SIMD (2048 work items),
+ * 1 = one wave per SIMD with twice the bytes in flight (1024 work items; bf16 caches only,
+ * other launches keep form 0), -1 = the library decides by the launch (form 1 where the waves
+ * would stream for long: many pages per work item). */
+int pkv_set_kernel_form(int form);
 /* Cost model that shares the waves out among the models of a grouped launch: a page
  * costs per_mille/1000 + 0.1 per KiB of its K and V tile (default 800). */
 int pkv_set_page_cost(int per_mille);

@@ -98,6 +98,8 @@ uint32_t *g_err = nullptr;         // device error flags
 void *g_safe = nullptr;            // 16 KiB of zeros: what kernels read instead of a block they must not touch
 uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
 int g_items = 0, g_min_share = 0, g_seg_cost = -1;
+int g_deep_mode = -1;                // which form of the attention kernel: -1 = by the launch, 0 = two waves per SIMD, 1 = one
+bool g_deep_now = false;             // the form chosen for the launch being prepared
 // How a block of eight shares is cut among the XCDs: weights (mean 1), and the state of a
 // tuning run that derives them from when each XCD's waves finish.
 float g_xcd_w[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
@@ -173,6 +175,11 @@ void free_model_dev(Model &m) {
 constexpr int kDefaultItems = 2048;
 constexpr int kDefaultMinShare = 4;
 constexpr int kDefaultSegCost = 6;
+// The kernel's second form (one wave per SIMD, twice the bytes in flight, half the work items) pays
+// where waves stream for long: measured 324 against 343 us on 16 sequences of 32768 tokens (128 page
+// units per work item of the ordinary form), 103 against 99 us on the two-model workload (47 units).
+constexpr int kDeepItems = 1024;
+constexpr double kDeepUnitsPerItem = 110.0;
 
 // Expected cost of a model's pages, used to share the waves out among the models of a
 // grouped launch.  A wave spends a fixed time per page (the load - MFMA - softmax - MFMA
@@ -182,6 +189,16 @@ double est_bytes(const Model &m, bool own, int batch, int row_stride) {
     const double blocks = own ? (double)m.used_blocks : (double)batch * row_stride;
     const double page_kib = (double)m.layer_bytes / m.Hkv / 1024.0;
     return blocks * m.Hkv * (g_page_cost + 0.1 * page_kib);
+}
+
+// page units (pages plus the allowance per segment) of a model's part of a launch, as far as the host knows
+double launch_units(const Model &m, bool own, int batch, int row_stride) {
+    const int seg = g_seg_cost >= 0 ? g_seg_cost : kDefaultSegCost;
+    return ((own ? (double)m.used_blocks : (double)batch * row_stride) + (double)batch * (seg + 1)) * m.Hkv;
+}
+
+void choose_form(bool all_bf16, double units) {
+    g_deep_now = all_bf16 && (g_deep_mode == 1 || (g_deep_mode < 0 && g_items == 0 && units / kDefaultItems >= kDeepUnitsPerItem));
 }
 
 // cols: MFMA columns per kv head (0 = g: one query token per row); units_hint: upper bound of the
@@ -216,7 +233,7 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     const double units = units_hint > 0.0 ? units_hint
                                           : ((own ? (double)m.used_blocks : (double)batch * d.row_stride) +
                                              (double)batch * (d.seg_cost + 1)) * m.Hkv;
-    double items = (g_items > 0 ? g_items : kDefaultItems) * share_of_launch;
+    double items = (g_items > 0 ? g_items : (g_deep_now ? kDeepItems : kDefaultItems)) * share_of_launch;
     if (items > units / d.min_share) items = units / d.min_share;
     d.n_items = items < 1.0 ? 1 : (int)items;                // never more than the slots in total
     if (d.n_items >= 8) d.n_items &= ~7;                     // whole blocks of eight: one item per XCD
@@ -334,7 +351,7 @@ int launch_attention(AttnGroup &grp) {
         HIP_TRY(hipMemsetAsync(g_xcd_stat, 0, 16 * sizeof(uint64_t), g_stream));
     }
     fill_tune(grp.tune, tune);
-    HIP_TRY(pkv_launch_attention(grp, g_stream, next_events()));
+    HIP_TRY(pkv_launch_attention(grp, g_deep_now, g_stream, next_events()));
     if (tune) {
         uint64_t st[16];
         HIP_TRY(hipStreamSynchronize(g_stream));
@@ -395,6 +412,12 @@ int pkv_set_split(int items, int min_share) {
     if (items < 0 || items > (1 << 20) || min_share < 0 || min_share > 4096) return PKV_E_ARG;
     g_items = items;
     g_min_share = min_share;
+    return PKV_OK;
+}
+
+int pkv_set_kernel_form(int form) {
+    if (form < -1 || form > 1) return PKV_E_ARG;
+    g_deep_mode = form;
     return PKV_OK;
 }
 
@@ -996,6 +1019,7 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     }
     AttnGroup grp;
     grp.n = 1;
+    choose_form(m->dtype == PKV_BF16, launch_units(*m, block_table == nullptr, batch, row_stride));
     int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
     if (rc) return rc;
 
@@ -1097,7 +1121,8 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
     AttnGroup grp;
     grp.n = 0;
     int items = 0, pool = -1;
-    double total_bytes = 0.0;
+    double total_bytes = 0.0, units = 0.0;
+    bool all_bf16 = true;
     for (int i = 0; i < n_models; ++i) {
         Model *m = get_model(models[i]);
         if (!m) return PKV_E_HANDLE;
@@ -1110,7 +1135,10 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
         if (!q[i] || !ctx_lens[i] || !out[i]) return PKV_E_ARG;
         if (((uintptr_t)q[i] & 15) || ((uintptr_t)out[i] & 15)) return PKV_E_ARG;
         total_bytes += est_bytes(*m, true, batches[i], 0) + 1.0;
+        all_bf16 &= m->dtype == PKV_BF16;
+        units += launch_units(*m, true, batches[i], 0);
     }
+    choose_form(all_bf16, units);
     for (int i = 0; i < n_models; ++i) {
         if (batches[i] == 0) continue;
         Model *m = get_model(models[i]);

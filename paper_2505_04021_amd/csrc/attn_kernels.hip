@@ -413,11 +413,18 @@ __host__ __device__ inline int partial_floats(int g, int D) { return g * (D + 2)
 // shape keeps the same number of bytes in flight (PKV_FLIGHT_KIB), small pages through
 // a deeper ring; otherwise waves of a small-page model would fall behind the others in
 // a grouped launch.
-template <int D, int DT>
+template <int D, int DT, int FLIGHT_KIB = PKV_FLIGHT_KIB>
 struct Ring {
     static constexpr int PAIR_BYTES = 4 * Tile<D, DT>::TILE_BYTES;        // K and V tiles of two pages
-    static constexpr int N = 1 + (PKV_FLIGHT_KIB * 1024 + PAIR_BYTES - 1) / PAIR_BYTES;
+    static constexpr int N = 1 + (FLIGHT_KIB * 1024 + PAIR_BYTES - 1) / PAIR_BYTES;
 };
+// The second form of the kernel: one wave per SIMD with twice the bytes in flight (its ring lives in
+// the registers the second wave would have had).  Fewer, longer shares: better where every wave
+// streams for long (long contexts), worse where set-up and piece ends weigh more, and no good for
+// e4m3 caches, whose conversion arithmetic wants a second wave to hide behind.
+#ifndef PKV_DEEP_FLIGHT_KIB
+#define PKV_DEEP_FLIGHT_KIB 32
+#endif
 constexpr int MAX_PIECES = 64;   // pieces of one (sequence, kv head) the merge stages in LDS
 
 // A row of a launch.  In a decode step it is a sequence with its one new query token.  In a
@@ -663,7 +670,7 @@ struct Cut {
 #define PKV_STAMP(slot) do { } while (0)
 #endif
 
-template <int D, int DT>
+template <int D, int DT, int FLIGHT_KIB = PKV_FLIGHT_KIB>
 __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, int item, float *s_m, float *s_l) {
     using TL = Tile<D, DT>;
     const int lane = threadIdx.x;
@@ -793,7 +800,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     pend_a.arrived = pend_b.arrived = 0;
 
     // prologue of the stream: the first page pairs of the first piece, and its q
-    constexpr int RING = Ring<D, DT>::N;
+    constexpr int RING = Ring<D, DT, FLIGHT_KIB>::N;
     PairRegs<D, DT> ring[RING];
     PairIds pre;                            // block ids of the next pair to be requested
     RowInfo ri_c = row_info_uniform(d, cur.seq);       // the row of the piece being worked on
@@ -1015,6 +1022,19 @@ __global__ __launch_bounds__(64, PKV_WAVES) void k_attention(const AttnGroup grp
         if (d.D == 128) attn_wave<128, PKV_E4M3>(d, grp.tune, item, s_m, s_l);
         else attn_wave<64, PKV_E4M3>(d, grp.tune, item, s_m, s_l);
     }
+}
+
+__global__ __launch_bounds__(64, 1) void k_attention_deep(const AttnGroup grp) {
+    __shared__ float s_m[MAX_PIECES * 16], s_l[MAX_PIECES * 16];
+    const int gi = blockIdx.x;
+    int mi = 0;
+    for (int i = 1; i < grp.n; ++i)
+        if (gi >= grp.m[i].item_begin) mi = i;
+    const AttnDesc &d = grp.m[mi];
+    const int item = gi - d.item_begin;
+    // bf16 caches only (the host never sends another kind here)
+    if (d.D == 128) attn_wave<128, PKV_BF16, PKV_DEEP_FLIGHT_KIB>(d, grp.tune, item, s_m, s_l);
+    else attn_wave<64, PKV_BF16, PKV_DEEP_FLIGHT_KIB>(d, grp.tune, item, s_m, s_l);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1451,13 +1471,14 @@ __global__ __launch_bounds__(256) void k_stream_read(const u32x4 *src, size_t n1
 
 }  // namespace
 
-hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t *ev) {
+hipError_t pkv_launch_attention(const AttnGroup &grp, bool deep, hipStream_t s, hipEvent_t *ev) {
     int items = 0;
     for (int i = 0; i < grp.n; ++i) items += grp.m[i].n_items;
     if (items == 0) return hipSuccess;
     hipError_t e;
     if (ev && (e = hipEventRecord(ev[0], s)) != hipSuccess) return e;
-    hipLaunchKernelGGL(k_attention, dim3(items), dim3(64), 0, s, grp);
+    if (deep) hipLaunchKernelGGL(k_attention_deep, dim3(items), dim3(64), 0, s, grp);
+    else hipLaunchKernelGGL(k_attention, dim3(items), dim3(64), 0, s, grp);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;

@@ -128,7 +128,7 @@ hipError_t pkv_launch_kv_read(const AttnDesc &d, int seq, int tok_begin, int n_t
 // d.batch sequences, d.ctx_lens / d.row_len / d.table as for attention
 hipError_t pkv_launch_kv_append(const AttnDesc &d, const void *k_new, const void *v_new, hipStream_t s);
 // ev: NULL or two events recorded before and after the attention kernel
-hipError_t pkv_launch_attention(const AttnGroup &grp, hipStream_t s, hipEvent_t *ev);
+hipError_t pkv_launch_attention(const AttnGroup &grp, bool deep, hipStream_t s, hipEvent_t *ev);
 // chunked prefill: d.vmap lists n_groups groups of up to PKV_PREFILL_TILES * (d.cols / d.g) query tokens
 hipError_t pkv_launch_prefill(const AttnDesc &d, int n_groups, bool any_split, hipStream_t s);
 hipError_t pkv_launch_stream_read(const void *src, size_t bytes, size_t granule_bytes, uint32_t *sink, hipStream_t s);

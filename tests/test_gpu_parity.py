@@ -121,6 +121,15 @@ def test_edge_lengths_and_shapes(gpu, oracle, hq, hkv, d, dtype):
         assert gpu.set_segment_cost(seg) == 0
         assert gpu.set_xcd_weights(w) == 0
         err = p.check()
+    # the kernel's other form (one wave per SIMD, deeper ring; e4m3 models keep the ordinary form)
+    assert gpu.set_kernel_form(1) == 0
+    for items, share, seg, w in ((0, 0, -1, None), (100000, 1, 2, None), (37, 3, 7, UNEVEN), (8, 5, 0, None), (1, 1, -1, None)):
+        assert gpu.set_split(items, share) == 0
+        assert gpu.set_segment_cost(seg) == 0
+        assert gpu.set_xcd_weights(w) == 0
+        err = p.check()
+    assert gpu.set_kernel_form(2) != 0
+    gpu.set_kernel_form(-1)
     gpu.set_split(0, 0)
     gpu.set_segment_cost(-1)
     gpu.set_xcd_weights(None)
@@ -169,6 +178,18 @@ def test_peaky_softmax(gpu, oracle):
         err = p.check()
     gpu.set_split(0, 0)
     p.close()
+
+
+@pytest.mark.parametrize("cfg_id", [2, 3])
+def test_config_small_other_kernel_form(gpu, oracle, cfg_id):
+    """The two-model and the bursty workload through the kernel's form with one wave per SIMD."""
+    assert gpu.set_kernel_form(1) == 0
+    try:
+        cfg = make_config(cfg_id, "small")
+        worst = run_pair(gpu, oracle, cfg, attn_steps=None if cfg_id == 2 else set(range(10)) | {20, 39})
+        print(f"cfg {cfg_id}, form 1: worst rel err {worst:.3e}")
+    finally:
+        gpu.set_kernel_form(-1)
 
 
 def test_grouped_launch_matches_single_launches(gpu, oracle):
