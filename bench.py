@@ -27,6 +27,7 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
+KERNEL_FORM_NAME = ("k_attention", "k_attention_deep")
 HBM_PEAK_GBPS = 8000.0      # MI355X datasheet HBM3E bandwidth
 
 
@@ -358,7 +359,7 @@ def bursty_run(gpu, torch, args):
                    "mean_active_models": round(active / args.steps, 2), "decode_launches": launches,
                    "bookkeeping_calls": len(r.log) - n_events0,
                    "kv_bytes_per_launch": int(kv / max(launches, 1))},
-        "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": KERNEL_FORM_NAME[gpu.last_kernel_form()], "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                      "avg_launch_us": round(attn_ms / max(n_rec, 1) * 1e3, 2), "launches": n_rec},
     }
@@ -473,7 +474,7 @@ def main():
         "step_us": round(ms_per_step * 1e3, 2),
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "device_ms_per_step": round(dev_ms / args.steps, 5),
-        "roofline": {"bound": "hbm", "kernel": "k_attention", "achieved": round(attn_gbps, 1),
+        "roofline": {"bound": "hbm", "kernel": KERNEL_FORM_NAME[gpu.last_kernel_form()], "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
                      "traffic": None if args.frame_bytes or args.layers > 1 else profiled_traffic(reps[0].cfg.name, args.size),
                      "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": args.steps,

@@ -312,6 +312,8 @@ int pkv_set_segment_cost(int pages);
  * other launches keep form 0), -1 = the library decides by the launch (form 1 where the waves
  * would stream for long: many pages per work item). */
 int pkv_set_kernel_form(int form);
+/* The form (0 or 1) of the most recent decode attention launch of this process. */
+int pkv_last_kernel_form(void);
 /* Cost model that shares the waves out among the models of a grouped launch: a page
  * costs per_mille/1000 + 0.1 per KiB of its K and V tile (default 800). */
 int pkv_set_page_cost(int per_mille);

@@ -421,6 +421,8 @@ int pkv_set_kernel_form(int form) {
     return PKV_OK;
 }
 
+int pkv_last_kernel_form(void) { return g_deep_now ? 1 : 0; }
+
 int pkv_set_segment_cost(int pages) {
     if (pages < -1 || pages > 256) return PKV_E_ARG;
     g_seg_cost = pages;
