@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprismkv.so")
 SOURCES = ["api.hip", "pool_kernels.hip", "attn_kernels.hip", "kv_kernels.hip", "policy.cpp"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", 
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          # keep single-lane atomics as written: the optimiser would broadcast their result at once,
          # which forces a full wait on all outstanding KV loads at every queue / arrival atomic

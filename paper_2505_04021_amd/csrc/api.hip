@@ -106,7 +106,7 @@ float g_xcd_w[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
 uint64_t *g_xcd_stat = nullptr;       // device: [8][2]
 int g_tune_left = 0, g_tune_done = 0;
 constexpr float kXcdWeightMin = 0.75f, kXcdWeightMax = 1.25f;
-double g_page_cost = 0.8;            // fixed cost of a page relative to 0.1 per KiB   // measurement knobs (0 = automatic)
+double g_page_cost = 0.8;            // fixed cost of a page relative to 0.1 per KiB
 int g_timing = 0;                 // 0 = off, n = bracket every n-th attention launch with events
 long g_launches = 0;
 std::vector<hipEvent_t> g_events;   // pairs: before and after the attention kernel
@@ -319,7 +319,7 @@ int pkv_device_errors(void) {
 
 /* ------------------------------------------------------------ XCD weights */
 
-void normalise_xcd_weights(float *w) {
+static void normalise_xcd_weights(float *w) {
     for (int pass = 0; pass < 4; ++pass) {          // mean 1 inside the clamp
         double sum = 0.0;
         for (int i = 0; i < 8; ++i) sum += w[i];
@@ -330,7 +330,7 @@ void normalise_xcd_weights(float *w) {
     }
 }
 
-void fill_tune(AttnTune &t, bool record) {
+static void fill_tune(AttnTune &t, bool record) {
     double sum = 0.0, acc = 0.0;
     for (int i = 0; i < 8; ++i) sum += g_xcd_w[i];
     t.cum[0] = 0;
@@ -344,7 +344,7 @@ void fill_tune(AttnTune &t, bool record) {
 
 // One attention launch; during a tuning run it also records when each XCD's waves finish
 // and moves the weights toward equal finishing times (synchronises in that case).
-int launch_attention(AttnGroup &grp) {
+static int launch_attention(AttnGroup &grp) {
     const bool tune = g_tune_left > 0;
     if (tune) {
         if (!g_xcd_stat) HIP_TRY(hipMalloc((void **)&g_xcd_stat, 16 * sizeof(uint64_t)));
@@ -512,7 +512,7 @@ int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *devi
 
 /* ------------------------------------------------------------ elastic pools */
 
-hipMemAllocationProp device_memory_prop() {
+static hipMemAllocationProp device_memory_prop() {
     hipMemAllocationProp prop = {};
     prop.type = hipMemAllocationTypePinned;
     prop.location.type = hipMemLocationTypeDevice;
@@ -524,7 +524,7 @@ hipMemAllocationProp device_memory_prop() {
 
 // back frame f of an elastic pool with memory: as it is if a deflate left it mapped, else with a
 // spare handle if there is one, else with newly created memory
-int elastic_map(Pool &p, uint32_t f) {
+static int elastic_map(Pool &p, uint32_t f) {
     if (f >= (uint64_t)p.n_frames) return PKV_E_INTERNAL;
     if (p.idle[f]) {                       // re-acquired before it was trimmed: nothing to do
         p.idle[f] = 0;
@@ -561,7 +561,7 @@ int elastic_map(Pool &p, uint32_t f) {
     return PKV_OK;
 }
 
-int elastic_unmap(Pool &p, uint32_t f) {
+static int elastic_unmap(Pool &p, uint32_t f) {
     if (f >= (uint64_t)p.n_frames || !p.mapped[f]) return PKV_E_INTERNAL;
     if (p.idle[f]) {
         p.idle[f] = 0;
@@ -579,7 +579,7 @@ int elastic_unmap(Pool &p, uint32_t f) {
 // a deflate gave frame f back: leave it mapped where it is while the buffer has room (an inflate
 // that takes it again — the free stack hands the latest frames out first — then costs nothing),
 // else unmap it
-int elastic_give_back(Pool &p, uint32_t f) {
+static int elastic_give_back(Pool &p, uint32_t f) {
     if (f >= (uint64_t)p.n_frames || !p.mapped[f] || p.idle[f]) return PKV_E_INTERNAL;
     if (p.spare.size() + (size_t)p.n_idle < p.spare_cap) {
         p.idle[f] = 1;
@@ -591,7 +591,7 @@ int elastic_give_back(Pool &p, uint32_t f) {
 }
 
 // shrink the buffer to its cap: spare handles first, then the idle frames that have waited longest
-int elastic_trim(Pool &p) {
+static int elastic_trim(Pool &p) {
     while (p.spare.size() + (size_t)p.n_idle > p.spare_cap && !p.spare.empty()) {
         (void)hipMemRelease(p.spare.back());
         p.spare.pop_back();

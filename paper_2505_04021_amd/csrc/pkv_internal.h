@@ -3,7 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// built with hidden visibility: only what the public header declares is exported
+#pragma GCC visibility push(default)
 #include "../../include/prism_kv.h"
+#pragma GCC visibility pop
 
 #define PKV_MAX_POOLS 8
 #define PKV_MAX_MODELS 64

@@ -10,7 +10,9 @@
 #include <queue>
 #include <vector>
 
+#pragma GCC visibility push(default)      // the library is built with hidden visibility
 #include "../../include/prism_kv.h"
+#pragma GCC visibility pop
 
 extern "C" {
 

@@ -29,6 +29,16 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(lib, n), f"{n} declared in prism_kv.h but not exported"
 
 
+def test_nothing_else_is_exported():
+    """The dynamic symbol table holds the declared entry points and no helper of the library's own."""
+    import subprocess
+    _lib()
+    from paper_2505_04021_amd import build
+    out = subprocess.run(["nm", "-D", "--defined-only", build.LIB], capture_output=True, text=True, check=True).stdout
+    exported = sorted(line.split()[2] for line in out.splitlines() if len(line.split()) == 3 and line.split()[1] == "T")
+    assert exported == declared_symbols()
+
+
 def test_binding_covers_the_header():
     from paper_2505_04021_amd import binding
     assert sorted(binding.EXPORTS) == declared_symbols()
