@@ -137,7 +137,9 @@ int model_unregister(int model);
 
 /* Make the model own `pages` frames.
  *   inflate: frames are popped from the pool's free stack and appended to the
- *            model's frame list; PKV_E_NOMEM if the pool has too few (no change).
+ *            model's frame list; PKV_E_NOMEM if the pool has too few (no change), or
+ *            if an elastic pool gets no memory for one of them (the inflate is undone:
+ *            no change either).
  *   deflate: empty frames are returned to the free stack, newest first, until
  *            the target is met; frames that still hold blocks stay.
  * Returns the number of frames owned afterwards (>= pages on a clamped deflate). */
@@ -333,6 +335,9 @@ int pkv_tune_xcd(int launches);
 /* Host-side check of the multiply-shift division the kernels use to split a block
  * id into (frame, slot): returns n / d computed that way. */
 uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d);
+/* Test hook for the out-of-memory path of elastic pools: after `after` more successful frame
+ * mappings the next one is refused as if the driver had no memory left, once (-1 = never). */
+int pkv_debug_fail_frame_map(int after);
 
 #ifdef __cplusplus
 }

@@ -35,6 +35,7 @@ def _load():
         "pkv_set_split": (i, [i, i]),
         "pkv_set_page_cost": (i, [i]),
         "pkv_debug_fastdiv": (u32, [u32, u32]),
+        "pkv_debug_fail_frame_map": (i, [i]),
         "pkv_set_xcd_weights": (i, [C.POINTER(C.c_float)]),
         "pkv_get_xcd_weights": (i, [C.POINTER(C.c_float)]),
         "pkv_tune_xcd": (i, [i]),
@@ -81,7 +82,7 @@ def _load():
     return lib
 
 
-EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_set_page_cost", "pkv_debug_fastdiv",
+EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_set_page_cost", "pkv_debug_fastdiv", "pkv_debug_fail_frame_map",
            "pkv_set_xcd_weights", "pkv_get_xcd_weights", "pkv_tune_xcd", "pkv_set_segment_cost", "pkv_set_kernel_form", "pkv_last_kernel_form",
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_destroy", "pool_seed_free_order", "model_register",
@@ -169,6 +170,9 @@ class PrismKV:
 
     def set_kernel_form(self, form=-1):
         return self.lib.pkv_set_kernel_form(form)
+
+    def debug_fail_frame_map(self, after=-1):
+        return self.lib.pkv_debug_fail_frame_map(int(after))
 
     def last_kernel_form(self):
         return self.lib.pkv_last_kernel_form()

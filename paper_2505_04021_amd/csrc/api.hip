@@ -107,6 +107,7 @@ uint64_t *g_xcd_stat = nullptr;       // device: [8][2]
 int g_tune_left = 0, g_tune_done = 0;
 constexpr float kXcdWeightMin = 0.75f, kXcdWeightMax = 1.25f;
 double g_page_cost = 0.8;            // fixed cost of a page relative to 0.1 per KiB
+int g_fail_map_after = -1;        // test hook: the (n+1)-th frame mapping from now fails as if memory had run out
 int g_timing = 0;                 // 0 = off, n = bracket every n-th attention launch with events
 long g_launches = 0;
 std::vector<hipEvent_t> g_events;   // pairs: before and after the attention kernel
@@ -464,6 +465,12 @@ int pkv_trace_buffer(void *dev_buf) {
 }
 #endif
 
+int pkv_debug_fail_frame_map(int after) {
+    if (after < -1) return PKV_E_ARG;
+    g_fail_map_after = after;
+    return PKV_OK;
+}
+
 uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d) {
     if (d == 0) return 0;
     return fastdiv_div(n, fastdiv_make(d));
@@ -532,6 +539,10 @@ static int elastic_map(Pool &p, uint32_t f) {
         return PKV_OK;
     }
     if (p.mapped[f]) return PKV_E_INTERNAL;
+    if (g_fail_map_after >= 0 && g_fail_map_after-- == 0) {
+        snprintf(g_errbuf, sizeof g_errbuf, "frame %u: mapping refused (pkv_debug_fail_frame_map)", f);
+        return PKV_E_NOMEM;
+    }
     hipMemGenericAllocationHandle_t h;
     if (!p.spare.empty()) {
         h = p.spare.back();
@@ -812,9 +823,16 @@ long balloon_resize(int model, long pages) {
             // can place a block there: they are the new tail of the model's frame list
             std::vector<uint32_t> got((size_t)(r - before));
             HIP_TRY(hipMemcpy(got.data(), m->dev.frames + before, got.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
-            for (uint32_t f : got) {
-                const int rc = elastic_map(p, f);
-                if (rc) return rc;
+            for (size_t i = 0; i < got.size(); ++i) {
+                const int rc = elastic_map(p, got[i]);
+                if (rc == PKV_OK) continue;
+                // No memory for this frame: undo the whole inflate, or kernels could be pointed at an
+                // address nothing backs.  The frames just taken are the model's newest and hold no
+                // block, so a deflate to the old size hands back exactly them, in the order that
+                // restores the free stack; those already backed go the way of any frame given back.
+                const int64_t back = book_call([&] { return pkv_launch_deflate(p.dev, m->dev, before, g_res, g_stream); });
+                for (size_t j = 0; j < i; ++j) (void)elastic_give_back(p, got[j]);
+                return back == before ? rc : PKV_E_INTERNAL;
             }
         }
         if (r >= 0) p.n_free -= r - before;

@@ -147,3 +147,43 @@ def test_dynamic_scenarios_on_an_elastic_pool(gpu, oracle, cfg_id):
     finally:
         rg.teardown()
         ro.teardown()
+
+
+def test_inflate_without_memory_is_undone(gpu, oracle):
+    """A frame mapping that fails in the middle of an inflate (forced from the host) leaves pool,
+    balloon and mappings as they were: the oracle, which never saw the call, still agrees bit for bit."""
+    fb = 2 << 20
+    pools = [gpu.pool_create_elastic(32 * fb, 16, fb), oracle.pool_create(32 * fb, 16, fb)]
+    assert min(pools) >= 0
+    bes = (gpu, oracle)
+    perm = gen.free_order(32, gen.generator(12))
+    ms = []
+    for be, pool in zip(bes, pools):
+        assert be.pool_seed_free_order(pool, perm) == 0
+        m = be.model_register(pool, 32, 8, 128, BF16, 2, 64)
+        assert be.balloon_resize(m, 4) == 4
+        assert be.seq_reserve(m, 0, 700) >= 0
+        ms.append(m)
+    try:
+        for fail_at in (0, 3):
+            assert gpu.debug_fail_frame_map(fail_at) == 0
+            assert gpu.balloon_resize(ms[0], 10) == -3             # PKV_E_NOMEM
+            assert "refused" in gpu.last_error()
+            assert_same_state(gpu, oracle, pools[0], pools[1], f"after the refused inflate ({fail_at})")
+            st = mapped_matches_owned(gpu, pools[0], fb)
+            assert st["mapped_bytes"] == 4 * fb and st["owned"][ms[0]] == 4
+        for be, m in zip(bes, ms):                                  # the hook fired once; now there is memory
+            assert be.balloon_resize(m, 10) == 10
+            assert be.seq_reserve(m, 1, 900) >= 0
+        assert_same_state(gpu, oracle, pools[0], pools[1], "after the inflate that went through")
+        assert mapped_matches_owned(gpu, pools[0], fb)["mapped_bytes"] == 10 * fb
+        kv = gen.seq_kv((12, 1), 900, 8, 128, BF16, 16)
+        assert gpu.kv_write(ms[0], 1, 0, kv["k"], kv["v"], None, None) == 900
+        rc, k, v, _, _ = gpu.kv_read(ms[0], 1, 0, 900)
+        assert rc == 900 and np.array_equal(k, kv["k"]) and np.array_equal(v, kv["v"])
+        assert gpu.device_errors() == 0
+    finally:
+        gpu.debug_fail_frame_map(-1)
+        for be, m, pool in zip(bes, ms, pools):
+            be.seq_release(m, 0), be.seq_release(m, 1)
+            assert be.balloon_resize(m, 0) == 0 and be.model_unregister(m) == 0 and be.pool_destroy(pool) == 0
