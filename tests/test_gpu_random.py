@@ -110,3 +110,82 @@ def test_random_cases(gpu, oracle):
         print(f"{N_CASES} cases, worst rel err bf16 {worst[BF16]:.2e}, e4m3 {worst[E4M3]:.2e}")
     finally:
         gpu.set_kernel_form(-1), gpu.set_split(0, 0), gpu.set_segment_cost(-1), gpu.set_xcd_weights(None)
+
+
+def test_random_bookkeeping(gpu, oracle):
+    """Random interleavings of inflate, deflate (clamped or not), reserve (single and batched, some
+    refused), release and KV appends over three co-located models: every call returns the same value
+    on both sides, and the state images agree bit for bit all along."""
+    rng = np.random.default_rng(4021)
+    frame, n_frames, n_seq, max_blocks = 64 << 10, 96, 6, 48
+    shapes = [(8, 2, 64, BF16, 1), (12, 4, 64, E4M3, 2), (16, 1, 128, BF16, 3)]
+    perm = gen.free_order(n_frames, gen.generator(4021))
+    pools, ms = [], []
+    for be in (gpu, oracle):
+        pool = be.pool_create(n_frames * frame, 16, frame)
+        assert pool >= 0 and be.pool_seed_free_order(pool, perm) == 0
+        ms.append([be.model_register(pool, hq, hkv, d, dt, n_seq, max_blocks, n_layers=L) for hq, hkv, d, dt, L in shapes])
+        assert min(ms[-1]) >= 0
+        pools.append(pool)
+    ctx = [[0] * n_seq for _ in shapes]
+    n_ok = n_refused = 0
+    try:
+        for op in range(900):
+            mi = int(rng.integers(len(shapes)))
+            kind = int(rng.integers(6))
+            if kind == 0:                                            # balloon: any target, also beyond the pool
+                pages = int(rng.integers(0, 60))
+                r = [be.balloon_resize(m[mi], pages) for be, m in zip((gpu, oracle), ms)]
+            elif kind in (1, 2):
+                s = int(rng.integers(n_seq))
+                want = ctx[mi][s] + int(rng.integers(1, 120))
+                r = [be.seq_reserve(m[mi], s, want) for be, m in zip((gpu, oracle), ms)]
+                if r[1] >= 0:
+                    ctx[mi][s] = want
+            elif kind == 3:                                          # a decode step: every row grows by one token
+                live = list(range(n_seq))
+                want = [ctx[mi][s] + 1 for s in live]
+                r = [be.seq_reserve_batch(m[mi], live, want) for be, m in zip((gpu, oracle), ms)]
+                if r[1] >= 0:
+                    for s, w in zip(live, want):
+                        ctx[mi][s] = w
+                    hq, hkv, d, dt, L = shapes[mi]
+                    layer = int(rng.integers(L))
+                    kx = gen.randn_bf16((n_seq, hkv, d), gen.generator(4021, op))
+                    lens = np.array(ctx[mi], dtype=np.int32)
+                    for be, m in zip((gpu, oracle), ms):
+                        assert be.set_layer(m[mi], layer) == 0
+                        assert be.kv_append(m[mi], kx, kx, lens) >= 0
+                    for s in range(n_seq):
+                        # read the token back; in an e4m3 block only a first slot is defined by this call
+                        # alone (later slots rescale with what the block held, and nothing filled it here)
+                        if dt == E4M3 and (ctx[mi][s] - 1) % 16 != 0:
+                            continue
+                        a, b = (be.kv_read(m[mi], s, ctx[mi][s] - 1, 1) for be, m in zip((gpu, oracle), ms))
+                        assert a[0] == b[0] == 1
+                        for x, y in zip(a[1:], b[1:]):
+                            assert (x is None and y is None) or np.array_equal(x, y), (op, mi, layer, s)
+            elif kind == 4:
+                s = int(rng.integers(n_seq))
+                r = [be.seq_release(m[mi], s) for be, m in zip((gpu, oracle), ms)]
+                ctx[mi][s] = 0
+            else:
+                s = int(rng.integers(n_seq))                         # beyond the row's capacity: refused
+                r = [be.seq_reserve(m[mi], s, 16 * max_blocks + 1 + int(rng.integers(50))) for be, m in zip((gpu, oracle), ms)]
+            assert r[0] == r[1], (op, kind, mi, r)
+            n_ok += r[1] >= 0
+            n_refused += r[1] < 0
+            if op % 60 == 59:
+                assert np.array_equal(gpu.pool_export_state(pools[0]), oracle.pool_export_state(pools[1])), op
+        assert np.array_equal(gpu.pool_export_state(pools[0]), oracle.pool_export_state(pools[1]))
+        assert n_ok > 200 and n_refused > 50, (n_ok, n_refused)
+        assert gpu.device_errors() == 0
+        print(f"{n_ok} calls went through, {n_refused} were refused alike")
+    finally:
+        for be, m, pool in zip((gpu, oracle), ms, pools):
+            for mm in m:
+                for s in range(n_seq):
+                    be.seq_release(mm, s)
+                be.balloon_resize(mm, 0)
+                be.model_unregister(mm)
+            be.pool_destroy(pool)
