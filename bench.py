@@ -71,12 +71,12 @@ def condition(torch, fn, ms):
     return i
 
 
-def profiled_traffic(workload, size):
-    """HBM bytes per k_attention launch from the committed rocprofv3 counter summary of this
+def profiled_traffic(kernel, workload, size):
+    """HBM bytes per launch of the decode kernel from the committed rocprofv3 counter summary of this
     workload (FETCH_SIZE and WRITE_SIZE runs, scaled by kernels of known size); counters cannot
     be read from inside a timed run, so the figure is the stored one or None."""
     import re
-    path = os.path.join(ROOT, "profiles", f"k_attention_{workload}.md")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}.md")
     if size != "full" or not os.path.exists(path):
         return None
     m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", open(path).read())
@@ -476,7 +476,7 @@ def main():
         "device_ms_per_step": round(dev_ms / args.steps, 5),
         "roofline": {"bound": "hbm", "kernel": KERNEL_FORM_NAME[gpu.last_kernel_form()], "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None if args.frame_bytes or args.layers > 1 else profiled_traffic(reps[0].cfg.name, args.size),
+                     "traffic": None if args.frame_bytes or args.layers > 1 else profiled_traffic(KERNEL_FORM_NAME[gpu.last_kernel_form()], reps[0].cfg.name, args.size),
                      "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": args.steps,
                      "bracketed_single_launch_us": round(br_ms / max(n_rec, 1) * 1e3, 2)},
     }
