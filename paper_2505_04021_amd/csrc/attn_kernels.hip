@@ -851,10 +851,8 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
 
         const int32_t *row_c = d.table + (size_t)ri_c.seq * d.row_stride;
         const int32_t *row_n = d.table + (size_t)ri_n.seq * d.row_stride;
-        // tokens this lane's column may see: the row's last query sees cur.L, the one before it one less, ...
+        // whether this lane's column is a query of the row at all
         const bool col_live = n < g && col.tok < ri_c.ntok;
-        const int col_lim = col_live ? cur.L - (ri_c.ntok - 1 - col.tok) : cur.L;
-        const int causal_from = cur.L - (ri_c.ntok - 1);              // the first token some column may not see
         const int n_live = cur.n_pages > 0 ? cur.pe - cur.pb : 0;       // pages to read and process
         const int n_next = (nxt.valid && nxt.n_pages > 0) ? nxt.pe - nxt.pb : 0;
         const int n_pairs = n_live > 0 ? (n_live + 1) >> 1 : 1;         // an empty segment still takes a turn
@@ -1086,7 +1084,6 @@ static_assert(PF_WAVES * PF_TILES == PKV_PREFILL_TILES, "host and kernel must ag
 template <int D, int DT>
 __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, uint8_t *lds1, uint8_t *lds2, uint8_t *lds3) {
     using TL = Tile<D, DT>;
-    constexpr int PAIR_LDS = 4 * TL::TILE_BYTES;            // K a, V a, K b, V b
     constexpr int NT = PF_TILES;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int G = lane >> 4, n = lane & 15;
