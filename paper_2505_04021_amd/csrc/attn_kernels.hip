@@ -227,6 +227,20 @@ __device__ __forceinline__ u32x2 v_half(const PageRegs<D, DT> &r, int jt) {
     return fp8x4_to_bf16x4(w);
 }
 
+// Probabilities reach the matrix unit as bf16: as hi + lo (16 significant bits, two products)
+// wherever the second product is free or the cache is bf16.  The exception is prefill (bound by
+// arithmetic, not by memory) on an e4m3 cache: its values carry 4 significant bits, one bf16
+// probability (8 bits, error 2^-9) is already 32 times finer than the V it multiplies, and the
+// second product is left out (measured error then ~4e-3 of a row's largest output against a bar of
+// 2e-2; 16 % less time).
+#ifndef PKV_E4M3_PREFILL_P_TERMS
+#define PKV_E4M3_PREFILL_P_TERMS 1
+#endif
+template <int DT, bool PREFILL>
+__device__ __forceinline__ constexpr bool p_has_lo() {
+    return DT == PKV_BF16 || !PREFILL || PKV_E4M3_PREFILL_P_TERMS == 2;
+}
+
 // bf16 hi + lo of four probabilities: 16 significant bits reach the matrix unit
 __device__ __forceinline__ void split_p(const float *p, u32x2 &hi, u32x2 &lo) {
     const uint32_t h01 = pack_bf16_rne(p[0], p[1]), h23 = pack_bf16_rne(p[2], p[3]);
@@ -309,7 +323,7 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
         u32x4 vv = tail ? mk4(va.x & ma01, va.y & ma23, vb.x & mb01, vb.y & mb23) : mk4(va.x, va.y, vb.x, vb.y);
         const bf16x8 av = *reinterpret_cast<bf16x8 *>(&vv);
         st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phv, st.acc[jt], 0, 0, 0);
-        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
+        if (p_has_lo<DT, CAUSAL>()) st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
     }
 }
 
@@ -386,7 +400,7 @@ __device__ __forceinline__ void pair_accumulate(State<D, DT> &st, const PairRegs
         u32x4 vv = mk4(va.x, va.y, vb.x, vb.y);
         const bf16x8 av = *reinterpret_cast<bf16x8 *>(&vv);
         st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phv, st.acc[jt], 0, 0, 0);
-        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
+        if (p_has_lo<DT, true>()) st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
     }
 }
 
@@ -400,7 +414,7 @@ __device__ __forceinline__ void pair_accumulate_ops(State<D, DT> &st, const u32x
         u32x4 vv = vop[jt];
         const bf16x8 av = *reinterpret_cast<bf16x8 *>(&vv);
         st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, phv, st.acc[jt], 0, 0, 0);
-        st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
+        if (p_has_lo<DT, true>()) st.acc[jt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, plv, st.acc[jt], 0, 0, 0);
     }
 }
 
