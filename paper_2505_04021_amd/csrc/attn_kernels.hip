@@ -1060,13 +1060,14 @@ __global__ __launch_bounds__(64, 1) void k_attention_deep(const AttnGroup grp) {
 // ---------------------------------------------------------------------------------
 // Chunked prefill: causal attention of a group of consecutive query tokens against the
 // paged cache (paper Sec. 5.2).  One work-group of four waves per (group, kv head).  Every
-// wave owns one tile of query tokens (16 MFMA columns = tokens x the g heads of the kv
-// head); the K and V tiles of a page pair are fetched once per work-group, one tile per
-// wave, and passed through LDS in the very byte order they have in the block, so each
-// wave reads its MFMA operands back with conflict-free 16-byte LDS loads.  Four tiles
-// share each byte fetched, against one in the decode kernel.  A group is never split:
-// no partials, no merge.  `vmap` lists the groups like the rows of a decode launch, with
-// up to 4 tiles of tokens each.
+// wave owns two tiles of query tokens (a tile = 16 MFMA columns = tokens x the g heads of
+// the kv head); the K and V tiles of a page pair are fetched once per work-group, one tile
+// per wave, and passed through LDS in the very byte order they have in the block, so each
+// wave reads its MFMA operands back with conflict-free LDS loads and uses each for both of
+// its tiles.  Eight tiles share each byte fetched, against one in the decode kernel.
+// `vmap` lists the groups like the rows of a decode launch, with up to 8 tiles of tokens
+// each.  A group of few tokens in front of a long context may come as several work-groups,
+// each with a part of the context; those leave partials that k_prefill_merge joins.
 // NL x 1 KiB from the pool straight into LDS: lane l's 16 bytes at src + 1024 j land at
 // dst + 1024 j + 16 l (the hardware adds the lane's offset to the LDS base held in M0).
 // Written as assembly so that the compiler neither drains all loads in flight before the
