@@ -329,14 +329,17 @@ def bursty_run(gpu, torch, args):
             rc = gpu.decode_attention_multi_dev([r.models[mi] for mi in act], [qs[mi] for mi in act],
                                                 [ctxs[mi] for mi in act], [outs[mi] for mi in act])
             assert rc == 0, (rc, gpu.last_error())
+            forms[gpu.last_kernel_form()] += 1
         return r.kv_bytes_step() if act else 0, len(act)
 
+    forms = [0, 0]            # launches per kernel form (the library chooses per launch)
     gpu.tune_xcd(min(args.tune, args.warmup))
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
     n_events0 = len(r.log)
     gpu.timing_enable(1)
+    forms[0] = forms[1] = 0
     kv, active, launches = 0, 0, 0
     t0 = time.perf_counter()
     for t in range(args.warmup, total):
@@ -359,9 +362,10 @@ def bursty_run(gpu, torch, args):
                    "mean_active_models": round(active / args.steps, 2), "decode_launches": launches,
                    "bookkeeping_calls": len(r.log) - n_events0,
                    "kv_bytes_per_launch": int(kv / max(launches, 1))},
-        "roofline": {"bound": "hbm", "kernel": KERNEL_FORM_NAME[gpu.last_kernel_form()], "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "kernel": KERNEL_FORM_NAME[0 if forms[0] >= forms[1] else 1], "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "avg_launch_us": round(attn_ms / max(n_rec, 1) * 1e3, 2), "launches": n_rec},
+                     "avg_launch_us": round(attn_ms / max(n_rec, 1) * 1e3, 2), "launches": n_rec,
+                     "launches_by_kernel": dict(zip(KERNEL_FORM_NAME, forms))},
     }
     r.teardown()
     print(json.dumps(result), flush=True)

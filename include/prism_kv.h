@@ -311,13 +311,14 @@ int pkv_set_split(int items, int min_share);
 int pkv_set_segment_cost(int pages);
 /* Which form of the decode kernel a launch uses: 0 = two waves per SIMD (2048 work items),
  * 1 = one wave per SIMD with twice the bytes in flight (1024 work items; bf16 caches only,
- * other launches keep form 0), -1 = the library decides by the launch (form 1 where the waves
- * would stream for long: many pages per work item). */
+ * other launches keep form 0), -1 = the library decides by the launch (form 1 for bf16 caches
+ * unless the launch is small: fewer than 24 pages per work item of form 0). */
 int pkv_set_kernel_form(int form);
 /* The form (0 or 1) of the most recent decode attention launch of this process. */
 int pkv_last_kernel_form(void);
 /* Cost model that shares the waves out among the models of a grouped launch: a page
- * costs per_mille/1000 + 0.1 per KiB of its K and V tile (default 800). */
+ * costs per_mille/1000 + 0.1 per KiB of its K and V tile (-1 = the default: 800 in kernel
+ * form 0, 4500 in form 1). */
 int pkv_set_page_cost(int per_mille);
 /* The eight XCDs of the chip do not get the same memory bandwidth, and work-groups are
  * dealt to them in turn; so each block of eight consecutive attention work items is

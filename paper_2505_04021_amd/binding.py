@@ -149,7 +149,7 @@ class PrismKV:
     def device_errors(self):
         return self.lib.pkv_device_errors()
 
-    def set_page_cost(self, per_mille=800):
+    def set_page_cost(self, per_mille=-1):
         return self.lib.pkv_set_page_cost(per_mille)
 
     def set_xcd_weights(self, w=None):

@@ -106,7 +106,7 @@ float g_xcd_w[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
 uint64_t *g_xcd_stat = nullptr;       // device: [8][2]
 int g_tune_left = 0, g_tune_done = 0;
 constexpr float kXcdWeightMin = 0.75f, kXcdWeightMax = 1.25f;
-double g_page_cost = 0.8;            // fixed cost of a page relative to 0.1 per KiB
+double g_page_cost = -1.0;           // fixed cost of a page relative to 0.1 per KiB (< 0: the default of the kernel form)
 int g_fail_map_after = -1;        // test hook: the (n+1)-th frame mapping from now fails as if memory had run out
 int g_timing = 0;                 // 0 = off, n = bracket every n-th attention launch with events
 long g_launches = 0;
@@ -176,11 +176,17 @@ void free_model_dev(Model &m) {
 constexpr int kDefaultItems = 2048;
 constexpr int kDefaultMinShare = 4;
 constexpr int kDefaultSegCost = 6;
-// The kernel's second form (one wave per SIMD, twice the bytes in flight, half the work items) pays
-// where waves stream for long: measured 324 against 343 us on 16 sequences of 32768 tokens (128 page
-// units per work item of the ordinary form), 103 against 99 us on the two-model workload (47 units).
+// The kernel's second form (one wave per SIMD, twice the bytes in flight, half the work items) is the
+// faster one for bf16 caches from middle-sized launches on: 2-5 % over shapes from 64 sequences of
+// ~1000 tokens (27 page units per work item of the ordinary form) to 16 sequences of 32768 tokens (128
+// units); below that the two forms differ by little and in either direction, and the ordinary form
+// stays.  A wave of the second form has nobody to hide its per-page arithmetic behind, so in the cost
+// model that shares the waves out among the models of a launch the fixed part of a page weighs more
+// (two-model workload, 128- and 64-wide heads: 101.8 us with the ordinary form's 0.8, 97.1-97.5 with
+// 4.5-10, against 98.5 in the ordinary form).
 constexpr int kDeepItems = 1024;
-constexpr double kDeepUnitsPerItem = 110.0;
+constexpr double kDeepUnitsPerItem = 24.0;
+constexpr double kPageCost = 0.8, kDeepPageCost = 4.5;
 
 // Expected cost of a model's pages, used to share the waves out among the models of a
 // grouped launch.  A wave spends a fixed time per page (the load - MFMA - softmax - MFMA
@@ -189,7 +195,8 @@ constexpr double kDeepUnitsPerItem = 110.0;
 double est_bytes(const Model &m, bool own, int batch, int row_stride) {
     const double blocks = own ? (double)m.used_blocks : (double)batch * row_stride;
     const double page_kib = (double)m.layer_bytes / m.Hkv / 1024.0;
-    return blocks * m.Hkv * (g_page_cost + 0.1 * page_kib);
+    const double fixed = g_page_cost >= 0.0 ? g_page_cost : (g_deep_now ? kDeepPageCost : kPageCost);
+    return blocks * m.Hkv * (fixed + 0.1 * page_kib);
 }
 
 // page units (pages plus the allowance per segment) of a model's part of a launch, as far as the host knows
@@ -404,8 +411,8 @@ int pkv_tune_xcd(int launches) {
 }
 
 int pkv_set_page_cost(int per_mille) {
-    if (per_mille < 0 || per_mille > 100000) return PKV_E_ARG;
-    g_page_cost = per_mille / 1000.0;
+    if (per_mille < -1 || per_mille > 100000) return PKV_E_ARG;
+    g_page_cost = per_mille < 0 ? -1.0 : per_mille / 1000.0;
     return PKV_OK;
 }
 
@@ -1154,11 +1161,12 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
         if (batches[i] == 0) continue;
         if (!q[i] || !ctx_lens[i] || !out[i]) return PKV_E_ARG;
         if (((uintptr_t)q[i] & 15) || ((uintptr_t)out[i] & 15)) return PKV_E_ARG;
-        total_bytes += est_bytes(*m, true, batches[i], 0) + 1.0;
         all_bf16 &= m->dtype == PKV_BF16;
         units += launch_units(*m, true, batches[i], 0);
     }
     choose_form(all_bf16, units);
+    for (int i = 0; i < n_models; ++i)              // (the cost of a page depends on the form)
+        if (batches[i] > 0) total_bytes += est_bytes(*get_model(models[i]), true, batches[i], 0) + 1.0;
     for (int i = 0; i < n_models; ++i) {
         if (batches[i] == 0) continue;
         Model *m = get_model(models[i]);
