@@ -441,9 +441,9 @@ struct Ring {
     static constexpr int N = 1 + (FLIGHT_KIB * 1024 + PAIR_BYTES - 1) / PAIR_BYTES;
 };
 // The second form of the kernel: one wave per SIMD with twice the bytes in flight (its ring lives in
-// the registers the second wave would have had).  Fewer, longer shares: better where every wave
-// streams for long (long contexts), worse where set-up and piece ends weigh more, and no good for
-// e4m3 caches, whose conversion arithmetic wants a second wave to hide behind.
+// the registers the second wave would have had).  Fewer, longer shares: measured faster for bf16
+// caches from middle-sized launches on (the host chooses), about equal on small ones, and no good
+// for e4m3 caches, whose conversion arithmetic wants a second wave to hide behind.
 #ifndef PKV_DEEP_FLIGHT_KIB
 #define PKV_DEEP_FLIGHT_KIB 32
 #endif
