@@ -303,7 +303,8 @@ long pkv_timing_read(double *attention_ms);
 int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double *gbps);
 /* Measurement / test knobs of the attention work split: `items` = work items (waves)
  * per launch, `min_share` = smallest number of pages a wave may be given; 0 selects
- * the automatic value of either. */
+ * the automatic value of either (items: what the chip holds at once; min_share: an
+ * eighth of a mean row, within 4..16 pages). */
 int pkv_set_split(int items, int min_share);
 /* What a (sequence, kv head) segment is taken to cost besides its pages when the pages
  * are cut into shares, in pages (0..256; -1 = the default).  A wave whose share holds

@@ -174,7 +174,12 @@ void free_model_dev(Model &m) {
 // starts while the memory system is saturated pays ~10 us before its first page arrives.
 // Each model of a grouped launch gets items in proportion to the KV bytes it will read.
 constexpr int kDefaultItems = 2048;
-constexpr int kDefaultMinShare = 4;
+// Smallest share of a wave, in pages.  It only binds in launches too small to give every wave slot a
+// share; there the last wave of a (sequence, kv head) merges one partial per piece, one after the
+// other, and many small pieces cost more than they gain in parallelism: an eighth of a mean row,
+// within 4..16 pages (4 sequences of 2048 tokens: 22.1 us at 4 pages, 16.5-17.3 at 8-16; 8 of 2048:
+// 28.2 / 20.4; 16 of 4096 with one kv head: 41.6 / 26.9; rows of 8-16 pages are best left at 4).
+constexpr int kDefaultMinShare = 4, kMaxAutoMinShare = 16;
 constexpr int kDefaultSegCost = 6;
 // The kernel's second form (one wave per SIMD, twice the bytes in flight, half the work items) is the
 // faster one for bf16 caches from middle-sized launches on: 2-5 % over shapes from 64 sequences of
@@ -235,7 +240,13 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.cols = cols > 0 ? cols : m.g;
     d.item_begin = 0;
     d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m.D));
-    d.min_share = g_min_share > 0 ? g_min_share : kDefaultMinShare;
+    if (g_min_share > 0) {
+        d.min_share = g_min_share;
+    } else {
+        const double row_pages = own ? (double)m.used_blocks / batch : (double)row_stride;
+        const int eighth = (int)(row_pages / 8.0);
+        d.min_share = eighth < kDefaultMinShare ? kDefaultMinShare : (eighth > kMaxAutoMinShare ? kMaxAutoMinShare : eighth);
+    }
     d.seg_cost = g_seg_cost >= 0 ? g_seg_cost : kDefaultSegCost;
     // no more items than there can be shares of min_share pages (an empty row counts as one page)
     const double units = units_hint > 0.0 ? units_hint
