@@ -293,3 +293,49 @@ def test_xcd_weights_api_and_tuning(gpu, oracle):
     assert abs(sum(w) / 8 - 1.0) < 0.05 and max(w) <= 1.25 + 1e-6 and min(w) >= 0.75 - 1e-6
     gpu.set_xcd_weights(None)
     p.close()
+
+
+def test_kernel_form_choice(gpu):
+    """Which form of the decode kernel a launch gets: the ordinary one for small launches and for
+    e4m3 caches (also when the other is asked for), the one-wave-per-SIMD form for bf16 launches
+    of 24 page units per work item or more, or when forced."""
+    pool = gpu.pool_create(1 << 30, 16, 2 << 20)
+    assert pool >= 0
+    big = gpu.model_register(pool, 32, 8, 128, BF16, 64, 128)
+    q8 = gpu.model_register(pool, 32, 8, 128, E4M3, 4, 16)
+    assert min(big, q8) >= 0
+    try:
+        assert gpu.balloon_resize(big, 400) == 400 and gpu.balloon_resize(q8, 2) == 2
+        q = gen.queries((77, 1), 64, 32, 128)
+
+        def form_after(model, n_seq, tokens):
+            for s in range(64 if model == big else 4):
+                gpu.seq_release(model, s)
+            ctx = np.full(n_seq, tokens, dtype=np.int32)
+            assert gpu.seq_reserve_batch(model, list(range(n_seq)), ctx) >= 0
+            kv = gen.seq_kv((77, 2), tokens, 8, 128, BF16 if model == big else E4M3, 16)
+            for s in range(n_seq):                      # defined values, whatever they are
+                assert gpu.kv_write(model, s, 0, kv["k"], kv["v"], kv.get("k_scale"), kv.get("v_scale")) == tokens
+            rc, out = gpu.decode_attention(model, q[:n_seq], ctx)
+            assert rc == 0 and np.isfinite(out).all()
+            return gpu.last_kernel_form()
+
+        assert gpu.set_kernel_form(-1) == 0
+        assert form_after(big, 4, 256) == 0             # 4 x 16 pages x 8 heads: a small launch
+        assert form_after(big, 64, 1600) == 1           # 64 x (100 + 7) x 8 / 2048 = 26.8 units per item
+        assert form_after(big, 64, 1200) == 0           # 64 x (75 + 7) x 8 / 2048 = 20.5
+        assert form_after(q8, 4, 200) == 0
+        assert gpu.set_kernel_form(1) == 0
+        assert form_after(big, 4, 256) == 1
+        assert form_after(q8, 4, 200) == 0              # e4m3 caches keep the ordinary form
+        assert gpu.set_kernel_form(0) == 0
+        assert form_after(big, 64, 1600) == 0
+        assert gpu.set_kernel_form(2) == -1 and gpu.set_kernel_form(-2) == -1
+        assert gpu.device_errors() == 0
+    finally:
+        gpu.set_kernel_form(-1)
+        for m, n in ((big, 64), (q8, 4)):
+            for s in range(n):
+                gpu.seq_release(m, s)
+            assert gpu.balloon_resize(m, 0) == 0 and gpu.model_unregister(m) == 0
+        assert gpu.pool_destroy(pool) == 0
