@@ -313,7 +313,7 @@ int pkv_set_segment_cost(int pages);
 /* Which form of the decode kernel a launch uses: 0 = two waves per SIMD (2048 work items),
  * 1 = one wave per SIMD with twice the bytes in flight (1024 work items; bf16 caches only,
  * other launches keep form 0), -1 = the library decides by the launch (form 1 for bf16 caches
- * unless the launch is small: fewer than 24 pages per work item of form 0). */
+ * unless the launch is small: fewer than 10 pages per work item of form 0). */
 int pkv_set_kernel_form(int form);
 /* The form (0 or 1) of the most recent decode attention launch of this process. */
 int pkv_last_kernel_form(void);

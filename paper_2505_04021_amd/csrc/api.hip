@@ -182,15 +182,15 @@ constexpr int kDefaultItems = 2048;
 constexpr int kDefaultMinShare = 4, kMaxAutoMinShare = 16;
 constexpr int kDefaultSegCost = 6;
 // The kernel's second form (one wave per SIMD, twice the bytes in flight, half the work items) is the
-// faster one for bf16 caches from middle-sized launches on: 2-5 % over shapes from 64 sequences of
-// ~1000 tokens (27 page units per work item of the ordinary form) to 16 sequences of 32768 tokens (128
-// units); below that the two forms differ by little and in either direction, and the ordinary form
-// stays.  A wave of the second form has nobody to hide its per-page arithmetic behind, so in the cost
+// faster one for bf16 caches from middle-sized launches on: 2-10 % over shapes from 16 sequences of
+// 2048 tokens (8 page units per work item of the ordinary form) to 16 sequences of 32768 tokens (128
+// units), short rows or long; below that the two forms differ by little and in either direction, and
+// the ordinary form stays.  A wave of the second form has nobody to hide its per-page arithmetic behind, so in the cost
 // model that shares the waves out among the models of a launch the fixed part of a page weighs more
 // (two-model workload, 128- and 64-wide heads: 101.8 us with the ordinary form's 0.8, 97.1-97.5 with
 // 4.5-10, against 98.5 in the ordinary form).
 constexpr int kDeepItems = 1024;
-constexpr double kDeepUnitsPerItem = 24.0;
+constexpr double kDeepUnitsPerItem = 10.0;
 constexpr double kPageCost = 0.8, kDeepPageCost = 4.5;
 
 // Expected cost of a model's pages, used to share the waves out among the models of a

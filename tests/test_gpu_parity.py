@@ -298,7 +298,7 @@ def test_xcd_weights_api_and_tuning(gpu, oracle):
 def test_kernel_form_choice(gpu):
     """Which form of the decode kernel a launch gets: the ordinary one for small launches and for
     e4m3 caches (also when the other is asked for), the one-wave-per-SIMD form for bf16 launches
-    of 24 page units per work item or more, or when forced."""
+    of 10 page units per work item or more, or when forced."""
     pool = gpu.pool_create(1 << 30, 16, 2 << 20)
     assert pool >= 0
     big = gpu.model_register(pool, 32, 8, 128, BF16, 64, 128)
@@ -323,7 +323,8 @@ def test_kernel_form_choice(gpu):
         assert gpu.set_kernel_form(-1) == 0
         assert form_after(big, 4, 256) == 0             # 4 x 16 pages x 8 heads: a small launch
         assert form_after(big, 64, 1600) == 1           # 64 x (100 + 7) x 8 / 2048 = 26.8 units per item
-        assert form_after(big, 64, 1200) == 0           # 64 x (75 + 7) x 8 / 2048 = 20.5
+        assert form_after(big, 64, 400) == 0            # 64 x (25 + 7) x 8 / 2048 = 8
+        assert form_after(big, 64, 600) == 1            # 64 x (38 + 7) x 8 / 2048 = 11.25
         assert form_after(q8, 4, 200) == 0
         assert gpu.set_kernel_form(1) == 0
         assert form_after(big, 4, 256) == 1
