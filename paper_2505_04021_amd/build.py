@@ -23,21 +23,42 @@ def newest_source_mtime():
 
 
 def build(force: bool = True, verbose: bool = False, defines=(), out: str = LIB) -> str:
-    """defines / out: build a variant with other compile-time kernel knobs beside the default library."""
+    """defines / out: build a variant with other compile-time kernel knobs beside the default library.
+    The sources are compiled side by side (one hipcc process each), then linked."""
     if not force and os.path.exists(out) and os.path.getmtime(out) >= newest_source_mtime():
         return out
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + [f for f in FLAGS if f] + [f"-D{d}" for d in defines] + ["-o", out] + \
-          [os.path.join(CSRC, s) for s in SOURCES]
-    if verbose:
-        print(" ".join(cmd))
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    # the host pass does not know the packed-fp32 feature flag and says so; harmless
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and l.strip())
-    if r.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + err)
-    if verbose and err:
-        print(err)
+    compile_flags = [f for f in FLAGS if f != "-shared"] + [f"-D{d}" for d in defines]
+
+    def quiet(text):
+        # the host pass does not know the packed-fp32 feature flag and says so; harmless
+        return "\n".join(l for l in text.splitlines() if "packed-fp32-ops" not in l and l.strip())
+
+    with tempfile.TemporaryDirectory(prefix="prismkv_build_") as tmp:
+        def compile_one(src):
+            obj = os.path.join(tmp, src + ".o")
+            cmd = [hipcc] + compile_flags + ["-c", "-o", obj, os.path.join(CSRC, src)]
+            if verbose:
+                print(" ".join(cmd))
+            r = subprocess.run(cmd, capture_output=True, text=True)
+            if r.returncode != 0:
+                raise RuntimeError(f"hipcc failed on {src}:\n" + quiet(r.stderr))
+            return obj, quiet(r.stderr)
+
+        with ThreadPoolExecutor(max_workers=len(SOURCES)) as ex:
+            done = list(ex.map(compile_one, SOURCES))
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fvisibility=hidden", "-o", out] + [o for o, _ in done]
+        if verbose:
+            print(" ".join(link))
+        r = subprocess.run(link, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc link failed:\n" + quiet(r.stderr))
+        if verbose:
+            for _, err in done:
+                if err:
+                    print(err)
     return out
 
 
