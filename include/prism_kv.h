@@ -222,6 +222,20 @@ int decode_attention(int model, const void *q, const int32_t *block_table,
                      const int32_t *ctx_lens, float *out);
 int decode_attention_ex(int model, int batch, const void *q, const int32_t *block_table,
                         int row_stride, const int32_t *ctx_lens, float *out);
+/* decode_attention_ex for callers that cannot allocate device memory or wait for the stream:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same result (up to the rounding of a different split), every cache type, but the
+ * split-K partials and arrival counters of its kernel live in a 20 MiB array that is part of
+ * the library's device code (one copy per GPU, held until the process ends) instead of the
+ * model's workspace.  The call allocates nothing, frees nothing and never waits; it enqueues
+ * a small kernel that clears the counters it needs, then the attention kernel.
+ * Limits: batch * kv_heads <= 32768 (PKV_E_RANGE, with a message in pkv_last_error()); when
+ * the partials of the usual number of work items do not fit the array, fewer items are used.
+ * All calls on one GPU share the one array: two such calls must not overlap in time (on
+ * different streams, or from different threads) — the second would clear counters the first
+ * still uses. */
+int decode_attention_static(int model, int batch, const void *q, const int32_t *block_table,
+                            int row_stride, const int32_t *ctx_lens, float *out);
 /* One grouped launch over several models of one pool (the multi-model decode
  * step); each uses the library's own block table rows 0..batches[i]-1.
  * models, batches, q, ctx_lens, out: host arrays of n_models entries holding

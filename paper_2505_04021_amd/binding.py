@@ -66,6 +66,7 @@ def _load():
         "model_set_batch": (i, [i, i, i]),
         "decode_attention": (i, [i, vp, vp, vp, vp]),
         "decode_attention_ex": (i, [i, i, vp, vp, i, vp, vp]),
+        "decode_attention_static": (i, [i, i, vp, vp, i, vp, vp]),
         "decode_attention_multi": (i, [i, vp, vp, vp, vp, vp]),
         "prefill_attention": (i, [i, i, vp, vp, vp, vp]),
         "pool_export_state": (l, [i, vp, sz]),
@@ -88,7 +89,7 @@ EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_spl
            "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_register_layers", "pkv_set_layer", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
            "seq_release", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
-           "decode_attention_ex", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats",
+           "decode_attention_ex", "decode_attention_static", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats",
            "arbitrate_requests", "place_models"]
 
 
@@ -345,6 +346,14 @@ class PrismKV:
             return self.lib.decode_attention_ex(model, b, self._p(q), None, 0, self._p(ctx_lens), self._p(out))
         return self.lib.decode_attention_ex(model, b, self._p(q), self._p(block_table), block_table.shape[1],
                                             self._p(ctx_lens), self._p(out))
+
+    def decode_attention_static_dev(self, model, q, ctx_lens, out, block_table=None):
+        """decode_attention_dev through the entry point that allocates nothing; only enqueues."""
+        b = ctx_lens.numel()
+        if block_table is None:
+            return self.lib.decode_attention_static(model, b, self._p(q), None, 0, self._p(ctx_lens), self._p(out))
+        return self.lib.decode_attention_static(model, b, self._p(q), self._p(block_table), block_table.shape[1],
+                                                self._p(ctx_lens), self._p(out))
 
     def decode_attention(self, model, q, ctx_lens, block_table=None):
         """Convenience for tests: host or device inputs -> (code, out as numpy fp32 [B][Hq][D])."""

@@ -133,6 +133,8 @@ int lib_init() {
     HIP_TRY(hipMemset(g_err, 0, sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&g_safe, 16384));
     HIP_TRY(hipMemset(g_safe, 0, 16384));
+    void *scratch_ptr = nullptr;          // resolve the current device's scratch array once, at set-up
+    HIP_TRY(pkv_static_scratch(&scratch_ptr));
     return PKV_OK;
 }
 
@@ -214,10 +216,11 @@ void choose_form(bool all_bf16, double units) {
     g_deep_now = all_bf16 && (g_deep_mode == 1 || (g_deep_mode < 0 && g_items == 0 && units / kDefaultItems >= kDeepUnitsPerItem));
 }
 
+// Everything of a launch descriptor except its split-K workspace.
 // cols: MFMA columns per kv head (0 = g: one query token per row); units_hint: upper bound of the
 // page units of the launch when the rows are not whole sequences (0 = derive from the blocks in use)
-int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *table, int row_stride,
-              const int32_t *ctx_lens, float *out, double share_of_launch, int cols = 0, double units_hint = 0.0) {
+void fill_desc_core(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *table, int row_stride,
+                    const int32_t *ctx_lens, float *out, double share_of_launch, int cols = 0, double units_hint = 0.0) {
     Pool &p = g_pools[m.pool];
     const bool own = table == nullptr;
     d.pool_base = p.base + (size_t)m.layer * m.layer_bytes;      // the layer's part of every block
@@ -257,26 +260,41 @@ int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *ta
     d.n_items = items < 1.0 ? 1 : (int)items;                // never more than the slots in total
     if (d.n_items >= 8) d.n_items &= ~7;                     // whole blocks of eight: one item per XCD
     d.weighted = d.n_items % 8 == 0 ? 1 : 0;
-    const size_t need = (size_t)2 * d.n_items * d.cols * (m.D + 2);
-    if (need > m.ws_floats) {
+}
+
+// floats of split-K partials a launch of n_items work items needs: two partials per item
+size_t ws_floats_for(const Model &m, int n_items, int cols) { return (size_t)2 * n_items * cols * (m.D + 2); }
+
+// The model's own workspace.  It is sized at registration for every launch the default settings can
+// produce from the library's table; only a caller's table with more rows than the model has, or a
+// work-item count raised through pkv_set_split, makes it grow here (after waiting for the stream).
+int ensure_workspace(Model &m, size_t need_floats, size_t n_cnt, size_t slack = 2) {
+    if (need_floats > m.ws_floats) {
         HIP_TRY(hipStreamSynchronize(g_stream));
         uc_release(m.ws);
         m.ws_floats = 0;
-        m.ws = (float *)uc_alloc(need * sizeof(float) * 2);
+        m.ws = (float *)uc_alloc(need_floats * sizeof(float) * slack);
         if (!m.ws) return PKV_E_NOMEM;
-        m.ws_floats = need * 2;
+        m.ws_floats = need_floats * slack;
     }
-    d.ws = m.ws;
-    const size_t n_cnt = (size_t)batch * m.Hkv;
     if (n_cnt > m.cnt_cap) {
         HIP_TRY(hipStreamSynchronize(g_stream));
         uc_release(m.cnt);
         m.cnt_cap = 0;
-        m.cnt = (uint32_t *)uc_alloc(n_cnt * 2 * sizeof(uint32_t));
+        m.cnt = (uint32_t *)uc_alloc(n_cnt * slack * sizeof(uint32_t));
         if (!m.cnt) return PKV_E_NOMEM;
-        HIP_TRY(hipMemset(m.cnt, 0, n_cnt * 2 * sizeof(uint32_t)));
-        m.cnt_cap = n_cnt * 2;
+        HIP_TRY(hipMemset(m.cnt, 0, n_cnt * slack * sizeof(uint32_t)));
+        m.cnt_cap = n_cnt * slack;
     }
+    return PKV_OK;
+}
+
+int fill_desc(AttnDesc &d, Model &m, int batch, const void *q, const int32_t *table, int row_stride,
+              const int32_t *ctx_lens, float *out, double share_of_launch, int cols = 0, double units_hint = 0.0) {
+    fill_desc_core(d, m, batch, q, table, row_stride, ctx_lens, out, share_of_launch, cols, units_hint);
+    const int rc = ensure_workspace(m, ws_floats_for(m, d.n_items, d.cols), (size_t)batch * m.Hkv);
+    if (rc) return rc;
+    d.ws = m.ws;
     d.cnt = m.cnt;
     return PKV_OK;
 }
@@ -804,6 +822,16 @@ int model_register_layers(int pool, int q_heads, int kv_heads, int head_dim, int
         fail_hip(err, "model_register");
         return PKV_E_NOMEM;
     }
+    // the split-K workspace of decode attention, for the largest launch the default settings give
+    // this model, so that decode_attention* neither waits nor allocates (graph capture needs no
+    // priming launch)
+    {
+        const int rc = ensure_workspace(m, ws_floats_for(m, kDefaultItems, m.g), (size_t)max_seqs * kv_heads, 1);
+        if (rc) {
+            free_model_dev(m);
+            return rc;
+        }
+    }
     m.live = true;
     g_models[id] = m;
     return id;
@@ -1062,6 +1090,51 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     if (rc) return rc;
 
     return launch_attention(grp);
+}
+
+int decode_attention_static(int model, int batch, const void *q, const int32_t *block_table, int row_stride,
+                            const int32_t *ctx_lens, float *out) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (batch < 0) return PKV_E_ARG;
+    if (batch == 0) return PKV_OK;
+    if (!q || !ctx_lens || !out) return PKV_E_ARG;
+    if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return PKV_E_ARG;
+    if (block_table) {
+        if (row_stride <= 0) return PKV_E_ARG;
+        if (g_pools[m->pool].elastic) return PKV_E_UNSUPPORTED;
+    } else if (batch > m->dev.max_seqs) {
+        return PKV_E_RANGE;
+    }
+    const size_t n_cnt = (size_t)batch * m->Hkv;
+    if (n_cnt > PKV_STATIC_COUNTERS) {
+        snprintf(g_errbuf, sizeof g_errbuf, "decode_attention_static: batch * kv_heads = %zu exceeds the %d arrival counters of the scratch array",
+                 n_cnt, PKV_STATIC_COUNTERS);
+        return PKV_E_RANGE;
+    }
+    void *scratch_ptr = nullptr;
+    HIP_TRY(pkv_static_scratch(&scratch_ptr));
+    AttnGroup grp;
+    grp.n = 1;
+    g_deep_now = false;                   // the ordinary kernel form, every cache type
+    AttnDesc &d = grp.m[0];
+    fill_desc_core(d, *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
+    // the partials of the work items must fit what is left of the array behind the counters: fewer,
+    // longer shares otherwise (any number of items gives the same result up to rounding)
+    const size_t cnt_bytes = (size_t)PKV_STATIC_COUNTERS * sizeof(uint32_t);
+    const size_t per_item = ws_floats_for(*m, 1, d.cols) * sizeof(float);
+    const size_t fit = (PKV_STATIC_SCRATCH_BYTES - cnt_bytes) / per_item;
+    if (fit < 1) return PKV_E_RANGE;
+    if ((size_t)d.n_items > fit) {
+        d.n_items = (int)fit;
+        if (d.n_items >= 8) d.n_items &= ~7;
+        d.weighted = d.n_items % 8 == 0 ? 1 : 0;
+    }
+    d.cnt = (uint32_t *)scratch_ptr;
+    d.ws = (float *)((uint8_t *)scratch_ptr + cnt_bytes);
+    fill_tune(grp.tune, false);
+    HIP_TRY(pkv_launch_attention_static(grp, d.cnt, n_cnt, g_stream));
+    return PKV_OK;
 }
 
 int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens, const int32_t *ctx_lens, float *out) {

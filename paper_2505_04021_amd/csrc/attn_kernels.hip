@@ -692,7 +692,12 @@ struct Cut {
 #define PKV_STAMP(slot) do { } while (0)
 #endif
 
-template <int D, int DT, int FLIGHT_KIB = PKV_FLIGHT_KIB>
+// CACHED: the partials and arrival counters sit in ordinary (cached) device memory instead of
+// uncached memory.  The L2 caches of the eight XCDs are not coherent with each other for such
+// memory, so the hand-over of a partial follows the memory model by the book: partial stores,
+// release fence, arrival atomic (agent scope) on the writer's side; arrival atomic, acquire fence,
+// partial loads on the merger's side.
+template <int D, int DT, int FLIGHT_KIB = PKV_FLIGHT_KIB, bool CACHED = false>
 __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, int item, float *s_m, float *s_l) {
     using TL = Tile<D, DT>;
     const int lane = threadIdx.x;
@@ -976,6 +981,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                 // Order is all that is left to enforce: the partial must have landed before the
                 // counter moves.  The count itself is looked at only when the share is finished.
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (CACHED) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
                 uint32_t arrived = 0;
                 if (lane == 0) arrived = atomicAdd(d.cnt + (size_t)cur.seq * Hkv + cur.kvh, 1u);
                 Pending &pd = cur.pb == 0 ? pend_b : pend_a;
@@ -1012,14 +1018,17 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     if (pend_a.valid) {
         const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)pend_a.arrived);
         if (arrived == pend_a.k1 - pend_a.k0) {
-            if (lane == 0) d.cnt[(size_t)pend_a.seq * Hkv + pend_a.kvh] = 0u;     // ready for the next launch
+            // ready for the next launch (cached counters are cleared by the host before every launch instead)
+            if (!CACHED && lane == 0) d.cnt[(size_t)pend_a.seq * Hkv + pend_a.kvh] = 0u;
+            if (CACHED) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             merge_segment<D>(d, pend_a, lane, s_m, s_l);
         }
     }
     if (pend_b.valid) {
         const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)pend_b.arrived);
         if (arrived == pend_b.k1 - pend_b.k0) {
-            if (lane == 0) d.cnt[(size_t)pend_b.seq * Hkv + pend_b.kvh] = 0u;
+            if (!CACHED && lane == 0) d.cnt[(size_t)pend_b.seq * Hkv + pend_b.kvh] = 0u;
+            if (CACHED) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             merge_segment<D>(d, pend_b, lane, s_m, s_l);
         }
     }
@@ -1055,6 +1064,25 @@ __global__ __launch_bounds__(64, 1) void k_attention_deep(const AttnGroup grp) {
     // bf16 caches only (the host never sends another kind here)
     if (d.D == 128) attn_wave<128, PKV_BF16, PKV_DEEP_FLIGHT_KIB>(d, grp.tune, item, s_m, s_l);
     else attn_wave<64, PKV_BF16, PKV_DEEP_FLIGHT_KIB>(d, grp.tune, item, s_m, s_l);
+}
+
+// The decode kernel for callers that may not allocate: the same code with its split-K partials and
+// arrival counters in the library's file-scope scratch array (ordinary cached memory).
+__global__ __launch_bounds__(64, PKV_WAVES) void k_attention_static(const AttnGroup grp) {
+    __shared__ float s_m[MAX_PIECES * 16], s_l[MAX_PIECES * 16];
+    const AttnDesc &d = grp.m[0];
+    const int item = blockIdx.x;
+    if (d.dtype == PKV_BF16) {
+        if (d.D == 128) attn_wave<128, PKV_BF16, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_BF16, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
+    } else {
+        if (d.D == 128) attn_wave<128, PKV_E4M3, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_E4M3, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
+    }
+}
+
+__global__ void k_clear_words(uint32_t *p, size_t n) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0u;
 }
 
 // ---------------------------------------------------------------------------------
@@ -1503,6 +1531,43 @@ hipError_t pkv_launch_attention(const AttnGroup &grp, bool deep, hipStream_t s, 
     if (e != hipSuccess) return e;
     if (ev && (e = hipEventRecord(ev[1], s)) != hipSuccess) return e;
     return hipSuccess;
+}
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------
+// Arrival counters first, split-K partials behind them.  Every GPU holds its own copy of the array
+// at its own address; in host code the array's name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[PKV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];     // per device: the address of its copy of `scratch`, once resolved
+}  // namespace
+
+// Address of the current device's copy of the scratch array (resolved once per device).
+hipError_t pkv_static_scratch(void **ptr) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+// One model, the ordinary kernel form; d.ws and d.cnt point into the scratch array.  The counters the
+// launch uses are cleared first (by a kernel: a caller may be capturing the stream into a graph).
+hipError_t pkv_launch_attention_static(const AttnGroup &grp, uint32_t *cnt, size_t n_cnt, hipStream_t s) {
+    if (grp.n != 1 || grp.m[0].n_items <= 0) return hipErrorInvalidValue;
+    const unsigned blocks = (unsigned)((n_cnt + 255) / 256);
+    hipLaunchKernelGGL(k_clear_words, dim3(blocks < 64 ? (blocks ? blocks : 1) : 64), dim3(256), 0, s, cnt, n_cnt);
+    hipLaunchKernelGGL(k_attention_static, dim3(grp.m[0].n_items), dim3(64), 0, s, grp);
+    return hipGetLastError();
 }
 
 hipError_t pkv_launch_prefill(const AttnDesc &d, int n_groups, bool any_split, hipStream_t s) {

@@ -14,6 +14,9 @@
 #define PKV_MAX_BATCH_OPS 2048
 #define PKV_MAX_SEQS 4096
 #define PKV_BOOK_THREADS 1024
+// The file-scope scratch array of decode_attention_static: arrival counters, then split-K partials.
+#define PKV_STATIC_COUNTERS 32768
+#define PKV_STATIC_SCRATCH_BYTES ((size_t)20 << 20)
 
 // Unsigned division by an invariant divisor with one multiply-high and two shifts
 // (Granlund & Montgomery, "Division by invariant integers using multiplication").
@@ -132,6 +135,9 @@ hipError_t pkv_launch_kv_read(const AttnDesc &d, int seq, int tok_begin, int n_t
 hipError_t pkv_launch_kv_append(const AttnDesc &d, const void *k_new, const void *v_new, hipStream_t s);
 // ev: NULL or two events recorded before and after the attention kernel
 hipError_t pkv_launch_attention(const AttnGroup &grp, bool deep, hipStream_t s, hipEvent_t *ev);
+// the entry point that allocates nothing: the current device's copy of the library's scratch array
+hipError_t pkv_static_scratch(void **ptr);
+hipError_t pkv_launch_attention_static(const AttnGroup &grp, uint32_t *cnt, size_t n_cnt, hipStream_t s);
 // chunked prefill: d.vmap lists n_groups groups of up to PKV_PREFILL_TILES * (d.cols / d.g) query tokens
 hipError_t pkv_launch_prefill(const AttnDesc &d, int n_groups, bool any_split, hipStream_t s);
 hipError_t pkv_launch_stream_read(const void *src, size_t bytes, size_t granule_bytes, uint32_t *sink, hipStream_t s);
