@@ -1,10 +1,12 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py
 times (grouped launch over the library's own block tables, automatic work split).
 
-The oracle cannot afford whole batches at these sizes, so both sides write the KV
-of a sample of the sequences only (everything else keeps whatever the pool held);
-bookkeeping is replayed in full and compared bit for bit, attention is compared on
-the sampled sequences' output rows.
+Whole batches: one step each of cfg 2, cfg 4 and cfg 5 with the KV of every sequence
+written on both sides and every output row compared (the oracle needs a fraction of a
+second to a second per such step on the machine's host cores; writing the KV is the larger
+part).  The multi-step runs (cfg 5's cycles, cfg 3's 1000 steps) write the KV of a sample
+of the sequences only (everything else keeps whatever the pool held); bookkeeping is
+replayed in full and compared bit for bit, attention on the sampled sequences' rows.
 """
 import numpy as np
 import pytest
@@ -69,6 +71,29 @@ def sample_longest_median_shortest(cfg, per_model):
     return chosen
 
 
+@pytest.mark.parametrize("cfg_id", [2, 4, 5])
+def test_full_size_whole_batch(gpu, oracle, cfg_id):
+    """Every sequence filled, every output row of the grouped launch compared with the oracle."""
+    cfg = make_config(cfg_id, "full")
+    rg, ro = Runner(gpu, cfg).setup(), Runner(oracle, cfg).setup()
+    try:
+        assert rg.log == ro.log
+        assert np.array_equal(gpu.pool_export_state(rg.pool), oracle.pool_export_state(ro.pool))
+        outs = grouped_decode(gpu, rg, 0)
+        worst, rows = 0.0, 0
+        for mi in rg.active_models():
+            rc, ref = oracle.decode_attention(ro.models[mi], ro.queries(0, mi), ro.ctx[mi])
+            assert rc == 0
+            err = row_rel_err(outs[mi], ref)
+            assert err <= TOL[cfg.models[mi].dtype], (cfg_id, mi, err)
+            worst, rows = max(worst, err), rows + ref.shape[0] * ref.shape[1]
+        assert gpu.device_errors() == 0
+        print(f"cfg {cfg_id}: {rows} output rows, worst rel err {worst:.2e}, kernel form {gpu.last_kernel_form()}")
+    finally:
+        rg.teardown()
+        ro.teardown()
+
+
 @pytest.mark.parametrize("cfg_id,per_model", [(2, 3), (4, 1), (5, 3)])
 def test_full_size_static(gpu, oracle, cfg_id, per_model):
     cfg = make_config(cfg_id, "full")
@@ -96,13 +121,16 @@ def test_full_size_bursty_1000_steps(gpu, oracle):
     for the sampled sequences (every 16th admitted sequence of each model)."""
     cfg = make_config(3, "full")
     fill = lambda mi, uid: uid % 16 == 0          # noqa: E731
-    rg, ro = Runner(gpu, cfg, fill=fill).setup(), Runner(oracle, cfg, fill=fill).setup()
+    # every admission is one enqueued reserve call, every departure one enqueued release call
+    rg, ro = Runner(gpu, cfg, fill=fill, mode="enqueue").setup(), Runner(oracle, cfg, fill=fill, mode="enqueue").setup()
     check = set(range(10)) | set(range(0, cfg.steps, 50))
     worst, n_active = 0.0, 0
     try:
         for t in range(cfg.steps):
             rg.step(t)
             ro.step(t)
+            rg.flush()
+            ro.flush()
             assert rg.log == ro.log, t
             assert np.array_equal(gpu.pool_export_state(rg.pool), oracle.pool_export_state(ro.pool)), t
             n_active += len(rg.active_models())
