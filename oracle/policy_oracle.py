@@ -18,53 +18,56 @@ import math
 
 
 def arbitrate(arrival, slo, prompt_len, speed, now):
+    """Sec. 5.2, Alg. 2.  The problem: one server, free from `now` on, jobs i with processing time
+    cost_i = prompt_len_i / speed_i and due date due_i = arrival_i + slo_i; keep as many jobs as can
+    all finish by their due dates when run back to back.  The Moore-Hodgson rule solves it: run
+    through the jobs by rising due date, keep each, and whenever the kept jobs no longer all fit in
+    front of the newcomer's due date, give up the costliest kept job.  Returns the kept indices in
+    running order."""
     n = len(arrival)
-    R = sorted(range(n), key=lambda i: (arrival[i] + slo[i], i))          # ascending deadlines
-    S = []
-    current_time = now
-    for r in R:
-        e_r = prompt_len[r] / speed[r]
-        S.append(r)
-        current_time = current_time + e_r
-        if current_time > arrival[r] + slo[r]:
-            # pop the request with the longest execution time (the first such in S)
-            longest = max(prompt_len[x] / speed[x] for x in S)
-            r_max = next(x for x in S if prompt_len[x] / speed[x] == longest)
-            S.remove(r_max)
-            current_time = current_time - prompt_len[r_max] / speed[r_max]
-    return S
+    due = [arrival[i] + slo[i] for i in range(n)]
+    cost = [prompt_len[i] / speed[i] for i in range(n)]
+    kept = []                      # by rising due date
+    busy_until = now               # when the kept jobs, run back to back, are done
+    for i in sorted(range(n), key=lambda i: (due[i], i)):
+        kept.append(i)
+        busy_until = busy_until + cost[i]
+        if busy_until > due[i]:
+            victim = max(kept, key=lambda j: cost[j])      # the first of the costliest, in running order
+            kept.remove(victim)
+            busy_until = busy_until - cost[victim]
+    return kept
 
 
 def place(n_gpus, capacity, tau, token_rate, token_size, slo, weight, current_gpu=None, tp_group=None):
-    M = len(token_rate)
-    demand = [token_rate[j] * token_size[j] / slo[j] for j in range(M)]
-    order = sorted(range(M), key=lambda j: (-demand[j], j))               # descending SLO-weighted rate
-    shared_kv = [capacity] * n_gpus
-    w_token_rate = [0.0] * n_gpus
-    out = [-1] * M
+    """Sec. 5.1, Alg. 1 with the tensor-parallel rule of the appendix.  Every GPU is a pair (load, room):
+    load = the summed SLO-weighted token rates of the models it hosts, room = capacity minus their
+    weights; its KV pressure ratio is load / room (infinite once no room is left).  Models are dealt out
+    by falling rate; each goes where the pressure is lowest, except that a model already living on a GPU
+    whose pressure is at most tau above the lowest stays there (no migration for a small gain), and no
+    two parts of one tensor-parallel model share a GPU."""
+    n = len(token_rate)
+    rate = [token_rate[j] * token_size[j] / slo[j] for j in range(n)]
+    load, room = [0.0] * n_gpus, [capacity] * n_gpus
+    home = [-1] * n
 
-    def kvpr(i):
-        return w_token_rate[i] / shared_kv[i] if shared_kv[i] > 0 else math.inf
+    def pressure(g):
+        return load[g] / room[g] if room[g] > 0 else math.inf
 
-    for j in order:
-        banned = set()
+    for j in sorted(range(n), key=lambda j: (-rate[j], j)):
+        taken = set()                                        # GPUs that already host a sibling part
         if tp_group is not None and tp_group[j] >= 0:
-            banned = {out[o] for o in range(M) if o != j and out[o] >= 0 and tp_group[o] == tp_group[j]}
-        candidates = [i for i in range(n_gpus) if i not in banned]
-        if not candidates:
+            taken = {home[o] for o in range(n) if o != j and home[o] >= 0 and tp_group[o] == tp_group[j]}
+        allowed = [g for g in range(n_gpus) if g not in taken]
+        if not allowed:
             raise ValueError("more tensor-parallel parts than GPUs")
-        best_idx = min(candidates, key=lambda i: (kvpr(i), i))
-        best_r = kvpr(best_idx)
-        g = -1 if current_gpu is None else current_gpu[j]
-        if g >= 0 and g not in banned:
-            current_r = kvpr(g)
-            best_gpu = best_idx if current_r - best_r > tau else g
-        else:
-            best_gpu = best_idx
-        out[j] = best_gpu
-        w_token_rate[best_gpu] += demand[j]
-        shared_kv[best_gpu] -= weight[j]
-    return out
+        calmest = min(allowed, key=lambda g: (pressure(g), g))
+        here = -1 if current_gpu is None else current_gpu[j]
+        stays = here >= 0 and here not in taken and not (pressure(here) - pressure(calmest) > tau)
+        home[j] = here if stays else calmest
+        load[home[j]] += rate[j]
+        room[home[j]] -= weight[j]
+    return home
 
 
 def max_kvpr(n_gpus, capacity, placement, token_rate, token_size, slo, weight):
