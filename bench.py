@@ -52,7 +52,9 @@ def parse_args():
                     help="untimed launches for this long before the warm-up, so that the clocks have settled (0 = none)")
     ap.add_argument("--kernel-form", type=int, default=-1, choices=[-1, 0, 1],
                     help="decode kernel: 0 = two waves per SIMD, 1 = one wave with a deeper ring, -1 = chosen by the launch")
-    ap.add_argument("--tune", type=int, default=48, help="untimed launches that tune the per-XCD share weights before the warm-up (0 = equal weights)")
+    ap.add_argument("--tune", type=int, default=24,
+                    help="weight updates the library's own tuning of the per-XCD shares may make (24 = what a process starts with; 0 = equal weights)")
+    ap.add_argument("--no-legs", dest="legs", action="store_false", help="skip the secondary workloads (cfg 1, 3, 4, 5, cfg 2 on 64 KiB frames)")
     ap.add_argument("--page-cost", type=int, default=-1, help="fixed cost of a page in the wave-sharing model, per mille (-1 = default)")
     ap.add_argument("--sweep-items", default="", help="comma list of work-item counts to time before the main run (stderr)")
     return ap.parse_args()
@@ -128,12 +130,37 @@ def balloon_latency(gpu, torch):
             gpu.seq_release(m, s)
         t3 = time.perf_counter(); assert gpu.balloon_resize(m, 0) == 0; t4 = time.perf_counter()
         t_inf.append(t1 - t0); t_res.append(t2 - t1); t_rel.append((t3 - t2) / 32); t_def.append(t4 - t3)
+    # the same calls enqueue-only: what a call costs the stream (events around 50 inflate / deflate pairs and
+    # around 50 reserve / release pairs, back to back) and what it costs the host to issue
+    e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    torch.cuda.synchronize()
+    h0 = time.perf_counter()
+    e0.record()
+    for _ in range(50):
+        gpu.balloon_resize_enqueue(m, 176)
+        gpu.balloon_resize_enqueue(m, 0)
+    e1.record()
+    h1 = time.perf_counter()
+    last = gpu.balloon_resize_enqueue(m, 176)
+    for _ in range(50):
+        gpu.seq_reserve_batch_enqueue(m, seqs, ctx)
+        last = gpu.seq_release_batch_enqueue(m, seqs)
+    e2.record()
+    assert gpu.ticket_result(last) == 5632
+    torch.cuda.synchronize()
+    assert gpu.balloon_resize(m, 0) == 0 and gpu.device_errors() == 0
     gpu.model_unregister(m)
     gpu.pool_destroy(pool)
     med = lambda x: round(float(np.median(x) * 1e6), 2)
     res = {"inflate_176_frames_us": med(t_inf), "deflate_176_frames_us": med(t_def),
+           "inflate_us_per_frame": round(med(t_inf) / 176, 4), "deflate_us_per_frame": round(med(t_def) / 176, 4),
            "reserve_batch_5632_blocks_us": med(t_res), "release_176_blocks_us": med(t_rel),
-           "kind": "host wall clock per call, median of 50"}
+           "kind": "host wall clock per call (launch + kernel + result read-back), median of 50",
+           "enqueued_resize_176_frames_device_us": round(e0.elapsed_time(e1) * 1e3 / 100, 2),
+           "enqueued_resize_device_us_per_frame": round(e0.elapsed_time(e1) * 1e3 / 100 / 176, 4),
+           "enqueued_resize_host_us": round((h1 - h0) * 1e6 / 100, 2),
+           "enqueued_reserve_plus_release_5632_blocks_device_us": round(e1.elapsed_time(e2) * 1e3 / 50, 2),
+           "enqueued_kind": "enqueue-only forms: stream time per call from events around 100 back-to-back calls; host time to issue one"}
     # the same balloon on an elastic pool: frames are mapped when acquired and unmapped when given back
     for name, spare in (("elastic", 0), ("elastic_prealloc_176", 176)):
         pool = gpu.pool_create_elastic(8 << 30, 16, 2 << 20)
@@ -296,78 +323,180 @@ def cpu_baseline(rep, seconds):
                       f"{t_total:.1f} s in total, fp64, {threads} OpenMP threads), then one step on one thread"}
 
 
-def bursty_run(gpu, torch, args):
-    """The bursty scenario (models switch on and off by a two-state Markov chain): each
-    step first applies its bookkeeping events (release + deflate of a model that went idle,
-    inflate + admission of one that woke up), then decodes every active model in one
-    launch.  The KV cache keeps whatever the pool memory holds (the values do not change
-    the time), queries are drawn once per model.  `value` counts the KV bytes of the
-    decoded steps over the whole wall time, events included."""
+def percentiles(us):
+    import numpy as np
+    a = np.asarray(us, dtype=np.float64)
+    return {"median": round(float(np.median(a)), 2), "p10": round(float(np.percentile(a, 10)), 2),
+            "p90": round(float(np.percentile(a, 90)), 2), "n": int(a.size)}
+
+
+def per_step_times(torch, step, n):
+    """Device time of n consecutive steps, one by one: an event behind every step on the library's
+    stream; a step's time is the span to the event before it (the gap to the next launch included)."""
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n + 1)]
+    torch.cuda.synchronize()
+    evs[0].record()
+    for i in range(n):
+        step(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    return [evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n)]
+
+
+def timed_decode(gpu, torch, step, bytes_of_step, steps, warmup, condition_ms):
+    """The timing protocol of a decode workload: conditioning, warm-up, `steps` timed steps between two
+    events on the library's stream (and the host's clock around them), then the same steps once more
+    with an event behind each for the spread."""
+    n_cond = condition(torch, step, condition_ms) if condition_ms > 0 else 0
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    dev_ms = ev0.elapsed_time(ev1)
+    total = sum(bytes_of_step(i) for i in range(steps))
+    dist = percentiles(per_step_times(torch, step, min(steps, 200)))
+    return {"wall_s": wall, "dev_ms": dev_ms, "bytes": total, "n_cond": n_cond, "dist": dist,
+            "form": gpu.last_kernel_form()}
+
+
+def decode_summary(t, steps):
+    """step time, GB/s and fraction of the HBM peak of a timed_decode() result, by the device's clock"""
+    us = t["dev_ms"] * 1e3 / steps
+    gbps = t["bytes"] / (t["dev_ms"] * 1e-3) / 1e9
+    return {"step_us": round(us, 2), "step_us_wall": round(t["wall_s"] * 1e6 / steps, 2), "step_us_spread": t["dist"],
+            "kv_gbps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+            "kernel": KERNEL_FORM_NAME[t["form"]], "steps": steps}
+
+
+def static_leg(gpu, torch, cfg_id, steps, warmup, condition_ms, replicas, frame_bytes=0):
+    """A secondary workload with a fixed batch (cfg 1, 2, 4, 5): set up, timed by the same protocol, torn down."""
+    reps = build_replicas(gpu, cfg_id, "full", replicas, frame_bytes)
+    inputs = [device_inputs(torch, rep, 0) for rep in reps]
+    kv = [rep.kv_bytes_step() for rep in reps]
+
+    def step(i):
+        mids, qs, ctxs, outs = inputs[i % len(reps)]
+        rc = gpu.decode_attention_multi_dev(mids, qs, ctxs, outs)
+        assert rc == 0, (rc, gpu.last_error())
+
+    t = timed_decode(gpu, torch, step, lambda i: kv[i % len(reps)], steps, warmup, condition_ms)
+    assert gpu.device_errors() == 0
+    res = decode_summary(t, steps)
+    res.update({"workload": reps[0].cfg.name, "kv_bytes_per_step": int(sum(kv) / len(kv)), "replicas_rotated": len(reps),
+                "frame_bytes": reps[0].cfg.frame_bytes, "ideal_us_at_hbm_peak": round(sum(kv) / len(kv) / HBM_PEAK_GBPS / 1e3, 1)})
+    for rep in reps:
+        rep.teardown()
+    return res
+
+
+def bursty_leg(gpu, torch, size, steps, warmup, frame_bytes=0):
+    """The bursty scenario (cfg 3: models switch on and off by a two-state Markov chain): each step
+    first issues its bookkeeping (release + deflate of a model that fell idle, inflate + admission of
+    one that woke up: one enqueue-only call each, nothing waits), then decodes every active model in
+    one launch.  The scenario is laid out as data beforehand, so the timed loop holds the library's
+    calls and nothing of the harness; the calls' results are fetched one step late (they must all be
+    successes) and never waited for.  The KV cache keeps whatever the pool memory holds (the values do
+    not change the time), queries are drawn once per model.  The whole-step figure counts the KV bytes
+    of the decoded steps over the whole wall time, bookkeeping included."""
     import numpy as np
     from workloads.scenarios import Runner, make_config
-    cfg = make_config(3, args.size)
-    if args.frame_bytes:
-        cfg.frame_bytes = args.frame_bytes
-    total = args.warmup + args.steps
+    cfg = make_config(3, size)
+    if frame_bytes:
+        cfg.frame_bytes = frame_bytes
+    total = warmup + steps
     if total > cfg.steps:
         print(f"bench.py: the scenario has {cfg.steps} steps; --warmup + --steps is {total}", file=sys.stderr)
         sys.exit(2)
-    r = Runner(gpu, cfg, write_kv=False).setup()
-    qs = [torch.from_numpy(r.queries(0, mi).view(np.int16)).cuda() for mi in range(len(cfg.models))]
+    r = Runner(gpu, cfg, write_kv=False, mode="enqueue").setup()
+    tape = r.plan(0, total)
+    n = len(cfg.models)
+    qs = [torch.from_numpy(r.queries(0, mi).view(np.int16)).cuda() for mi in range(n)]
     outs = [torch.empty((s.batch, s.q_heads, s.head_dim), dtype=torch.float32, device="cuda") for s in cfg.models]
     ctxs = [torch.zeros(s.batch, dtype=torch.int32, device="cuda") for s in cfg.models]
-    uids = [None] * len(cfg.models)
+    staged = [[torch.from_numpy(adm[mi]).pin_memory() if mi in adm else None for mi in range(n)] for _, _, adm, _ in tape]
+    forms = [0, 0]
+    tickets = []              # (step, ticket) of calls whose result has not been looked at yet
 
     def step(t):
-        r.step(t)
-        act = r.active_models()
-        for mi in act:
-            if uids[mi] is None or not np.array_equal(uids[mi], r.uid[mi]):    # a new batch was admitted
-                ctxs[mi].copy_(torch.from_numpy(r.ctx[mi]))
-                uids[mi] = r.uid[mi].copy()
+        calls, act, adm, _ = tape[t]
+        for name, mi, a in calls:
+            tk = getattr(gpu, name)(r.models[mi], *a)
+            assert tk >= 0, (name, tk)
+            tickets.append((t, tk))
+        for mi in adm:
+            ctxs[mi].copy_(staged[t][mi], non_blocking=True)
         if act:
             rc = gpu.decode_attention_multi_dev([r.models[mi] for mi in act], [qs[mi] for mi in act],
                                                 [ctxs[mi] for mi in act], [outs[mi] for mi in act])
             assert rc == 0, (rc, gpu.last_error())
             forms[gpu.last_kernel_form()] += 1
-        return r.kv_bytes_step() if act else 0, len(act)
+        while tickets and tickets[0][0] < t:          # the previous steps' calls: done long ago
+            res = gpu.ticket_result(tickets.pop(0)[1])
+            assert res >= 0, res
 
-    forms = [0, 0]            # launches per kernel form (the library chooses per launch)
-    gpu.tune_xcd(min(args.tune, args.warmup))
-    for t in range(args.warmup):
+    for t in range(warmup):
         step(t)
     torch.cuda.synchronize()
-    n_events0 = len(r.log)
     gpu.timing_enable(1)
     forms[0] = forms[1] = 0
-    kv, active, launches = 0, 0, 0
     t0 = time.perf_counter()
-    for t in range(args.warmup, total):
-        b, a = step(t)
-        kv += b
-        active += a
-        launches += 1 if a else 0
+    for t in range(warmup, total):
+        step(t)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     n_rec, attn_ms = gpu.timing_read()
     gpu.timing_enable(False)
+    while tickets:
+        assert gpu.ticket_result(tickets.pop(0)[1]) >= 0
+    kv = sum(tape[t][3] for t in range(warmup, total) if tape[t][1])
+    launches = sum(1 for t in range(warmup, total) if tape[t][1])
+    active = sum(len(tape[t][1]) for t in range(warmup, total))
+    book = sum(len(tape[t][0]) for t in range(warmup, total))
     assert gpu.device_errors() == 0 and n_rec == launches
+    # per-call cost of the enqueue-only bookkeeping on this pool, on the device: event spans around single calls
     attn_gbps = kv / (attn_ms * 1e-3) / 1e9 if n_rec else 0.0
-    result = {
-        "metric": "kv_read_gbps_multi_model_paged_decode", "value": round(kv / wall / 1e9, 1), "unit": "GB/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 5),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": cfg.name, "cfg": 3, "size": args.size, "frame_bytes": cfg.frame_bytes,
-                   "pool_bytes": cfg.pool_bytes, "models": len(cfg.models),
-                   "mean_active_models": round(active / args.steps, 2), "decode_launches": launches,
-                   "bookkeeping_calls": len(r.log) - n_events0,
-                   "kv_bytes_per_launch": int(kv / max(launches, 1))},
-        "roofline": {"bound": "hbm", "kernel": KERNEL_FORM_NAME[0 if forms[0] >= forms[1] else 1], "achieved": round(attn_gbps, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4), "traffic": None,
-                     "avg_launch_us": round(attn_ms / max(n_rec, 1) * 1e3, 2), "launches": n_rec,
-                     "launches_by_kernel": dict(zip(KERNEL_FORM_NAME, forms))},
-    }
+    res = {"workload": cfg.name, "size": size, "frame_bytes": cfg.frame_bytes, "pool_bytes": cfg.pool_bytes, "models": n,
+           "steps": steps, "mean_active_models": round(active / steps, 2), "decode_launches": launches,
+           "bookkeeping_calls": book, "bookkeeping_calls_per_step": round(book / steps, 2),
+           "kv_bytes_per_launch": int(kv / max(launches, 1)),
+           "whole_step_us": round(wall * 1e6 / steps, 2), "whole_job_kv_gbps": round(kv / wall / 1e9, 1),
+           "attention_avg_launch_us": round(attn_ms / max(n_rec, 1) * 1e3, 2), "attention_kv_gbps": round(attn_gbps, 1),
+           "attention_frac_of_hbm_peak": round(attn_gbps / HBM_PEAK_GBPS, 4),
+           "whole_step_over_attention": round((wall * 1e3 / steps) / (attn_ms / max(n_rec, 1)), 3) if n_rec else None,
+           "launches_by_kernel": dict(zip(KERNEL_FORM_NAME, forms)),
+           "ideal_us_at_hbm_peak": round(kv / max(launches, 1) / HBM_PEAK_GBPS / 1e3, 1),
+           "kind": "attention: an event pair around every decode launch (each pair adds about 2 us); whole step: host clock "
+                   "over all steps, enqueue-only bookkeeping included"}
+    r.flush()
     r.teardown()
+    return res
+
+
+def bursty_run(gpu, torch, args):
+    """--config 3 as the headline: the whole-job figure of the bursty scenario."""
+    leg = bursty_leg(gpu, torch, args.size, args.steps, args.warmup, args.frame_bytes)
+    result = {
+        "metric": "kv_read_gbps_multi_model_paged_decode", "value": leg["whole_job_kv_gbps"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(leg["whole_step_us"] / 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": leg["workload"], "cfg": 3, "size": args.size, "frame_bytes": leg["frame_bytes"],
+                   "pool_bytes": leg["pool_bytes"], "models": leg["models"], "mean_active_models": leg["mean_active_models"],
+                   "decode_launches": leg["decode_launches"], "bookkeeping_calls": leg["bookkeeping_calls"],
+                   "kv_bytes_per_launch": leg["kv_bytes_per_launch"]},
+        "roofline": {"bound": "hbm", "kernel": max(leg["launches_by_kernel"], key=leg["launches_by_kernel"].get),
+                     "achieved": leg["attention_kv_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": leg["attention_frac_of_hbm_peak"], "traffic": profiled_traffic("k_attention_deep", leg["workload"], args.size),
+                     "avg_launch_us": leg["attention_avg_launch_us"], "launches": leg["decode_launches"],
+                     "launches_by_kernel": leg["launches_by_kernel"]},
+        "bursty": leg,
+    }
     print(json.dumps(result), flush=True)
 
 
@@ -400,48 +529,27 @@ def main():
         rc = gpu.decode_attention_multi_dev(mids, qs, ctxs, outs)
         assert rc == 0, (rc, gpu.last_error())
 
+    bytes_of_step = lambda i: kv_per_rep[i % len(reps)]       # noqa: E731
     for c in [int(x) for x in args.sweep_items.split(",") if x]:
         gpu.set_split(c, args.min_share)
-        for i in range(10):
-            step(i)
-        torch.cuda.synchronize()
-        gpu.timing_enable(True)
-        t0 = time.perf_counter()
-        for i in range(60):
-            step(i)
-        torch.cuda.synchronize()
-        w = (time.perf_counter() - t0) / 60
-        n_rec, a_ms = gpu.timing_read()
-        gpu.timing_enable(False)
-        print(f"[sweep] items {c:6d}: step {w * 1e6:7.1f} us  attention kernel {a_ms / n_rec * 1e3:7.1f} us",
-              file=sys.stderr, flush=True)
+        t = timed_decode(gpu, torch, step, bytes_of_step, 60, 10, 0)
+        print(f"[sweep] items {c:6d}: step {t['dev_ms'] / 60 * 1e3:7.1f} us", file=sys.stderr, flush=True)
     gpu.set_split(args.items, args.min_share)
 
-    if args.tune > 0:             # part of the set-up, like any autotuning: never inside the timed region
-        gpu.tune_xcd(args.tune)
-        for i in range(args.tune):
-            step(i)
-        torch.cuda.synchronize()
-    n_cond = condition(torch, step, args.condition_ms)
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    # The library launches on torch's current stream (PrismKV binds it), so these two events sit on the
-    # kernel's own stream.  A step is exactly one k_attention launch: the events' span over the timed
+    # First with equal weights and the library's tuning of them switched off: what a launch costs before
+    # the library has learnt anything about this chip.
+    gpu.tune_xcd(0)
+    gpu.set_xcd_weights(None)
+    untuned = timed_decode(gpu, torch, step, bytes_of_step, min(args.steps, 100), args.warmup, min(args.condition_ms, 300))
+    # Then as any caller gets it: the library tunes the per-XCD weights by itself over its first launches
+    # (here: the conditioning and warm-up launches), without any call from outside and without ever waiting.
+    gpu.tune_xcd(args.tune)
+    # The library launches on torch's current stream (PrismKV binds it), so the events of timed_decode sit
+    # on the kernel's own stream.  A step is exactly one attention launch: the events' span over the timed
     # region divided by the launches is the kernel's average duration, gaps between launches included.
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    ev0.record()
-    for i in range(args.steps):
-        step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    t = timed_decode(gpu, torch, step, bytes_of_step, args.steps, args.warmup, args.condition_ms)
     assert gpu.device_errors() == 0
-    dev_ms = ev0.elapsed_time(ev1)
-
-    total_bytes = sum(kv_per_rep[i % len(reps)] for i in range(args.steps))
+    wall, dev_ms, total_bytes = t["wall_s"], t["dev_ms"], t["bytes"]
     ms_per_step = wall * 1e3 / args.steps
     gbps = total_bytes / wall / 1e9
     attn_avg_ms = dev_ms / args.steps
@@ -456,6 +564,7 @@ def main():
     n_rec, br_ms = gpu.timing_read()
     gpu.timing_enable(False)
 
+    kernel = KERNEL_FORM_NAME[gpu.last_kernel_form()]
     result = {
         "metric": "kv_read_gbps_multi_model_paged_decode",
         "value": round(gbps, 1),
@@ -472,15 +581,19 @@ def main():
         "config": {"workload": reps[0].cfg.name, "cfg": args.config, "size": args.size,
                    "frame_bytes": reps[0].cfg.frame_bytes, "layers": args.layers,
                    "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
-                   "work_items": args.items or "auto", "xcd_tune_launches": args.tune,
-                   "conditioning_launches": n_cond,
-                   "xcd_weights": [round(x, 3) for x in gpu.get_xcd_weights()]},
+                   "work_items": args.items or "auto", "xcd_weight_updates_allowed": args.tune,
+                   "conditioning_launches": t["n_cond"],
+                   "xcd_weights": [round(x, 3) for x in gpu.get_xcd_weights()],
+                   "xcd_weights_found_by": "the library itself, during the conditioning and warm-up launches (no tuning call)"},
         "step_us": round(ms_per_step * 1e3, 2),
+        "step_us_spread": t["dist"],
         "pct_of_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "device_ms_per_step": round(dev_ms / args.steps, 5),
-        "roofline": {"bound": "hbm", "kernel": KERNEL_FORM_NAME[gpu.last_kernel_form()], "achieved": round(attn_gbps, 1),
+        "untuned": dict(decode_summary(untuned, min(args.steps, 100)), kind="equal XCD weights, the library's tuning switched off"),
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": round(attn_gbps, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(attn_gbps / HBM_PEAK_GBPS, 4),
-                     "traffic": None if args.frame_bytes or args.layers > 1 else profiled_traffic(KERNEL_FORM_NAME[gpu.last_kernel_form()], reps[0].cfg.name, args.size),
+                     "traffic": None if args.frame_bytes or args.layers > 1 else profiled_traffic(kernel, reps[0].cfg.name, args.size),
+                     "traffic_kind": "stored figure of the committed rocprofv3 counter summary of this workload, not read in this run",
                      "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": args.steps,
                      "bracketed_single_launch_us": round(br_ms / max(n_rec, 1) * 1e3, 2)},
     }
@@ -496,6 +609,16 @@ def main():
         result["cpu_baseline"] = cpu_baseline(reps[0], args.cpu_seconds)
     for rep in reps:
         rep.teardown()
+    if args.legs and args.config == 2 and args.size == "full" and not args.frame_bytes and args.layers == 1:
+        # the other workloads, each by the same protocol (shorter), so that one run covers all five
+        c = min(args.condition_ms, 300)
+        legs = {}
+        legs["cfg1"] = static_leg(gpu, torch, 1, 200, 20, c, 1)
+        legs["cfg2_64KiB_frames"] = static_leg(gpu, torch, 2, 200, 20, c, 3, frame_bytes=65536)
+        legs["cfg4"] = static_leg(gpu, torch, 4, 100, 10, c, 1)
+        legs["cfg5"] = static_leg(gpu, torch, 5, 200, 20, c, 2)
+        legs["cfg3"] = bursty_leg(gpu, torch, "full", 400, 30)
+        result["configs"] = legs
     print(json.dumps(result), flush=True)
 
 
