@@ -27,8 +27,8 @@
  *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
  *     addresses.  Unless stated, buffers belong to the caller.
  *   - Work is enqueued on the HIP stream given to pkv_set_stream (default: the
- *     null stream).  Bookkeeping calls that return a count wait for their kernel;
- *     kv_write and the decode_attention family only enqueue.
+ *     null stream).  Bookkeeping calls that return a count wait for their kernel
+ *     (their *_enqueue forms do not); kv_write and the decode_attention family only enqueue.
  *   - All bookkeeping (free stack, ownership, frame lists, slot bitmaps, block
  *     tables) lives in device memory and is changed only by the library's kernels.
  *   - Calls are not thread-safe; one thread drives one library instance.
@@ -74,8 +74,9 @@ typedef struct pkv_stats {
 int pkv_set_stream(void *hip_stream);
 /* Text of the last HIP / library error on this thread (never NULL). */
 const char *pkv_last_error(void);
-/* Sticky device-side error flags raised by kernels that only enqueue (bit 0: a
- * block id outside the pool was met in decode_attention; that page was skipped).
+/* Sticky device-side error flags raised by calls that only enqueue (bit 0: a block id outside
+ * the pool was met in decode_attention, that page was skipped; bit 1: kv_append met a context
+ * length outside the row's blocks; bit 2: an enqueue-only bookkeeping call was refused).
  * Synchronises the stream; clears the flags. */
 int pkv_device_errors(void);
 
@@ -89,7 +90,6 @@ int pool_create(size_t bytes, int page_tokens);
 /* Same with an explicit frame size and optionally caller-owned device memory
  * (device_base, dev, at least bytes long, 256-byte aligned; NULL = allocate). */
 int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *device_base);
-/* Fails with PKV_E_BUSY while any model is registered in the pool. */
 /* A pool whose memory is elastic (paper Sec. 4.2, D1 / D3: the balloon driver hands physical
  * pages out lazily and takes them back, so that what one model gives up can serve another
  * model or its weights).  The pool is a reserved range of device addresses; a frame is backed
@@ -105,6 +105,7 @@ int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *devi
  * exceeds it, oldest first.  Returns the frames held now; synchronises the stream. */
 int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes);
 int pool_set_prealloc(int pool, long frames);
+/* Fails with PKV_E_BUSY while any model is registered in the pool. */
 int pool_destroy(int pool);
 /* Set the order in which a still-untouched pool hands out frames: perm (host,
  * n = number of frames) is a permutation of the frame ids, perm[0] first. */
@@ -151,11 +152,38 @@ long balloon_resize(int model, long pages);
  * free slots (no change); PKV_E_RANGE beyond max_blocks_per_seq. */
 int seq_reserve(int model, int seq, int ctx_len);
 /* Same effect as seq_reserve for (seqs[i], ctx_lens[i]), i = 0..n-1 in order, in
- * one kernel launch; refused as a whole when the total does not fit.
- * seqs, ctx_lens: host, n <= 2048. */
+ * one kernel launch; refused as a whole when the total does not fit.  A sequence may be
+ * listed more than once (the growth rounds of a whole admission in one call).
+ * seqs, ctx_lens: host, n <= 4096. */
 int seq_reserve_batch(int model, int n, const int32_t *seqs, const int32_t *ctx_lens);
 /* Free all blocks of the row; returns how many (0 for an empty row). */
 int seq_release(int model, int seq);
+/* Same effect as seq_release for seqs[0..n-1] in order, in one kernel launch; returns the
+ * blocks freed in total.  seqs: host, n <= 4096. */
+int seq_release_batch(int model, int n, const int32_t *seqs);
+
+/* ---- the same bookkeeping, enqueue-only ------------------------------------------------------
+ * A serving loop issues the bookkeeping of a step (the deflates of models that fell idle, the
+ * inflate and the reservations of an admission: Sec. 3.1 bursty groups, Sec. 4.2 D1 / D2) and
+ * goes on to enqueue the step's attention without waiting for any of it.  These forms launch the
+ * same kernels as balloon_resize, seq_reserve_batch and seq_release_batch, in stream order, and
+ * return at once with a ticket (>= 0) instead of the result; argument errors that need no device
+ * state still come back at once as a negative code (unknown model, bad n, NULL list).
+ *   - pkv_ticket_result(ticket) waits for that call if need be and returns what the synchronous
+ *     form would have returned.  The library remembers the last 128 tickets (PKV_E_RANGE for an
+ *     older one).
+ *   - A refused call (PKV_E_NOMEM, PKV_E_BALLOON, PKV_E_ARG, PKV_E_RANGE) changes nothing, as in
+ *     the synchronous form, and raises bit 2 of pkv_device_errors(), so a caller need not read
+ *     every ticket.  Later calls run against the unchanged state: a reserve after a refused
+ *     inflate is refused too, and attention over rows that never got their blocks reads nothing
+ *     (the kernels bound every row by the blocks it really holds).
+ *   - All bookkeeping calls of a pool must go to one stream, or be ordered by the caller.
+ *   - On an elastic pool balloon_resize_enqueue does its work at once (mapping frames is host
+ *     work) and returns a ticket that is already complete. */
+int balloon_resize_enqueue(int model, long pages);
+int seq_reserve_batch_enqueue(int model, int n, const int32_t *seqs, const int32_t *ctx_lens);
+int seq_release_batch_enqueue(int model, int n, const int32_t *seqs);
+long pkv_ticket_result(int ticket);
 
 /* Device pointer to the model's block table, int32 [max_seqs][*row_stride],
  * owned by the library, valid until model_unregister. */
@@ -214,7 +242,8 @@ int model_set_batch(int model, int batch, int row_stride);
  * over t < ctx_lens[s], g = q_heads / kv_heads, K/V read through the block table.
  *   q           dev, bf16 [batch][q_heads][head_dim]
  *   block_table dev, int32 [batch][row_stride] block ids; NULL = the library's own
- *               table, rows 0..batch-1
+ *               table, rows 0..batch-1.  A caller's table is refused on an elastic pool
+ *               (PKV_E_UNSUPPORTED): its ids could name frames that nothing backs.
  *   ctx_lens    dev, int32 [batch]; 0 gives a zero output row
  *   out         dev, fp32 [batch][q_heads][head_dim]
  * fp32 accumulation.  Enqueues only. */
@@ -337,17 +366,20 @@ int pkv_last_kernel_form(void);
 int pkv_set_page_cost(int per_mille);
 /* The eight XCDs of the chip do not get the same memory bandwidth, and work-groups are
  * dealt to them in turn; so each block of eight consecutive attention work items is
- * cut in proportion to eight weights rather than evenly.  pkv_set_xcd_weights sets
- * them (w: 8 positive floats, host memory, copied; NULL = all equal; they are scaled to
- * mean 1 and clamped to [0.75, 1.25]); pkv_get_xcd_weights copies the current ones to
- * w[8].  pkv_tune_xcd(n) makes the next n attention launches measure when each XCD's
- * waves finish and move the weights toward equal finishing times; those launches
- * compute their results as usual but wait for the stream before they return.  Weights
- * change where the split-K boundaries fall, hence the rounding of the results (by
- * about 1e-6 relative), not what is computed.  PKV_E_ARG on a bad argument. */
+ * cut in proportion to eight weights rather than evenly.  The library finds the weights
+ * by itself: the first launches of a process that fill the chip (512 work items or more)
+ * also record how long each XCD's waves streamed, the sums travel to the host behind the
+ * launch, and a later launch that finds them there moves the weights toward equal times
+ * (24 updates, the first 8 coarse; nothing ever waits, and launches under stream capture
+ * are left alone).  pkv_tune_xcd(n) restarts that for n more updates (0 = stop: the
+ * weights stay as they are).  pkv_set_xcd_weights sets them by hand and stops the tuning
+ * (w: 8 positive floats, host memory, copied; NULL = all equal; they are scaled to mean 1
+ * and clamped to [0.75, 1.25]); pkv_get_xcd_weights copies the current ones to w[8].  Weights change where
+ * the split-K boundaries fall, hence the rounding of the results (by about 1e-6
+ * relative), not what is computed.  PKV_E_ARG on a bad argument. */
 int pkv_set_xcd_weights(const float *w);
 int pkv_get_xcd_weights(float *w);
-int pkv_tune_xcd(int launches);
+int pkv_tune_xcd(int updates);
 /* Host-side check of the multiply-shift division the kernels use to split a block
  * id into (frame, slot): returns n / d computed that way. */
 uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d);

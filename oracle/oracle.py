@@ -137,6 +137,43 @@ class Oracle:
     def seq_release(self, model, seq):
         return self.lib.orc_seq_release(model, seq)
 
+    def seq_release_batch(self, model, seqs):
+        """The batched release is defined as the single releases in order (paper Sec. 4.2, D2: blocks go
+        back to the slots of the model's pages); a list with an invalid sequence is refused as a whole."""
+        seqs = [int(x) for x in np.asarray(seqs).ravel()]
+        for sq in seqs:
+            if self.lib.orc_model_row_len(model, sq) < 0:
+                return self.lib.orc_model_row_len(model, sq)
+        total = 0
+        for sq in seqs:
+            total += self.lib.orc_seq_release(model, sq)
+        return total
+
+    # The product has enqueue-only forms of the bookkeeping calls (the result is fetched later through a
+    # ticket).  The oracle knows no streams: it runs the call at once and keeps the result for the ticket.
+    def _ticket(self, value):
+        if not hasattr(self, "_tickets"):
+            self._tickets = []
+        self._tickets.append(int(value))
+        return len(self._tickets) - 1
+
+    def balloon_resize_enqueue(self, model, frames):
+        return self._ticket(self.balloon_resize(model, frames))
+
+    def seq_reserve_batch_enqueue(self, model, seqs, ctx_lens):
+        return self._ticket(self.seq_reserve_batch(model, seqs, ctx_lens))
+
+    def seq_release_batch_enqueue(self, model, seqs):
+        return self._ticket(self.seq_release_batch(model, seqs))
+
+    def ticket_result(self, ticket):
+        return self._tickets[ticket]
+
+    # ---- host policies: the plain definitions of oracle/policy_oracle.py under the product's call names
+    def arbitrate_requests(self, arrival, ttft_slo, prompt_len, prefill_speed, now):
+        from . import policy_oracle
+        return policy_oracle.arbitrate(list(arrival), list(ttft_slo), list(prompt_len), list(prefill_speed), now)
+
     # ---- data
     def kv_write(self, model, seq, tok_begin, k, v, k_scale=None, v_scale=None):
         _, hkv, d, dtype = self._shape[model]

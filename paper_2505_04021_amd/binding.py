@@ -58,6 +58,11 @@ def _load():
         "seq_reserve": (i, [i, i, i]),
         "seq_reserve_batch": (i, [i, i, vp, vp]),
         "seq_release": (i, [i, i]),
+        "seq_release_batch": (i, [i, i, vp]),
+        "balloon_resize_enqueue": (i, [i, l]),
+        "seq_reserve_batch_enqueue": (i, [i, i, vp, vp]),
+        "seq_release_batch_enqueue": (i, [i, i, vp]),
+        "pkv_ticket_result": (l, [i]),
         "model_block_table": (vp, [i, C.POINTER(i)]),
         "kv_write": (i, [i, i, i, i, vp, vp, vp, vp]),
         "kv_append": (i, [i, i, vp, vp, vp]),
@@ -88,7 +93,8 @@ EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_spl
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_register_layers", "pkv_set_layer", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
-           "seq_release", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
+           "seq_release", "seq_release_batch", "balloon_resize_enqueue", "seq_reserve_batch_enqueue", "seq_release_batch_enqueue",
+           "pkv_ticket_result", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
            "decode_attention_ex", "decode_attention_static", "decode_attention_multi", "prefill_attention", "pool_export_state", "pool_stats",
            "arbitrate_requests", "place_models"]
 
@@ -138,6 +144,13 @@ class PrismKV:
         self._shape = {}
         self._keep = {}
         self.use_current_stream()
+
+    # ---- host policies (no GPU work)
+    def arbitrate_requests(self, arrival, ttft_slo, prompt_len, prefill_speed, now):
+        return arbitrate_requests(arrival, ttft_slo, prompt_len, prefill_speed, now, lib=self.lib)
+
+    def place_models(self, *args, **kw):
+        return place_models(*args, lib=self.lib, **kw)
 
     # ---- plumbing
     def use_current_stream(self):
@@ -271,6 +284,28 @@ class PrismKV:
 
     def seq_release(self, model, seq):
         return self.lib.seq_release(model, seq)
+
+    def seq_release_batch(self, model, seqs):
+        seqs = np.ascontiguousarray(seqs, dtype=np.int32)
+        return self.lib.seq_release_batch(model, seqs.size, seqs.ctypes.data_as(C.c_void_p))
+
+    # ---- the same bookkeeping, enqueue-only: each returns a ticket (or a negative code at once)
+    def balloon_resize_enqueue(self, model, frames):
+        return self.lib.balloon_resize_enqueue(model, frames)
+
+    def seq_reserve_batch_enqueue(self, model, seqs, ctx_lens):
+        seqs = np.ascontiguousarray(seqs, dtype=np.int32)
+        ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        assert seqs.size == ctx_lens.size
+        return self.lib.seq_reserve_batch_enqueue(model, seqs.size, seqs.ctypes.data_as(C.c_void_p),
+                                                  ctx_lens.ctypes.data_as(C.c_void_p))
+
+    def seq_release_batch_enqueue(self, model, seqs):
+        seqs = np.ascontiguousarray(seqs, dtype=np.int32)
+        return self.lib.seq_release_batch_enqueue(model, seqs.size, seqs.ctypes.data_as(C.c_void_p))
+
+    def ticket_result(self, ticket):
+        return self.lib.pkv_ticket_result(ticket)
 
     def model_block_table(self, model):
         """(device pointer, row stride) of the library-owned block table."""

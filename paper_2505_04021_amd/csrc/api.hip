@@ -13,6 +13,8 @@
 
 #include "pkv_internal.h"
 
+static int tune_setup();      // buffers of the XCD weight tuning (defined with the tuning code)
+
 namespace {
 
 struct Pool {
@@ -49,6 +51,10 @@ struct Model {
     int64_t owned = 0;                      // shadow of the device counter
     int64_t used_blocks = 0;
     std::vector<int32_t> row_len;           // shadow
+    // The shadows follow the calls as if each had succeeded in full.  After an enqueue-only bookkeeping
+    // call nobody has looked at the outcome yet: the shadows are then estimates (good for sizing a
+    // launch) until reconcile() has read the device's own counts back.
+    bool stale = false;
     ModelDev dev{};
     float *ws = nullptr;                    // split-K partials
     size_t ws_floats = 0;
@@ -92,9 +98,22 @@ Pool g_pools[PKV_MAX_POOLS];
 Model g_models[PKV_MAX_MODELS];
 int g_last_pool = -1;
 hipStream_t g_stream = nullptr;
-BookResult *g_res = nullptr;       // pinned host
-int32_t *g_ops = nullptr;          // pinned host, 2 * PKV_MAX_BATCH_OPS
+// Bookkeeping calls run as kernels whose result lands in a slot of pinned host memory.  A call takes
+// the next slot of a ring (its ticket); the synchronous forms wait for their slot, the enqueue-only
+// forms hand the ticket to the caller.  A slot also carries the call's host-side operands (the list
+// of a reserve / release batch), which its kernel reads straight from pinned memory.
+constexpr int kTickets = 128;
+constexpr int64_t kPending = INT64_MIN;
+struct Ticket {
+    long id = -1;
+    hipStream_t stream = nullptr;
+};
+BookResult *g_res = nullptr;       // pinned host, [kTickets]
+int32_t *g_ops = nullptr;          // pinned host, [kTickets][2 * PKV_MAX_BATCH_OPS]
+Ticket g_tickets[kTickets];
+long g_next_ticket = 0;
 uint32_t *g_err = nullptr;         // device error flags
+uint32_t g_host_flags = 0;         // the same flags, raised by the host (an enqueue-only call refused before any kernel ran)
 void *g_safe = nullptr;            // 16 KiB of zeros: what kernels read instead of a block they must not touch
 uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
 int g_items = 0, g_min_share = 0, g_seg_cost = -1;
@@ -103,8 +122,23 @@ bool g_deep_now = false;             // the form chosen for the launch being pre
 // How a block of eight shares is cut among the XCDs: weights (mean 1), and the state of a
 // tuning run that derives them from when each XCD's waves finish.
 float g_xcd_w[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
-uint64_t *g_xcd_stat = nullptr;       // device: [8][2]
-int g_tune_left = 0, g_tune_done = 0;
+// The library tunes the weights itself, without ever waiting: while updates are still owed, a launch
+// that fills the chip lets its waves add their streaming times to per-XCD sums on the device (running
+// totals, never cleared); a copy of the totals travels to pinned host memory behind the launch, and a
+// later launch that finds such a copy complete turns the difference to the previous copy into the
+// next step of the weights.
+constexpr int kAutoTuneUpdates = 24;        // weight updates a process starts with (coarse ones first)
+constexpr int kTuneSlots = 4;
+constexpr int kMinTuneItems = 512;          // smaller launches do not fill the chip: their times say little
+uint64_t *g_xcd_stat = nullptr;             // device: [8][2] running sums of streaming time and wave counts
+uint64_t *g_tune_host = nullptr;            // pinned: [kTuneSlots][16] copies of the totals
+hipEvent_t g_tune_ev[kTuneSlots];
+bool g_tune_busy[kTuneSlots];
+long g_tune_version[kTuneSlots];            // which set of weights the launch behind the copy ran with
+uint64_t g_tune_last[16];                   // the totals of the last copy looked at
+long g_xcd_version = 0;                     // counts changes of the weights
+int g_tune_left = kAutoTuneUpdates, g_tune_done = 0, g_tune_measured = 0;
+constexpr int kMaxTuneMeasured = 4096;      // give up measuring if the updates never come (launches too alike in time)
 constexpr float kXcdWeightMin = 0.75f, kXcdWeightMax = 1.25f;
 double g_page_cost = -1.0;           // fixed cost of a page relative to 0.1 per KiB (< 0: the default of the kernel form)
 int g_fail_map_after = -1;        // test hook: the (n+1)-th frame mapping from now fails as if memory had run out
@@ -127,30 +161,58 @@ int fail_hip(hipError_t e, const char *what) {
 
 int lib_init() {
     if (g_res) return PKV_OK;
-    HIP_TRY(hipHostMalloc((void **)&g_res, sizeof(BookResult), hipHostMallocDefault));
-    HIP_TRY(hipHostMalloc((void **)&g_ops, sizeof(int32_t) * 2 * PKV_MAX_BATCH_OPS, hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc((void **)&g_res, sizeof(BookResult) * kTickets, hipHostMallocDefault));
+    for (int i = 0; i < kTickets; ++i) g_res[i].value = 0;
+    HIP_TRY(hipHostMalloc((void **)&g_ops, sizeof(int32_t) * 2 * PKV_MAX_BATCH_OPS * kTickets, hipHostMallocDefault));
     HIP_TRY(hipMalloc((void **)&g_err, sizeof(uint32_t)));
     HIP_TRY(hipMemset(g_err, 0, sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&g_safe, 16384));
     HIP_TRY(hipMemset(g_safe, 0, 16384));
     void *scratch_ptr = nullptr;          // resolve the current device's scratch array once, at set-up
     HIP_TRY(pkv_static_scratch(&scratch_ptr));
-    return PKV_OK;
+    return tune_setup();
 }
 
 Pool *get_pool(int id) { return (id >= 0 && id < PKV_MAX_POOLS && g_pools[id].live) ? &g_pools[id] : nullptr; }
 Model *get_model(int id) { return (id >= 0 && id < PKV_MAX_MODELS && g_models[id].live) ? &g_models[id] : nullptr; }
 
-// run one bookkeeping kernel and wait for its result
-template <class F>
-int64_t book_call(F launch) {
-    g_res->value = PKV_E_INTERNAL;
-    g_res->aux0 = g_res->aux1 = 0;
-    hipError_t e = launch();
-    if (e != hipSuccess) return fail_hip(e, "bookkeeping launch");
-    e = hipStreamSynchronize(g_stream);
-    if (e != hipSuccess) return fail_hip(e, "bookkeeping sync");
-    return g_res->value;
+// The next slot of the ring.  A slot whose previous call has not finished yet (its kernel still
+// reads the slot's operands) is waited for first.
+int take_ticket() {
+    const long id = g_next_ticket++;
+    const int slot = (int)(id % kTickets);
+    if (g_tickets[slot].id >= 0 && g_res[slot].value == kPending) (void)hipStreamSynchronize(g_tickets[slot].stream);
+    g_tickets[slot].id = id;
+    g_tickets[slot].stream = g_stream;
+    g_res[slot].value = kPending;
+    g_res[slot].aux0 = g_res[slot].aux1 = 0;
+    return slot;
+}
+
+int32_t *ticket_ops(int slot) { return g_ops + (size_t)slot * 2 * PKV_MAX_BATCH_OPS; }
+int ticket_handle(int slot) { return (int)(g_tickets[slot].id & 0x7fffffff); }
+
+// a call that was refused before anything was enqueued still gets a (finished) ticket
+int finished_ticket(int64_t value) {
+    const int slot = take_ticket();
+    g_res[slot].value = value;
+    return slot;
+}
+
+// Wait for a slot's kernel and return its result.  The kernel writes the slot when it ends, so the
+// host watches the slot rather than the stream: work enqueued behind the call (a decode step) is
+// not waited for.  The stream is asked now and then, so that a failed launch cannot hang the caller.
+int64_t wait_ticket(int slot) {
+    volatile int64_t *v = &g_res[slot].value;
+    for (long spin = 0; *v == kPending; ++spin) {
+        if ((spin & 1023) != 1023) continue;
+        const hipError_t e = hipStreamQuery(g_tickets[slot].stream);
+        if (e == hipErrorNotReady) continue;
+        if (e != hipSuccess) return fail_hip(e, "bookkeeping call");
+        break;                                        // the stream is idle: the kernel has ended
+    }
+    const int64_t r = *v;
+    return r == kPending ? (int64_t)PKV_E_INTERNAL : r;
 }
 
 void free_model_dev(Model &m) {
@@ -344,6 +406,8 @@ int pkv_set_stream(void *hip_stream) {
 
 const char *pkv_last_error(void) { return g_errbuf; }
 
+static int reconcile_pool(int pool_id);
+
 int pkv_device_errors(void) {
     int rc = lib_init();
     if (rc) return rc;
@@ -351,6 +415,11 @@ int pkv_device_errors(void) {
     HIP_TRY(hipStreamSynchronize(g_stream));
     HIP_TRY(hipMemcpy(&v, g_err, sizeof v, hipMemcpyDeviceToHost));
     if (v) HIP_TRY(hipMemset(g_err, 0, sizeof v));
+    v |= g_host_flags;
+    g_host_flags = 0;
+    if (v & 4u)                     // an enqueued bookkeeping call was refused: the host's estimates are off
+        for (int p = 0; p < PKV_MAX_POOLS; ++p)
+            if (g_pools[p].live && (rc = reconcile_pool(p)) != PKV_OK) return rc;
     return (int)v;
 }
 
@@ -379,36 +448,71 @@ static void fill_tune(AttnTune &t, bool record) {
     t.stat = record ? g_xcd_stat : nullptr;
 }
 
-// One attention launch; during a tuning run it also records when each XCD's waves finish
-// and moves the weights toward equal finishing times (synchronises in that case).
-static int launch_attention(AttnGroup &grp) {
-    const bool tune = g_tune_left > 0;
-    if (tune) {
-        if (!g_xcd_stat) HIP_TRY(hipMalloc((void **)&g_xcd_stat, 16 * sizeof(uint64_t)));
-        HIP_TRY(hipMemsetAsync(g_xcd_stat, 0, 16 * sizeof(uint64_t), g_stream));
+// one step of the weights from the per-XCD sums of a measured launch (or of several)
+static void tune_apply(const uint64_t *tot, bool same_weights) {
+    uint64_t d[16];
+    for (int i = 0; i < 16; ++i) d[i] = tot[i] - g_tune_last[i];
+    for (int i = 0; i < 16; ++i) g_tune_last[i] = tot[i];
+    if (!same_weights || g_tune_left <= 0) return;      // measured with weights that have changed since
+    double t[8], mean = 0.0;
+    for (int i = 0; i < 8; ++i) {
+        if (d[2 * i + 1] < 8) return;                    // too few waves on this XCD to judge
+        t[i] = (double)d[2 * i] / (double)d[2 * i + 1];
+        mean += t[i] / 8.0;
     }
-    fill_tune(grp.tune, tune);
+    if (!(mean > 0.0)) return;
+    // a wave's time is its share over its XCD's rate: move each weight part of the way to where the
+    // times would be equal, and let the next launches correct the rest
+    const double gain = g_tune_done < 8 ? 0.5 : 0.2;      // coarse first, then averaging out the noise
+    for (int i = 0; i < 8; ++i) g_xcd_w[i] = (float)(g_xcd_w[i] * pow(mean / t[i], gain));
+    normalise_xcd_weights(g_xcd_w);
+    ++g_tune_done;
+    --g_tune_left;
+    ++g_xcd_version;
+}
+
+static int tune_setup() {
+    if (g_xcd_stat) return PKV_OK;
+    HIP_TRY(hipMalloc((void **)&g_xcd_stat, 16 * sizeof(uint64_t)));
+    HIP_TRY(hipMemset(g_xcd_stat, 0, 16 * sizeof(uint64_t)));
+    HIP_TRY(hipHostMalloc((void **)&g_tune_host, kTuneSlots * 16 * sizeof(uint64_t), hipHostMallocDefault));
+    for (int i = 0; i < kTuneSlots; ++i) {
+        HIP_TRY(hipEventCreateWithFlags(&g_tune_ev[i], hipEventDisableTiming));
+        g_tune_busy[i] = false;
+    }
+    return PKV_OK;
+}
+
+// One attention launch.  While weight updates are owed, a launch that fills the chip is also measured.
+static int launch_attention(AttnGroup &grp) {
+    // copies of the totals that have arrived meanwhile (never waits)
+    for (int i = 0; i < kTuneSlots && g_xcd_stat; ++i)
+        if (g_tune_busy[i] && hipEventQuery(g_tune_ev[i]) == hipSuccess) {
+            g_tune_busy[i] = false;
+            tune_apply(g_tune_host + 16 * i, g_tune_version[i] == g_xcd_version);
+        }
+    bool measure = g_tune_left > 0 && g_tune_measured < kMaxTuneMeasured && g_xcd_stat != nullptr;
+    int items = 0, slot = -1;
+    for (int i = 0; i < grp.n; ++i) {
+        items += grp.m[i].n_items;
+        measure = measure && grp.m[i].weighted;
+    }
+    measure = measure && items >= kMinTuneItems;
+    if (measure) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(g_stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) measure = false;
+        for (int i = 0; i < kTuneSlots && slot < 0; ++i)
+            if (!g_tune_busy[i]) slot = i;
+        if (slot < 0) measure = false;                     // all copies still travelling
+    }
+    fill_tune(grp.tune, measure);
     HIP_TRY(pkv_launch_attention(grp, g_deep_now, g_stream, next_events()));
-    if (tune) {
-        uint64_t st[16];
-        HIP_TRY(hipStreamSynchronize(g_stream));
-        HIP_TRY(hipMemcpy(st, g_xcd_stat, sizeof st, hipMemcpyDeviceToHost));
-        --g_tune_left;
-        double t[8], mean = 0.0;
-        bool ok = true;
-        for (int i = 0; i < 8; ++i) {
-            if (st[2 * i + 1] < 8) { ok = false; break; }      // too few waves on this XCD to judge
-            t[i] = (double)st[2 * i] / (double)st[2 * i + 1];
-            mean += t[i] / 8.0;
-        }
-        if (ok && mean > 0.0) {
-            // a wave's time is its share over its XCD's rate: move each weight part of the way
-            // to where the times would be equal, and let the next launches correct the rest
-            const double gain = g_tune_done < 8 ? 0.5 : 0.2;      // coarse first, then averaging out the noise
-            for (int i = 0; i < 8; ++i) g_xcd_w[i] = (float)(g_xcd_w[i] * pow(mean / t[i], gain));
-            ++g_tune_done;
-            normalise_xcd_weights(g_xcd_w);
-        }
+    if (measure) {
+        HIP_TRY(hipMemcpyAsync(g_tune_host + 16 * slot, g_xcd_stat, 16 * sizeof(uint64_t), hipMemcpyDeviceToHost, g_stream));
+        HIP_TRY(hipEventRecord(g_tune_ev[slot], g_stream));
+        g_tune_busy[slot] = true;
+        g_tune_version[slot] = g_xcd_version;
+        ++g_tune_measured;
     }
     return PKV_OK;
 }
@@ -421,6 +525,8 @@ int pkv_set_xcd_weights(const float *w) {
     }
     normalise_xcd_weights(v);
     for (int i = 0; i < 8; ++i) g_xcd_w[i] = v[i];
+    ++g_xcd_version;
+    g_tune_left = 0;              // weights set by hand stay until pkv_tune_xcd asks for tuning again
     return PKV_OK;
 }
 
@@ -430,12 +536,13 @@ int pkv_get_xcd_weights(float *w) {
     return PKV_OK;
 }
 
-int pkv_tune_xcd(int launches) {
-    if (launches < 0 || launches > 100000) return PKV_E_ARG;
+int pkv_tune_xcd(int updates) {
+    if (updates < 0 || updates > 100000) return PKV_E_ARG;
     int rc = lib_init();
     if (rc) return rc;
-    g_tune_left = launches;
+    g_tune_left = updates;
     g_tune_done = 0;
+    g_tune_measured = 0;
     return PKV_OK;
 }
 
@@ -733,6 +840,8 @@ int pool_seed_free_order(int pool, const uint32_t *perm, size_t n) {
     Pool *p = get_pool(pool);
     if (!p) return PKV_E_HANDLE;
     if (!perm || (int64_t)n != p->n_frames) return PKV_E_ARG;
+    int rcs = reconcile_pool(pool);
+    if (rcs) return rcs;
     for (int m = 0; m < PKV_MAX_MODELS; ++m)      // only while every frame is still free
         if (g_models[m].live && g_models[m].pool == pool && g_models[m].owned != 0) return PKV_E_ARG;
     std::vector<uint8_t> seen(n, 0);
@@ -773,7 +882,7 @@ int model_register_layers(int pool, int q_heads, int kv_heads, int head_dim, int
         n_layers <= 0)
         return PKV_E_ARG;
     if (dtype != PKV_BF16 && dtype != PKV_E4M3) return PKV_E_ARG;
-    if (max_seqs > PKV_MAX_SEQS) return PKV_E_ARG;
+    if (max_seqs > PKV_MAX_SEQS || max_blocks_per_seq > PKV_MAX_ROW_BLOCKS) return PKV_E_ARG;
     if (q_heads % kv_heads != 0) return PKV_E_SHAPE;
     const size_t e = dtype == PKV_BF16 ? 2 : 1;
     size_t block_bytes = (size_t)2 * p->T * kv_heads * head_dim * e;
@@ -845,6 +954,8 @@ int model_register(int q_heads, int kv_heads, int head_dim, int dtype) {
 int model_unregister(int model) {
     Model *m = get_model(model);
     if (!m) return PKV_E_HANDLE;
+    int rcs = reconcile_pool(m->pool);
+    if (rcs) return rcs;
     if (m->owned != 0) return PKV_E_BUSY;
     HIP_TRY(hipStreamSynchronize(g_stream));
     free_model_dev(*m);
@@ -854,54 +965,162 @@ int model_unregister(int model) {
 
 /* --------------------------------------------------------------- balloon */
 
+// Bring the host's shadows of a pool and its models back in line with the device: waits for every
+// bookkeeping call still in flight, then reads the counts the kernels keep.
+static int reconcile_pool(int pool_id) {
+    Pool &p = g_pools[pool_id];
+    bool any = false;
+    for (int id = 0; id < PKV_MAX_MODELS; ++id) any |= g_models[id].live && g_models[id].pool == pool_id && g_models[id].stale;
+    if (!any) return PKV_OK;
+    for (int i = 0; i < kTickets; ++i)
+        if (g_tickets[i].id >= 0 && g_res[i].value == kPending) HIP_TRY(hipStreamSynchronize(g_tickets[i].stream));
+    HIP_TRY(hipMemcpy(&p.n_free, p.dev.n_free, sizeof(int64_t), hipMemcpyDeviceToHost));
+    for (int id = 0; id < PKV_MAX_MODELS; ++id) {
+        Model &m = g_models[id];
+        if (!m.live || m.pool != pool_id || !m.stale) continue;
+        int64_t cnt[2];
+        HIP_TRY(hipMemcpy(cnt, m.dev.counters, sizeof cnt, hipMemcpyDeviceToHost));
+        HIP_TRY(hipMemcpy(m.row_len.data(), m.dev.row_len, sizeof(int32_t) * m.row_len.size(), hipMemcpyDeviceToHost));
+        m.owned = cnt[0];
+        m.used_blocks = cnt[0] * m.slots - cnt[1];
+        m.stale = false;
+    }
+    return PKV_OK;
+}
+
+// balloon_resize on an ordinary pool: one kernel that decides the direction itself.
+// sticky: a refusal also raises bit 2 of the device flags (the enqueue-only forms; the caller of a
+// synchronous form gets the code itself)
+static int enqueue_resize(Model &m, long pages, bool sticky = false) {
+    Pool &p = g_pools[m.pool];
+    const int slot = take_ticket();
+    hipError_t e = pkv_launch_resize(p.dev, m.dev, pages, &g_res[slot], sticky ? g_err : nullptr, g_stream);
+    if (e != hipSuccess) {
+        g_res[slot].value = fail_hip(e, "balloon_resize launch");
+        return slot;
+    }
+    return slot;
+}
+
 long balloon_resize(int model, long pages) {
     Model *m = get_model(model);
     if (!m) return PKV_E_HANDLE;
     if (pages < 0) return PKV_E_ARG;
     Pool &p = g_pools[m->pool];
     if (pages > p.n_frames) return PKV_E_NOMEM;
-    int64_t r;
-    const int64_t before = m->owned;
-    if (pages > m->owned) {
-        r = book_call([&] { return pkv_launch_inflate(p.dev, m->dev, pages, g_res, g_stream); });
-        if (r >= 0 && p.elastic && r > before) {
-            // the kernel chose the frames (top of the free stack); back them with memory before anyone
-            // can place a block there: they are the new tail of the model's frame list
-            std::vector<uint32_t> got((size_t)(r - before));
-            HIP_TRY(hipMemcpy(got.data(), m->dev.frames + before, got.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
-            for (size_t i = 0; i < got.size(); ++i) {
-                const int rc = elastic_map(p, got[i]);
-                if (rc == PKV_OK) continue;
-                // No memory for this frame: undo the whole inflate, or kernels could be pointed at an
-                // address nothing backs.  The frames just taken are the model's newest and hold no
-                // block, so a deflate to the old size hands back exactly them, in the order that
-                // restores the free stack; those already backed go the way of any frame given back.
-                const int64_t back = book_call([&] { return pkv_launch_deflate(p.dev, m->dev, before, g_res, g_stream); });
-                for (size_t j = 0; j < i; ++j) (void)elastic_give_back(p, got[j]);
-                return back == before ? rc : PKV_E_INTERNAL;
-            }
+    if (!p.elastic) {
+        const int64_t r = wait_ticket(enqueue_resize(*m, pages));
+        if (r >= 0) {
+            p.n_free -= r - m->owned;
+            m->owned = r;
         }
-        if (r >= 0) p.n_free -= r - before;
-    } else if (pages < m->owned) {
-        r = book_call([&] { return pkv_launch_deflate(p.dev, m->dev, pages, g_res, g_stream); });
-        if (r >= 0 && p.elastic && r < before) {
-            // the frames given back are the new top of the free stack; nothing refers to them any more
-            // (they held no block) and the stream is idle (the call above waited for its result)
-            std::vector<uint32_t> gone((size_t)(before - r));
-            HIP_TRY(hipMemcpy(gone.data(), p.dev.free_stack + p.n_free, gone.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
-            // top of the stack first: those are the frames the next inflate takes, so they are the
-            // ones worth leaving mapped while the buffer has room
-            for (auto it = gone.rbegin(); it != gone.rend(); ++it) {
-                const int rc = elastic_give_back(p, *it);
-                if (rc) return rc;
-            }
-        }
-        if (r >= 0) p.n_free += before - r;
-    } else {
-        return (long)m->owned;
+        return (long)r;
     }
-    if (r >= 0) m->owned = r;
+    // elastic pool: the frames that change hands are mapped / given back by the host, which therefore
+    // needs to know exactly what the model owned before
+    int rc = reconcile_pool(m->pool);
+    if (rc) return rc;
+    const int64_t before = m->owned;
+    if (pages == before) return (long)before;
+    const int64_t r = wait_ticket(enqueue_resize(*m, pages));
+    if (r < 0) return (long)r;
+    // the bookkeeping has changed: bring the shadows along before any mapping work, so that a failure
+    // below cannot leave them behind the device's state
+    const int64_t n_free_before = p.n_free;
+    p.n_free -= r - before;
+    m->owned = r;
+    if (r > before) {
+        // the kernel chose the frames (top of the free stack); back them with memory before anyone
+        // can place a block there: they are the new tail of the model's frame list
+        std::vector<uint32_t> got((size_t)(r - before));
+        hipError_t e = hipMemcpy(got.data(), m->dev.frames + before, got.size() * sizeof(uint32_t), hipMemcpyDeviceToHost);
+        int fail = e == hipSuccess ? PKV_OK : fail_hip(e, "balloon_resize: reading the acquired frames");
+        size_t backed = 0;
+        for (; fail == PKV_OK && backed < got.size(); ++backed) {
+            fail = elastic_map(p, got[backed]);
+            if (fail) break;
+        }
+        if (fail == PKV_OK) return (long)r;
+        // No memory for a frame (or the list could not be read): undo the whole inflate, or kernels
+        // could be pointed at an address nothing backs.  The frames just taken are the model's newest
+        // and hold no block, so a deflate to the old size hands back exactly them, in the order that
+        // restores the free stack; those already backed go the way of any frame given back.
+        const int64_t back = wait_ticket(enqueue_resize(*m, before));
+        if (back >= 0) {
+            p.n_free -= back - m->owned;
+            m->owned = back;
+        }
+        for (size_t j = 0; j < backed; ++j) (void)elastic_give_back(p, got[j]);
+        return back == before ? fail : PKV_E_INTERNAL;
+    }
+    if (r < before) {
+        // the frames given back are the new top of the free stack; nothing refers to them any more
+        // (they held no block) and the stream is idle (the call above waited for its result)
+        std::vector<uint32_t> gone((size_t)(before - r));
+        HIP_TRY(hipMemcpy(gone.data(), p.dev.free_stack + n_free_before, gone.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
+        // top of the stack first: those are the frames the next inflate takes, so they are the
+        // ones worth leaving mapped while the buffer has room
+        for (auto it = gone.rbegin(); it != gone.rend(); ++it) {
+            const int rc2 = elastic_give_back(p, *it);
+            if (rc2) return rc2;
+        }
+    }
     return (long)r;
+}
+
+int balloon_resize_enqueue(int model, long pages) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (pages < 0) return PKV_E_ARG;
+    Pool &p = g_pools[m->pool];
+    if (p.elastic) {
+        // mapping and unmapping frames is host work that needs the kernel's choice: done at once
+        return ticket_handle(finished_ticket(balloon_resize(model, pages)));
+    }
+    if (pages > p.n_frames) {
+        g_host_flags |= 4u;
+        return ticket_handle(finished_ticket(PKV_E_NOMEM));
+    }
+    const int slot = enqueue_resize(*m, pages, true);
+    // estimate: the call succeeds in full
+    p.n_free -= pages - m->owned;
+    m->owned = pages;
+    m->stale = true;
+    return ticket_handle(slot);
+}
+
+// checks of a reserve list that need no device state, in the order of the sequential definition
+static int check_reserve_list(const Model &m, int T, int n, const int32_t *seqs, const int32_t *ctx_lens) {
+    for (int i = 0; i < n; ++i) {
+        if (seqs[i] < 0 || seqs[i] >= m.dev.max_seqs || ctx_lens[i] < 0) return PKV_E_ARG;
+        if (((int64_t)ctx_lens[i] + T - 1) / T > m.dev.max_blocks) return PKV_E_RANGE;
+    }
+    return PKV_OK;
+}
+
+static int enqueue_reserve(Model &m, int n, const int32_t *seqs, const int32_t *ctx_lens, bool sticky = false) {
+    Pool &p = g_pools[m.pool];
+    const int slot = take_ticket();
+    int32_t *ops = ticket_ops(slot);
+    memcpy(ops, seqs, sizeof(int32_t) * n);
+    memcpy(ops + n, ctx_lens, sizeof(int32_t) * n);
+    hipError_t e = pkv_launch_reserve(p.dev, m.dev, n, ops, &g_res[slot], sticky ? g_err : nullptr, g_stream);
+    if (e != hipSuccess) g_res[slot].value = fail_hip(e, "seq_reserve_batch launch");
+    return slot;
+}
+
+// the effect of a reserve list that succeeds as a whole on the shadows; returns the blocks added
+static int64_t shadow_reserve(Model &m, int T, int n, const int32_t *seqs, const int32_t *ctx_lens) {
+    int64_t added = 0;
+    for (int i = 0; i < n; ++i) {
+        const int want = (int)(((int64_t)ctx_lens[i] + T - 1) / T);
+        if (want > m.row_len[seqs[i]]) {
+            added += want - m.row_len[seqs[i]];
+            m.row_len[seqs[i]] = want;
+        }
+    }
+    m.used_blocks += added;
+    return added;
 }
 
 int seq_reserve_batch(int model, int n, const int32_t *seqs, const int32_t *ctx_lens) {
@@ -910,17 +1129,28 @@ int seq_reserve_batch(int model, int n, const int32_t *seqs, const int32_t *ctx_
     if (n < 0 || n > PKV_MAX_BATCH_OPS || (n > 0 && (!seqs || !ctx_lens))) return PKV_E_ARG;
     if (n == 0) return 0;
     Pool &p = g_pools[m->pool];
-    memcpy(g_ops, seqs, sizeof(int32_t) * n);
-    memcpy(g_ops + n, ctx_lens, sizeof(int32_t) * n);
-    const int64_t r = book_call([&] { return pkv_launch_reserve(p.dev, m->dev, n, g_ops, g_res, g_stream); });
-    if (r >= 0) {   // the call succeeded as a whole: replay its effect on the shadow lengths
-        for (int i = 0; i < n; ++i) {
-            const int want = (int)(((int64_t)ctx_lens[i] + p.T - 1) / p.T);
-            if (want > m->row_len[seqs[i]]) m->row_len[seqs[i]] = want;
-        }
-        m->used_blocks += r;
-    }
+    int rc = check_reserve_list(*m, p.T, n, seqs, ctx_lens);
+    if (rc) return rc;
+    const int64_t r = wait_ticket(enqueue_reserve(*m, n, seqs, ctx_lens));
+    if (r >= 0) shadow_reserve(*m, p.T, n, seqs, ctx_lens);   // the call succeeded as a whole: replay its effect
     return (int)r;
+}
+
+int seq_reserve_batch_enqueue(int model, int n, const int32_t *seqs, const int32_t *ctx_lens) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (n < 0 || n > PKV_MAX_BATCH_OPS || (n > 0 && (!seqs || !ctx_lens))) return PKV_E_ARG;
+    if (n == 0) return ticket_handle(finished_ticket(0));
+    Pool &p = g_pools[m->pool];
+    int rc = check_reserve_list(*m, p.T, n, seqs, ctx_lens);
+    if (rc) {                                                 // refused before anything was enqueued
+        g_host_flags |= 4u;
+        return ticket_handle(finished_ticket(rc));
+    }
+    const int slot = enqueue_reserve(*m, n, seqs, ctx_lens, true);
+    shadow_reserve(*m, p.T, n, seqs, ctx_lens);               // estimate: the call succeeds
+    m->stale = true;
+    return ticket_handle(slot);
 }
 
 int seq_reserve(int model, int seq, int ctx_len) {
@@ -928,18 +1158,62 @@ int seq_reserve(int model, int seq, int ctx_len) {
     return seq_reserve_batch(model, 1, &s, &c);
 }
 
+static int enqueue_release(Model &m, int n, const int32_t *seqs, bool sticky = false) {
+    Pool &p = g_pools[m.pool];
+    const int slot = take_ticket();
+    int32_t *ops = ticket_ops(slot);
+    memcpy(ops, seqs, sizeof(int32_t) * n);
+    hipError_t e = pkv_launch_release(p.dev, m.dev, n, ops, &g_res[slot], sticky ? g_err : nullptr, g_stream);
+    if (e != hipSuccess) g_res[slot].value = fail_hip(e, "seq_release launch");
+    return slot;
+}
+
+static void shadow_release(Model &m, int n, const int32_t *seqs) {
+    for (int i = 0; i < n; ++i) {
+        m.used_blocks -= m.row_len[seqs[i]];
+        m.row_len[seqs[i]] = 0;
+    }
+}
+
+int seq_release_batch(int model, int n, const int32_t *seqs) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (n < 0 || n > PKV_MAX_SEQS || (n > 0 && !seqs)) return PKV_E_ARG;
+    for (int i = 0; i < n; ++i)
+        if (seqs[i] < 0 || seqs[i] >= m->dev.max_seqs) return PKV_E_ARG;
+    if (n == 0) return 0;
+    const int64_t r = wait_ticket(enqueue_release(*m, n, seqs));
+    if (r >= 0) shadow_release(*m, n, seqs);
+    return (int)r;
+}
+
+int seq_release_batch_enqueue(int model, int n, const int32_t *seqs) {
+    Model *m = get_model(model);
+    if (!m) return PKV_E_HANDLE;
+    if (n < 0 || n > PKV_MAX_SEQS || (n > 0 && !seqs)) return PKV_E_ARG;
+    for (int i = 0; i < n; ++i)
+        if (seqs[i] < 0 || seqs[i] >= m->dev.max_seqs) return PKV_E_ARG;
+    if (n == 0) return ticket_handle(finished_ticket(0));
+    const int slot = enqueue_release(*m, n, seqs, true);
+    shadow_release(*m, n, seqs);
+    m->stale = true;
+    return ticket_handle(slot);
+}
+
 int seq_release(int model, int seq) {
     Model *m = get_model(model);
     if (!m) return PKV_E_HANDLE;
     if (seq < 0 || seq >= m->dev.max_seqs) return PKV_E_ARG;
-    if (m->row_len[seq] == 0) return 0;
-    Pool &p = g_pools[m->pool];
-    const int64_t r = book_call([&] { return pkv_launch_release(p.dev, m->dev, seq, g_res, g_stream); });
-    if (r >= 0) {
-        m->row_len[seq] = 0;
-        m->used_blocks -= r;
-    }
-    return (int)r;
+    if (!m->stale && m->row_len[seq] == 0) return 0;
+    const int32_t s = seq;
+    return seq_release_batch(model, 1, &s);
+}
+
+long pkv_ticket_result(int ticket) {
+    if (ticket < 0) return PKV_E_ARG;
+    for (int slot = 0; slot < kTickets; ++slot)
+        if (g_tickets[slot].id >= 0 && (int)(g_tickets[slot].id & 0x7fffffff) == ticket) return (long)wait_ticket(slot);
+    return PKV_E_RANGE;        // older than the ring remembers
 }
 
 const int32_t *model_block_table(int model, int *row_stride) {
@@ -960,6 +1234,10 @@ int kv_write(int model, int seq, int tok_begin, int n_tok, const void *k, const 
     if (!k || !v) return PKV_E_ARG;
     if (m->dtype == PKV_E4M3 && (!k_scale || !v_scale)) return PKV_E_ARG;
     Pool &p = g_pools[m->pool];
+    if (m->stale) {                 // the range check below needs the row's true length
+        int rcs = reconcile_pool(m->pool);
+        if (rcs) return rcs;
+    }
     if (((int64_t)tok_begin + n_tok + p.T - 1) / p.T > m->row_len[seq]) return PKV_E_RANGE;
     AttnDesc d{};
     d.pool_base = p.base + (size_t)m->layer * m->layer_bytes;
@@ -998,6 +1276,10 @@ int kv_read(int model, int seq, int tok_begin, int n_tok, void *k_out, void *v_o
     if (!k_out || !v_out) return PKV_E_ARG;
     if (m->dtype == PKV_E4M3 && (!k_scale_out || !v_scale_out)) return PKV_E_ARG;
     Pool &p = g_pools[m->pool];
+    if (m->stale) {
+        int rcs = reconcile_pool(m->pool);
+        if (rcs) return rcs;
+    }
     if (((int64_t)tok_begin + n_tok + p.T - 1) / p.T > m->row_len[seq]) return PKV_E_RANGE;
     AttnDesc d{};
     fill_addressing(d, *m);
@@ -1080,6 +1362,13 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     if (((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return PKV_E_ARG;
     if (block_table) {
         if (row_stride <= 0) return PKV_E_ARG;
+        // An elastic pool backs a frame with memory only while a model owns it, and the kernels cannot
+        // tell whether an id of a caller's table points into such a frame: only the library's own table
+        // (whose rows end where the model's live blocks end) is served there.
+        if (g_pools[m->pool].elastic) {
+            snprintf(g_errbuf, sizeof g_errbuf, "decode_attention: a caller's block table is not served on an elastic pool");
+            return PKV_E_UNSUPPORTED;
+        }
     } else if (batch > m->dev.max_seqs) {
         return PKV_E_RANGE;
     }

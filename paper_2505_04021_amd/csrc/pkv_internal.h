@@ -11,7 +11,8 @@
 #define PKV_MAX_POOLS 8
 #define PKV_MAX_MODELS 64
 #define PKV_FP8_HEADER 128   // bytes in front of an e4m3 block: fp32 sK[Hkv], fp32 sV[Hkv]
-#define PKV_MAX_BATCH_OPS 2048
+#define PKV_MAX_BATCH_OPS 4096   // entries of one reserve call (the growth rounds of a whole admission)
+#define PKV_MAX_ROW_BLOCKS (1 << 20)   // blocks a row can hold at most (the reserve kernel packs a row position into 20 bits)
 #define PKV_MAX_SEQS 4096
 #define PKV_BOOK_THREADS 1024
 // The file-scope scratch array of decode_attention_static: arrival counters, then split-K partials.
@@ -121,11 +122,14 @@ struct AttnGroup {
 
 // ---- launch wrappers implemented in the .hip files ----------------------------
 hipError_t pkv_launch_pool_init(const PoolDev &p, const uint32_t *perm_dev, hipStream_t s);
-hipError_t pkv_launch_inflate(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, hipStream_t s);
-hipError_t pkv_launch_deflate(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, hipStream_t s);
-hipError_t pkv_launch_reserve(const PoolDev &p, const ModelDev &m, int n, const int32_t *seqs_ctx /*pinned host: n seqs then n ctx*/,
-                              BookResult *res, hipStream_t s);
-hipError_t pkv_launch_release(const PoolDev &p, const ModelDev &m, int seq, BookResult *res, hipStream_t s);
+// Bookkeeping kernels: the result goes to *res (pinned host memory); a refused call also sets bit 2 of *err.
+hipError_t pkv_launch_resize(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, uint32_t *err, hipStream_t s);
+// ops: pinned host memory, n sequence ids then n context lengths (n <= PKV_MAX_BATCH_OPS)
+hipError_t pkv_launch_reserve(const PoolDev &p, const ModelDev &m, int n, const int32_t *ops, BookResult *res, uint32_t *err,
+                              hipStream_t s);
+// ops: pinned host memory, n sequence ids (n <= PKV_MAX_SEQS)
+hipError_t pkv_launch_release(const PoolDev &p, const ModelDev &m, int n, const int32_t *ops, BookResult *res, uint32_t *err,
+                              hipStream_t s);
 
 hipError_t pkv_launch_kv_write(const AttnDesc &d, int seq, int tok_begin, int n_tok, const void *k, const void *v,
                                const float *ks, const float *vs, int page_tokens, hipStream_t s);

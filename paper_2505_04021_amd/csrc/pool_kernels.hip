@@ -49,17 +49,25 @@ __global__ void k_pool_init(PoolDev p, const uint32_t *perm) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *p.n_free = n;
 }
 
+// A call's result goes to its slot in pinned host memory; a refused call also raises the sticky
+// device flag (bit 2), so that a caller who only enqueues learns of it without reading every slot.
+__device__ inline void book_finish(BookResult *res, uint32_t *err, int64_t value) {
+    if (value < 0 && err) atomicOr(err, 4u);
+    __threadfence_system();
+    res->value = value;
+}
+
 // inflate: pop `need` frames, append them to the model's list, all or nothing.
-__global__ __launch_bounds__(NT) void k_inflate(PoolDev p, ModelDev m, int64_t target, BookResult *res) {
+__device__ inline void inflate_body(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, uint32_t *err) {
     const int64_t owned = m.counters[0];
     const int64_t n_free = *p.n_free;
     const int64_t need = target - owned;
     if (need <= 0) {
-        if (threadIdx.x == 0) res->value = owned;
+        if (threadIdx.x == 0) book_finish(res, err, owned);
         return;
     }
     if (need > n_free) {
-        if (threadIdx.x == 0) res->value = PKV_E_NOMEM;
+        if (threadIdx.x == 0) book_finish(res, err, PKV_E_NOMEM);
         return;
     }
     for (int64_t k = threadIdx.x; k < need; k += NT) {
@@ -76,22 +84,20 @@ __global__ __launch_bounds__(NT) void k_inflate(PoolDev p, ModelDev m, int64_t t
         m.counters[0] = target;
         m.counters[1] += need * m.slots;
         res->aux0 = need;
-        __threadfence_system();
-        res->value = target;
+        book_finish(res, err, target);
     }
 }
 
 // deflate: hand back empty frames, newest first, until `target` is met (clamp at
 // frames that still hold blocks); then close the gaps in the frame list and bitmap
 // keeping the order of what stays.
-__global__ __launch_bounds__(NT) void k_deflate(PoolDev p, ModelDev m, int64_t target, BookResult *res) {
-    __shared__ int s_wave[NW];
+__device__ inline void deflate_body(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, uint32_t *err, int *s_wave) {
     const int tid = threadIdx.x;
     const int64_t owned = m.counters[0];
     const int64_t n_free = *p.n_free;
     const int64_t want = owned - target;
     if (want <= 0) {
-        if (tid == 0) res->value = owned;
+        if (tid == 0) book_finish(res, err, owned);
         return;
     }
     const int wpf = m.wpf;
@@ -149,52 +155,87 @@ __global__ __launch_bounds__(NT) void k_deflate(PoolDev p, ModelDev m, int64_t t
         m.counters[0] = owned - reclaimed;
         m.counters[1] -= reclaimed * m.slots;
         res->aux0 = reclaimed;
-        __threadfence_system();
-        res->value = owned - reclaimed;
+        book_finish(res, err, owned - reclaimed);
     }
+}
+
+// balloon_resize: the direction is decided here, from the device's own count of owned frames, so
+// that a caller can enqueue the call without knowing how earlier enqueued calls ended.
+__global__ __launch_bounds__(NT) void k_resize(PoolDev p, ModelDev m, int64_t target, BookResult *res, uint32_t *err) {
+    __shared__ int s_wave[NW];
+    const int64_t owned = m.counters[0];          // uniform: every lane takes the same branch
+    if (target > owned) inflate_body(p, m, target, res, err);
+    else if (target < owned) deflate_body(p, m, target, res, err, s_wave);
+    else if (threadIdx.x == 0) book_finish(res, err, owned);
 }
 
 // reserve (batched): rows grow to ceil(ctx / T) blocks; the new blocks of the whole
 // batch take the lowest free slots in frame-list order, entry by entry — the same
-// state a sequential loop of single reserves leaves.
-__global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, const int32_t *ops, BookResult *res) {
+// state a sequential loop of single reserves leaves.  A sequence may appear several
+// times (the growth rounds of an admission in one call): entry i then needs what its
+// row lacks after the earlier entries, i.e. its want minus the largest want among the
+// earlier entries of the same sequence (and the row's length before the call).
+// ops: host (pinned) memory, n sequence ids then n context lengths.
+__global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, const int32_t *ops, BookResult *res, uint32_t *err) {
     __shared__ int s_wave[NW];
-    __shared__ int s_cur[4096];                     // row length while walking the batch
+    __shared__ int s_cur[PKV_MAX_SEQS];             // row length after the entries walked so far
     __shared__ int s_start[PKV_MAX_BATCH_OPS + 1];  // first rank of entry i
-    __shared__ int s_base[PKV_MAX_BATCH_OPS];       // row length before entry i
-    __shared__ int s_seq[PKV_MAX_BATCH_OPS];
-    __shared__ int s_ctx[PKV_MAX_BATCH_OPS];
-    __shared__ int s_status, s_total;
-    const int tid = threadIdx.x;
+    __shared__ uint32_t s_ent[PKV_MAX_BATCH_OPS];   // entry i: sequence << 20 | row length before the entry
+    __shared__ int s_fail;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     for (int s = tid; s < m.max_seqs; s += NT) s_cur[s] = m.row_len[s];
-    for (int i = tid; i < n; i += NT) {          // ops sits in host memory: fetch it once, in parallel
-        s_seq[i] = ops[i];
-        s_ctx[i] = ops[n + i];
-    }
+    if (tid == 0) s_fail = 0x7fffffff;
     __syncthreads();
-    if (tid == 0) {
-        int total = 0, status = 0;
-        const int T = m.page_tokens;
-        for (int i = 0; i < n; ++i) {
-            const int s = s_seq[i], c = s_ctx[i];
-            if (s < 0 || s >= m.max_seqs || c < 0) { status = PKV_E_ARG; break; }
-            const int want = (int)(((int64_t)c + T - 1) / T);
-            if (want > m.max_blocks) { status = PKV_E_RANGE; break; }
-            const int need = want > s_cur[s] ? want - s_cur[s] : 0;
-            s_start[i] = total;
-            s_base[i] = s_cur[s];
-            s_cur[s] += need;
-            total += need;
+    const int T = m.page_tokens;
+    int total = 0;
+    for (int c0 = 0; c0 < n; c0 += NT) {
+        const int i = c0 + tid;
+        int seq = -1, want = 0;
+        if (i < n) {
+            const int s_ = ops[i], c = ops[n + i];
+            if (s_ < 0 || s_ >= m.max_seqs || c < 0) {
+                atomicMin(&s_fail, i * 2);                       // the first refused entry decides the code
+            } else {
+                const int64_t w = ((int64_t)c + T - 1) / T;
+                if (w > m.max_blocks) atomicMin(&s_fail, i * 2 + 1);
+                else { seq = s_; want = (int)w; }
+            }
         }
-        s_start[n] = total;
-        if (status == 0 && (int64_t)total > m.counters[1]) status = PKV_E_BALLOON;
-        s_status = status;
-        s_total = total;
+        // Row length before each entry = the largest want among the earlier entries of its sequence, or
+        // the row's length when the call began.  First every wave looks, for its own 64 entries at once,
+        // at the earlier entries of the same wave through lane reads; then the waves go one after the
+        // other: each reads what the earlier waves (and chunks) left in s_cur and leaves its own wants.
+        int prev = 0;
+#pragma unroll
+        for (int k = 0; k < 63; ++k) {
+            const int sk = __builtin_amdgcn_readlane(seq, k), wk = __builtin_amdgcn_readlane(want, k);
+            if (k < lane && sk == seq && wk > prev) prev = wk;
+        }
+        const int live_waves = ((n - c0 < NT ? n - c0 : NT) + 63) >> 6;
+        for (int w = 0; w < live_waves; ++w) {
+            if (w == wave && seq >= 0) {
+                const int before = s_cur[seq];
+                prev = before > prev ? before : prev;
+                atomicMax(&s_cur[seq], want);
+            }
+            __syncthreads();
+        }
+        const int need = (seq >= 0 && want > prev) ? want - prev : 0;
+        int chunk_total;
+        const int excl = block_excl_scan(need, chunk_total, s_wave);
+        if (i < n) {
+            s_start[i] = total + excl;
+            s_ent[i] = ((uint32_t)(seq >= 0 ? seq : 0) << 20) | (uint32_t)prev;
+        }
+        total += chunk_total;
     }
+    if (tid == 0) s_start[n] = total;
     __syncthreads();
-    const int status = s_status, total = s_total;
+    int status = 0;
+    if (s_fail != 0x7fffffff) status = (s_fail & 1) ? PKV_E_RANGE : PKV_E_ARG;
+    else if ((int64_t)total > m.counters[1]) status = PKV_E_BALLOON;
     if (status != 0 || total == 0) {
-        if (tid == 0) res->value = status;
+        if (tid == 0) book_finish(res, err, status);
         return;
     }
     const int64_t owned = m.counters[0];
@@ -228,7 +269,8 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
                     const int b = __ffs(freeb) - 1;
                     freeb &= freeb - 1;
                     while (s_start[lo + 1] <= r) ++lo;   // ranks rise by one: walk forward
-                    m.rows[(int64_t)s_seq[lo] * m.max_blocks + s_base[lo] + (r - s_start[lo])] =
+                    const uint32_t ent = s_ent[lo];
+                    m.rows[(int64_t)(ent >> 20) * m.max_blocks + (ent & 0xfffffu) + (r - s_start[lo])] =
                         (int32_t)(f * (uint32_t)slots + (uint32_t)(32 * w + b));
                     word |= 1u << b;
                     ++r;
@@ -242,26 +284,57 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
     for (int s = tid; s < m.max_seqs; s += NT) m.row_len[s] = s_cur[s];
     if (tid == 0) {
         m.counters[1] -= total;
-        __threadfence_system();
-        res->value = total;
+        book_finish(res, err, total);
     }
 }
 
-// release: clear the slot bits of every block of the row.
-__global__ __launch_bounds__(NT) void k_release(PoolDev p, ModelDev m, int seq, BookResult *res) {
-    const int n = m.row_len[seq];
-    for (int b = threadIdx.x; b < n; b += NT) {
+// release (batched): clear the slot bits of every block of the listed rows; the same state as single
+// releases in order (a sequence listed twice is empty the second time).
+// ops: host (pinned) memory, n sequence ids, checked by the host.
+__global__ __launch_bounds__(NT) void k_release(PoolDev p, ModelDev m, int n, const int32_t *ops, BookResult *res, uint32_t *err) {
+    __shared__ int s_wave[NW];
+    __shared__ int s_start[PKV_MAX_SEQS + 1];
+    __shared__ int s_seq[PKV_MAX_SEQS];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < n; i += NT) {
+        const int s_ = ops[i];
+        s_seq[i] = (s_ >= 0 && s_ < m.max_seqs) ? s_ : -1;
+    }
+    __syncthreads();
+    int total = 0;
+    for (int c0 = 0; c0 < n; c0 += NT) {
+        const int i = c0 + tid;
+        int len = 0;
+        if (i < n && s_seq[i] >= 0) {
+            len = m.row_len[s_seq[i]];
+            for (int j = 0; j < i && len > 0; ++j)       // listed before: already empty
+                if (s_seq[j] == s_seq[i]) len = 0;
+        }
+        int chunk_total;
+        const int excl = block_excl_scan(len, chunk_total, s_wave);
+        if (i < n) s_start[i] = total + excl;
+        total += chunk_total;
+    }
+    if (tid == 0) s_start[n] = total;
+    __syncthreads();
+    for (int x = tid; x < total; x += NT) {
+        int lo = 0, hi = n;                              // last entry with s_start <= x
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (s_start[mid] <= x) lo = mid; else hi = mid;
+        }
+        const int seq = s_seq[lo], b = x - s_start[lo];
         const uint32_t id = (uint32_t)m.rows[(int64_t)seq * m.max_blocks + b];
         const uint32_t f = id / (uint32_t)m.slots, s = id % (uint32_t)m.slots;
         const int64_t at = p.pos[f];
         atomicAnd(&m.bits[at * m.wpf + (s >> 5)], ~(1u << (s & 31)));
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        m.row_len[seq] = 0;
-        m.counters[1] += n;
-        __threadfence_system();
-        res->value = n;
+    for (int i = tid; i < n; i += NT)
+        if (s_seq[i] >= 0) m.row_len[s_seq[i]] = 0;
+    if (tid == 0) {
+        m.counters[1] += total;
+        book_finish(res, err, total);
     }
 }
 
@@ -274,19 +347,17 @@ hipError_t pkv_launch_pool_init(const PoolDev &p, const uint32_t *perm_dev, hipS
     hipLaunchKernelGGL(k_pool_init, dim3(blocks), dim3(256), 0, s, p, perm_dev);
     return hipGetLastError();
 }
-hipError_t pkv_launch_inflate(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, hipStream_t s) {
-    hipLaunchKernelGGL(k_inflate, dim3(1), dim3(NT), 0, s, p, m, target, res);
+hipError_t pkv_launch_resize(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, uint32_t *err, hipStream_t s) {
+    hipLaunchKernelGGL(k_resize, dim3(1), dim3(NT), 0, s, p, m, target, res, err);
     return hipGetLastError();
 }
-hipError_t pkv_launch_deflate(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, hipStream_t s) {
-    hipLaunchKernelGGL(k_deflate, dim3(1), dim3(NT), 0, s, p, m, target, res);
+hipError_t pkv_launch_reserve(const PoolDev &p, const ModelDev &m, int n, const int32_t *ops, BookResult *res, uint32_t *err,
+                              hipStream_t s) {
+    hipLaunchKernelGGL(k_reserve, dim3(1), dim3(NT), 0, s, p, m, n, ops, res, err);
     return hipGetLastError();
 }
-hipError_t pkv_launch_reserve(const PoolDev &p, const ModelDev &m, int n, const int32_t *ops, BookResult *res, hipStream_t s) {
-    hipLaunchKernelGGL(k_reserve, dim3(1), dim3(NT), 0, s, p, m, n, ops, res);
-    return hipGetLastError();
-}
-hipError_t pkv_launch_release(const PoolDev &p, const ModelDev &m, int seq, BookResult *res, hipStream_t s) {
-    hipLaunchKernelGGL(k_release, dim3(1), dim3(NT), 0, s, p, m, seq, res);
+hipError_t pkv_launch_release(const PoolDev &p, const ModelDev &m, int n, const int32_t *ops, BookResult *res, uint32_t *err,
+                              hipStream_t s) {
+    hipLaunchKernelGGL(k_release, dim3(1), dim3(NT), 0, s, p, m, n, ops, res, err);
     return hipGetLastError();
 }

@@ -276,8 +276,9 @@ def test_bookkeeping_is_deterministic(gpu, oracle):
 
 
 def test_xcd_weights_api_and_tuning(gpu, oracle):
-    """Weights are scaled to mean 1 and clamped; a tuning run leaves valid weights and
-    the launches inside it still compute the right result."""
+    """Weights are scaled to mean 1 and clamped; weights set by hand stay; the library's own tuning
+    (no call ever waits for it) moves them within the clamp while launches that fill the chip go by,
+    and those launches still compute the right result."""
     assert gpu.set_xcd_weights([1, 1, 1, 1, 1, 1, 1, -1]) != 0
     assert gpu.set_xcd_weights([2, 2, 2, 2, 2, 2, 2, 2]) == 0
     assert np.allclose(gpu.get_xcd_weights(), 1.0)
@@ -285,13 +286,23 @@ def test_xcd_weights_api_and_tuning(gpu, oracle):
     w = gpu.get_xcd_weights()
     assert max(w) <= 1.25 + 1e-6 and min(w) >= 0.75 - 1e-6
     gpu.set_xcd_weights(None)
-    p = Pair(gpu, oracle, 32, 8, 128, BF16, [700, 33, 1200, 64, 2000, 5], pool_bytes=128 << 20, max_blocks=160)
+    p = Pair(gpu, oracle, 32, 8, 128, BF16, [1500 + 37 * s for s in range(20)], pool_bytes=256 << 20, max_blocks=160)
+    for _ in range(3):                  # set by hand: the tuning is off
+        p.check()
+    assert np.allclose(gpu.get_xcd_weights(), 1.0)
     assert gpu.tune_xcd(6) == 0
-    for _ in range(8):
+    for _ in range(12):
         p.check()
     w = gpu.get_xcd_weights()
     assert abs(sum(w) / 8 - 1.0) < 0.05 and max(w) <= 1.25 + 1e-6 and min(w) >= 0.75 - 1e-6
+    assert max(abs(x - 1.0) for x in w) > 1e-4, w          # it did move them
+    assert gpu.tune_xcd(0) == 0
+    frozen = gpu.get_xcd_weights()
+    for _ in range(3):
+        p.check()
+    assert gpu.get_xcd_weights() == frozen
     gpu.set_xcd_weights(None)
+    assert gpu.tune_xcd(24) == 0        # the state a process starts in
     p.close()
 
 

@@ -196,3 +196,21 @@ def test_scenarios_keep_invariants(oracle):
             seen_active.add(tuple(r.active_models()))
         assert len(seen_active) > (3 if cfg_id == 3 else 0)
         r.teardown()
+
+
+def test_one_call_admission_equals_the_growth_rounds(oracle):
+    """A batched reserve is defined as its single reserves in order, so the growth rounds of an
+    admission in one list, and the departures in one release list, leave the very state the
+    round-by-round calls leave: the bursty scenario in all three runner modes, step by step."""
+    from workloads.scenarios import Runner, make_config
+    images = {}
+    for mode in ("calls", "batched", "enqueue"):
+        cfg = make_config(3, "small")
+        r = Runner(oracle, cfg, write_kv=False, mode=mode).setup()
+        images[mode] = []
+        for t in range(cfg.steps):
+            r.step(t).flush()
+            images[mode].append(oracle.pool_export_state(r.pool).copy())
+        r.teardown()
+    for t, ref in enumerate(images["calls"]):
+        assert np.array_equal(ref, images["batched"][t]) and np.array_equal(ref, images["enqueue"][t]), t

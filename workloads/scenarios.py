@@ -24,6 +24,7 @@ from . import gen
 
 MiB = 1 << 20
 GiB = 1 << 30
+MAX_RESERVE_LIST = 4096       # entries one seq_reserve_batch call takes
 
 
 @dataclass
@@ -128,10 +129,20 @@ class Runner:
     their KV written: None = all, a set of (model index, sequence uid), or a
     predicate fill(model index, uid)."""
 
-    def __init__(self, be, cfg: Config, fill=None, write_kv: bool = True):
+    def __init__(self, be, cfg: Config, fill=None, write_kv: bool = True, mode: str = "calls"):
+        """mode: how the bookkeeping of an admission / a departure is issued —
+        "calls"   one seq_reserve_batch per growth round and one seq_release per sequence, each waited for;
+        "batched" the growth rounds of an admission in ONE seq_reserve_batch, the departures in ONE
+                  seq_release_batch (the same state by definition of the batched calls), each waited for;
+        "enqueue" as "batched" through the enqueue-only forms: nothing waits, the return values are
+                  fetched by flush(), which whoever drives the scenario calls when it wants them."""
+        assert mode in ("calls", "batched", "enqueue")
         self.be, self.cfg = be, cfg
         self.fill = fill
         self.write_kv = write_kv
+        self.mode = mode
+        self._pending = []            # (index into log, ticket) of enqueued calls whose result is still out
+        self._tape = None             # plan(): the enqueue-only calls are listed here instead of being made
         self.log = []
         self.pool = None
         self.models: List[int] = []
@@ -155,6 +166,54 @@ class Runner:
         if rc < 0:
             raise RuntimeError(f"{self.be.name}: {what} returned {rc}")
         return rc
+
+    def _enqueue(self, what, mi, *args):
+        """An enqueue-only bookkeeping call on model index mi (or its entry on the tape while planning)."""
+        if self._tape is not None:
+            self._tape.append((what + "_enqueue", mi, args))
+            return
+        self._later(what, getattr(self.be, what + "_enqueue")(self.models[mi], *args))
+
+    def plan(self, t0, t1):
+        """Steps t0 .. t1-1 of an enqueue-mode scenario as data, for a driver that wants to issue the
+        calls itself without this module's Python in its timed loop.  Returns one entry per step:
+        (calls, active model indices, {model index: context lengths of a batch admitted in this step},
+        KV bytes a decode of the active models reads); calls = [(method name, model index, args)].
+        The runner's own view (active, ctx, uid) moves on as if the calls had been made."""
+        assert self.mode == "enqueue" and not self.write_kv
+        steps = []
+        for t in range(t0, t1):
+            self._tape = []
+            before = [u.copy() for u in self.uid]
+            self.step(t)
+            admitted = {mi: self.ctx[mi].copy() for mi in self.active_models() if not np.array_equal(before[mi], self.uid[mi])}
+            steps.append((self._tape, self.active_models(), admitted, self.kv_bytes_step()))
+            self._tape = None
+        return steps
+
+    def _later(self, what, ticket):
+        """An enqueue-only call: its place in the log is kept, the value follows in flush()."""
+        if ticket < 0:
+            raise RuntimeError(f"{self.be.name}: {what} was refused at once with {ticket}")
+        self._pending.append((len(self.log), ticket))
+        self.log.append((what, None))
+
+    def flush(self, n=None):
+        """Fetch the results of the first n enqueued calls still out (all of them by default); waits
+        for those calls only."""
+        n = len(self._pending) if n is None else min(n, len(self._pending))
+        for at, ticket in self._pending[:n]:
+            rc = int(self.be.ticket_result(ticket))
+            self.log[at] = (self.log[at][0], rc)
+            if rc < 0:
+                raise RuntimeError(f"{self.be.name}: {self.log[at][0]} returned {rc}")
+        self._pending = self._pending[n:]
+        return self
+
+    def _resize(self, mi, frames):
+        if self.mode == "enqueue":
+            return self._enqueue("balloon_resize", mi, frames)
+        return self._need("balloon_resize", self.be.balloon_resize(self.models[mi], frames))
 
     def _wants(self, mi, uid):
         if self.fill is None:
@@ -190,11 +249,24 @@ class Runner:
         g = gen.generator(c.seed, 12, mi, *key)
         rounds = int((int(ctx_lens.max()) + c.grow_tokens - 1) // c.grow_tokens) if len(seqs) else 0
         import torch
+        all_seqs, all_ctx = [], []
         for r in range(rounds):
             cur = np.minimum(ctx_lens, (r + 1) * c.grow_tokens)
             live = np.nonzero(ctx_lens > r * c.grow_tokens)[0]
             order = live[torch.randperm(len(live), generator=g).numpy()]
-            self._need("seq_reserve_batch", self.be.seq_reserve_batch(m, seqs[order], cur[order]))
+            if self.mode == "calls":
+                self._need("seq_reserve_batch", self.be.seq_reserve_batch(m, seqs[order], cur[order]))
+            else:
+                all_seqs.append(seqs[order])
+                all_ctx.append(cur[order])
+        if all_seqs:
+            a, b = np.concatenate(all_seqs), np.concatenate(all_ctx)
+            for lo in range(0, len(a), MAX_RESERVE_LIST):          # (a list longer than one call takes: several calls)
+                part = slice(lo, lo + MAX_RESERVE_LIST)
+                if self.mode == "enqueue":
+                    self._enqueue("seq_reserve_batch", mi, a[part], b[part])
+                else:
+                    self._need("seq_reserve_batch", self.be.seq_reserve_batch(m, a[part], b[part]))
         for s, n_tok in zip(seqs, ctx_lens):
             u = self.next_uid[mi]
             self.next_uid[mi] += 1
@@ -222,8 +294,13 @@ class Runner:
         return self._need("set_layer", self.be.set_layer(self.models[mi], layer))
 
     def _release(self, mi, seqs):
+        if self.mode == "enqueue":
+            self._enqueue("seq_release_batch", mi, np.asarray(seqs, dtype=np.int32))
+        elif self.mode == "batched":
+            self._need("seq_release_batch", self.be.seq_release_batch(self.models[mi], np.asarray(seqs, dtype=np.int32)))
         for s in seqs:
-            self._need("seq_release", self.be.seq_release(self.models[mi], int(s)))
+            if self.mode == "calls":
+                self._need("seq_release", self.be.seq_release(self.models[mi], int(s)))
             self.blocks[mi] -= int(self._blocks(self.ctx[mi][s]))
             self.ctx[mi][s] = 0
             self.uid[mi][s] = -1
@@ -272,12 +349,12 @@ class Runner:
                 on = bool(self.activity[t][mi])
                 if self.active[mi] and not on:       # burst over: give everything back
                     self._release(mi, np.arange(spec.batch))
-                    self._need("balloon_resize", be.balloon_resize(self.models[mi], 0))
+                    self._resize(mi, 0)
                     self.active[mi] = False
                 elif on and not self.active[mi]:      # burst starts: inflate, admit a batch
                     ctx = self._draw_ctx(spec.batch, (mi, t + 1))
                     frames = self._frames_for(mi, int(self._blocks(ctx).sum()))
-                    self._need("balloon_resize", be.balloon_resize(self.models[mi], frames))
+                    self._resize(mi, frames)
                     self._admit(mi, np.arange(spec.batch), ctx, (t + 1,))
                     self.active[mi] = True
         elif c.cfg == 5 and t > 0 and t % c.cycle_every == 0:
@@ -311,6 +388,7 @@ class Runner:
     # ------------------------------------------------------------ teardown
     def teardown(self):
         be = self.be
+        self.flush()
         for mi, m in enumerate(self.models):
             for s in range(self.cfg.models[mi].batch):
                 be.seq_release(m, s)
