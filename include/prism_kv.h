@@ -32,6 +32,16 @@
  *   - All bookkeeping (free stack, ownership, frame lists, slot bitmaps, block
  *     tables) lives in device memory and is changed only by the library's kernels.
  *   - Calls are not thread-safe; one thread drives one library instance.
+ *   - Streams: a call enqueues on the stream that was current when it was made.  The
+ *     bookkeeping calls of one pool must all go to one stream (or be ordered by the
+ *     caller); attention and KV calls may go to other streams once the caller has ordered
+ *     them behind the bookkeeping they depend on.  A model has ONE split-K workspace: two
+ *     decode_attention* calls on the same model must not overlap in time (different models
+ *     may).  The workspace is sized when the model is registered, so decode_attention*
+ *     neither allocates nor waits and can be captured into a HIP graph without a priming
+ *     launch; the exceptions are a caller's block table with more rows than the model was
+ *     registered for, and a work-item count raised through the tuning header.
+ *   - Knobs and probes for measurements and tests live in prism_kv_tuning.h.
  */
 #ifndef PRISM_KV_H
 #define PRISM_KV_H
@@ -63,8 +73,8 @@ typedef struct pkv_stats {
     int64_t owned[64];          /* frames per model id (0 for ids not in this pool) */
     int64_t used_blocks[64];    /* reserved blocks per model id */
     int64_t mapped_bytes;       /* pool bytes backed by device memory (all of it unless the pool is elastic) */
-    int64_t spare_frames;       /* elastic pools: frames of memory held ready to be mapped */
-    int64_t idle_frames;        /* elastic pools: frames no model owns that were left mapped in place */
+    int64_t spare_frames;       /* (always 0: kept for the layout of the structure) */
+    int64_t idle_frames;        /* elastic pools: frames that have memory but no owner (the pre-allocation buffer) */
 } pkv_stats;
 
 /* ---- library ------------------------------------------------------------ */
@@ -93,18 +103,26 @@ int pool_create_ex(size_t bytes, int page_tokens, size_t frame_bytes, void *devi
 /* A pool whose memory is elastic (paper Sec. 4.2, D1 / D3: the balloon driver hands physical
  * pages out lazily and takes them back, so that what one model gives up can serve another
  * model or its weights).  The pool is a reserved range of device addresses; a frame is backed
- * by device memory exactly while a model owns it: balloon_resize maps the frames an inflate
- * acquires and unmaps the frames a deflate gives back (HIP virtual memory management).
- * frame_bytes must be a multiple of the device's allocation granularity (PKV_E_SHAPE).
- * Everything else behaves like pool_create_ex; pool_stats reports mapped_bytes.
- * pool_set_prealloc sets the size of the pre-allocation buffer (paper D3): up to `frames` frames
- * of memory that no model owns are kept, either created and unmapped, or — when a deflate gave
- * them back — still mapped where they were.  An inflate that takes such a frame again (the free
- * stack hands the latest frames out first) costs no mapping at all; other inflates take a
- * prepared handle before they ask the driver.  Shrinking the buffer unmaps and releases what
- * exceeds it, oldest first.  Returns the frames held now; synchronises the stream. */
+ * by device memory while a model owns it (HIP virtual memory management), and besides that only
+ * while it waits in the pre-allocation buffer.  frame_bytes must be a multiple of the device's
+ * allocation granularity (PKV_E_SHAPE).  Everything else behaves like pool_create_ex;
+ * pool_stats reports mapped_bytes and idle_frames (frames that have memory but no owner).
+ *
+ * The pre-allocation buffer (paper D3: a pre-allocation thread keeps pages ready so that the
+ * cost of mapping stays off the critical path): pool_set_prealloc(pool, n) asks that the n
+ * frames on top of the free stack — the next n an inflate will be given — have memory.  An
+ * inflate of up to n frames then maps nothing, and no balloon_resize ever unmaps: a deflate
+ * pushes its frames, memory and all, on top of the stack and returns.  A thread of the
+ * library restores the rule afterwards: it creates and maps memory for frames that have risen
+ * into the top n, and unmaps and releases the free frames that have sunk below them (about
+ * 50 us per frame to map, 250 us to unmap, so mapped_bytes is back at (owned + n) frames within
+ * roughly 0.3 ms per frame moved).  An inflate that outruns the thread maps what is missing
+ * itself, as it does for everything beyond n.  pool_set_prealloc waits until the buffer
+ * stands and returns the frames held; pool_prealloc_wait waits until the thread has caught up
+ * with every balloon_resize so far and returns the same.  n = 0 (the start) keeps nothing. */
 int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes);
 int pool_set_prealloc(int pool, long frames);
+int pool_prealloc_wait(int pool);
 /* Fails with PKV_E_BUSY while any model is registered in the pool. */
 int pool_destroy(int pool);
 /* Set the order in which a still-untouched pool hands out frames: perm (host,
@@ -330,62 +348,6 @@ int arbitrate_requests(int n, const double *arrival, const double *ttft_slo, con
 int place_models(int n_gpus, double capacity, double tau, int n_models, const double *token_rate,
                  const double *token_size, const double *slo, const double *weight,
                  const int32_t *current_gpu, const int32_t *tp_group, int32_t *gpu_out);
-
-/* Per-kernel timing for measurements: with every = n > 0, every n-th decode_attention*
- * call brackets its attention kernel with HIP events on the library's stream (at most
- * 8192 calls are recorded); 0 switches it off.  pkv_timing_read waits for the stream,
- * returns the number of recorded calls and the summed kernel time in milliseconds, and
- * clears the record. */
-int pkv_timing_enable(int every);
-long pkv_timing_read(double *attention_ms);
-/* Measured ceilings for comparison: reads a freshly allocated buffer of `bytes` bytes
- * (a power of two) `iters` times with a kernel that does no arithmetic and reports
- * the read bandwidth in GB/s.  granule_bytes = 0: plain streaming read; otherwise a
- * power of two >= 1024: whole granules of that size are read in a scrambled order,
- * the access pattern of paged KV tiles.  Allocates and frees its buffer; synchronises. */
-int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double *gbps);
-/* Measurement / test knobs of the attention work split: `items` = work items (waves)
- * per launch, `min_share` = smallest number of pages a wave may be given; 0 selects
- * the automatic value of either (items: what the chip holds at once; min_share: an
- * eighth of a mean row, within 4..16 pages). */
-int pkv_set_split(int items, int min_share);
-/* What a (sequence, kv head) segment is taken to cost besides its pages when the pages
- * are cut into shares, in pages (0..256; -1 = the default).  A wave whose share holds
- * many short sequences then gets fewer pages than one inside a long sequence. */
-int pkv_set_segment_cost(int pages);
-/* Which form of the decode kernel a launch uses: 0 = two waves per SIMD (2048 work items),
- * 1 = one wave per SIMD with twice the bytes in flight (1024 work items; bf16 caches only,
- * other launches keep form 0), -1 = the library decides by the launch (form 1 for bf16 caches
- * unless the launch is small: fewer than 10 pages per work item of form 0). */
-int pkv_set_kernel_form(int form);
-/* The form (0 or 1) of the most recent decode attention launch of this process. */
-int pkv_last_kernel_form(void);
-/* Cost model that shares the waves out among the models of a grouped launch: a page
- * costs per_mille/1000 + 0.1 per KiB of its K and V tile (-1 = the default: 800 in kernel
- * form 0, 4500 in form 1). */
-int pkv_set_page_cost(int per_mille);
-/* The eight XCDs of the chip do not get the same memory bandwidth, and work-groups are
- * dealt to them in turn; so each block of eight consecutive attention work items is
- * cut in proportion to eight weights rather than evenly.  The library finds the weights
- * by itself: the first launches of a process that fill the chip (512 work items or more)
- * also record how long each XCD's waves streamed, the sums travel to the host behind the
- * launch, and a later launch that finds them there moves the weights toward equal times
- * (24 updates, the first 8 coarse; nothing ever waits, and launches under stream capture
- * are left alone).  pkv_tune_xcd(n) restarts that for n more updates (0 = stop: the
- * weights stay as they are).  pkv_set_xcd_weights sets them by hand and stops the tuning
- * (w: 8 positive floats, host memory, copied; NULL = all equal; they are scaled to mean 1
- * and clamped to [0.75, 1.25]); pkv_get_xcd_weights copies the current ones to w[8].  Weights change where
- * the split-K boundaries fall, hence the rounding of the results (by about 1e-6
- * relative), not what is computed.  PKV_E_ARG on a bad argument. */
-int pkv_set_xcd_weights(const float *w);
-int pkv_get_xcd_weights(float *w);
-int pkv_tune_xcd(int updates);
-/* Host-side check of the multiply-shift division the kernels use to split a block
- * id into (frame, slot): returns n / d computed that way. */
-uint32_t pkv_debug_fastdiv(uint32_t n, uint32_t d);
-/* Test hook for the out-of-memory path of elastic pools: after `after` more successful frame
- * mappings the next one is refused as if the driver had no memory left, once (-1 = never). */
-int pkv_debug_fail_frame_map(int after);
 
 #ifdef __cplusplus
 }

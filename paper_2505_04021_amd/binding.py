@@ -80,6 +80,7 @@ def _load():
         "arbitrate_requests": (i, [i, vp, vp, vp, vp, C.c_double, vp]),
         "place_models": (i, [i, C.c_double, C.c_double, i, vp, vp, vp, vp, vp, vp, vp]),
         "pool_set_prealloc": (i, [i, l]),
+        "pool_prealloc_wait": (i, [i]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -91,7 +92,7 @@ def _load():
 EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_set_page_cost", "pkv_debug_fastdiv", "pkv_debug_fail_frame_map",
            "pkv_set_xcd_weights", "pkv_get_xcd_weights", "pkv_tune_xcd", "pkv_set_segment_cost", "pkv_set_kernel_form", "pkv_last_kernel_form",
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
-           "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_destroy", "pool_seed_free_order", "model_register",
+           "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_prealloc_wait", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_register_layers", "pkv_set_layer", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
            "seq_release", "seq_release_batch", "balloon_resize_enqueue", "seq_reserve_batch_enqueue", "seq_release_batch_enqueue",
            "pkv_ticket_result", "model_block_table", "kv_write", "kv_append", "kv_append_chunk", "kv_read", "model_set_batch", "decode_attention",
@@ -439,6 +440,9 @@ class PrismKV:
 
     def pool_set_prealloc(self, pool, frames):
         return self.lib.pool_set_prealloc(pool, frames)
+
+    def pool_prealloc_wait(self, pool):
+        return self.lib.pool_prealloc_wait(pool)
 
     def pool_stats(self, pool):
         """-> dict(n_frames, n_free, owned[64], used_blocks[64], mapped_bytes, spare_frames, idle_frames)"""

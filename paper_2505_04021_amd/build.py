@@ -18,7 +18,8 @@ def newest_source_mtime():
     for root, _, files in os.walk(CSRC):
         for f in files:
             t = max(t, os.path.getmtime(os.path.join(root, f)))
-    t = max(t, os.path.getmtime(os.path.join(HERE, "..", "include", "prism_kv.h")))
+    for h in ("prism_kv.h", "prism_kv_tuning.h"):
+        t = max(t, os.path.getmtime(os.path.join(HERE, "..", "include", h)))
     return t
 
 

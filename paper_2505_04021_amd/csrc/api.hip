@@ -7,8 +7,12 @@
 // successful calls) for argument validation.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
+#include <condition_variable>
+#include <mutex>
+#include <thread>
 #include <vector>
 
 #include "pkv_internal.h"
@@ -26,17 +30,37 @@ struct Pool {
     bool own_base = false;
     PoolDev dev{};
     int64_t n_free = 0;                     // shadow of the device counter
-    // elastic pools: `base` is a reserved address range; a frame is backed by memory only while a model owns it
+    // elastic pools: `base` is a reserved address range; a frame is backed by memory while a model owns
+    // it or while it waits, near the top of the free stack, in the pre-allocation buffer
     bool elastic = false;
-    std::vector<hipMemGenericAllocationHandle_t> handle;   // per frame, valid while mapped[f]
-    std::vector<uint8_t> mapped;
-    // the pre-allocation buffer (paper D3), at most spare_cap frames of memory in two forms:
-    std::vector<hipMemGenericAllocationHandle_t> spare;    //   created but unmapped
-    std::vector<uint8_t> idle;                              //   per frame: given back by a deflate, left mapped in place
-    std::vector<uint32_t> idle_fifo;                        //   the same frames, oldest first (entries may be stale)
-    int64_t n_idle = 0;
-    size_t spare_cap = 0;
-    int64_t mapped_frames = 0;
+    struct Elastic *el = nullptr;
+};
+
+// The memory side of an elastic pool (paper Sec. 4.2, D3: a pre-allocation thread keeps a buffer of pages
+// ready, so that mapping cost stays off the critical path).  The free stack hands frames out from its
+// top, so the buffer is simply "the top `target` frames of the free stack are backed by memory": an
+// inflate of up to that many frames finds them ready and maps nothing; a deflate pushes its (mapped)
+// frames on top and returns at once.  A worker thread restores the rule behind the caller's back: it maps
+// frames that have risen into the top region and unmaps free frames that have sunk below it.  The host
+// keeps a copy of the free stack for that (every change of the stack goes through balloon_resize, which
+// on an elastic pool waits for its kernel and knows the frames that moved).
+enum : uint8_t { F_UNMAPPED = 0, F_MAPPING, F_MAPPED, F_UNMAPPING };
+struct Elastic {
+    std::mutex mu;
+    std::condition_variable work, done;     // work: something for the worker; done: a frame changed state / the worker is idle
+    std::thread worker;
+    bool stop = false, idle = true;
+    uint64_t changes = 0, seen = 0;         // callers count every change of stack or target; the worker notes the count it has dealt with
+    int device = 0;
+    uint8_t *base = nullptr;
+    size_t frame_bytes = 0;
+    std::vector<uint32_t> stack;            // copy of the free stack, bottom .. top
+    std::vector<uint8_t> state;             // per frame
+    std::vector<hipMemGenericAllocationHandle_t> handle;    // per frame, valid unless F_UNMAPPED
+    size_t target = 0;                      // frames of the buffer
+    size_t low_water = 0;                   // every stack position below holds an unmapped frame
+    int64_t mapped_frames = 0;              // frames not F_UNMAPPED
+    int64_t mapped_free = 0;                // of those, frames no model owns
 };
 
 struct Model {
@@ -672,100 +696,159 @@ static hipMemAllocationProp device_memory_prop() {
     return prop;
 }
 
-// back frame f of an elastic pool with memory: as it is if a deflate left it mapped, else with a
-// spare handle if there is one, else with newly created memory
-static int elastic_map(Pool &p, uint32_t f) {
-    if (f >= (uint64_t)p.n_frames) return PKV_E_INTERNAL;
-    if (p.idle[f]) {                       // re-acquired before it was trimmed: nothing to do
-        p.idle[f] = 0;
-        p.n_idle--;
+static hipError_t frame_map(Elastic &el, uint32_t f, hipMemGenericAllocationHandle_t h) {
+    void *at = el.base + (size_t)f * el.frame_bytes;
+    hipError_t e = hipMemMap(at, el.frame_bytes, 0, h, 0);
+    if (e != hipSuccess) return e;
+    hipMemAccessDesc acc = {};
+    acc.location.type = hipMemLocationTypeDevice;
+    acc.location.id = el.device;
+    acc.flags = hipMemAccessFlagsProtReadWrite;
+    e = hipMemSetAccess(at, el.frame_bytes, &acc, 1);
+    if (e != hipSuccess) (void)hipMemUnmap(at, el.frame_bytes);
+    return e;
+}
+
+static hipError_t frame_create(Elastic &el, hipMemGenericAllocationHandle_t *h) {
+    hipMemAllocationProp prop = {};
+    prop.type = hipMemAllocationTypePinned;
+    prop.location.type = hipMemLocationTypeDevice;
+    prop.location.id = el.device;
+    return hipMemCreate(h, el.frame_bytes, &prop, 0);
+}
+
+// The pre-allocation thread.  It holds the lock only to choose its next task and to publish the outcome;
+// the driver calls (a mapping costs tens of microseconds, an unmapping a quarter of a millisecond) run
+// with the lock released, the frame marked F_MAPPING / F_UNMAPPING meanwhile.
+static void elastic_worker(Elastic *el) {
+    (void)hipSetDevice(el->device);
+    std::unique_lock<std::mutex> lk(el->mu);
+    while (!el->stop) {
+        const uint64_t gen = el->changes;
+        const size_t n = el->stack.size();
+        const size_t top_from = n > el->target ? n - el->target : 0;      // positions >= top_from form the buffer
+        if (el->low_water > n) el->low_water = n;
+        // 1. a frame of the buffer that has no memory yet (nearest to the top first: it is taken first)
+        long map_at = -1;
+        for (size_t i = n; i-- > top_from;)
+            if (el->state[el->stack[i]] == F_UNMAPPED) { map_at = (long)i; break; }
+        if (map_at >= 0) {
+            const uint32_t f = el->stack[(size_t)map_at];
+            hipMemGenericAllocationHandle_t h{};
+            el->state[f] = F_MAPPING;
+            el->idle = false;
+            lk.unlock();
+            hipError_t e = frame_create(*el, &h);
+            if (e == hipSuccess && (e = frame_map(*el, f, h)) != hipSuccess) (void)hipMemRelease(h);
+            lk.lock();
+            if (e == hipSuccess) {
+                el->handle[f] = h;
+                el->state[f] = F_MAPPED;
+                el->mapped_frames++;
+                el->mapped_free++;          // (a model that took the frame meanwhile waits for this state and corrects the count)
+                if ((size_t)map_at < el->low_water) el->low_water = (size_t)map_at;
+                el->done.notify_all();
+                continue;
+            }
+            // no memory for the buffer right now: leave the frame as it was and rest until something changes
+            el->state[f] = F_UNMAPPED;
+        } else {
+            // 2. a free frame below the buffer that still has memory
+            long unmap_at = -1;
+            while (el->low_water < top_from) {
+                if (el->state[el->stack[el->low_water]] == F_MAPPED) { unmap_at = (long)el->low_water; break; }
+                el->low_water++;
+            }
+            if (unmap_at >= 0) {
+                const uint32_t f = el->stack[(size_t)unmap_at];
+                const hipMemGenericAllocationHandle_t h = el->handle[f];
+                el->state[f] = F_UNMAPPING;
+                el->idle = false;
+                lk.unlock();
+                (void)hipMemUnmap(el->base + (size_t)f * el->frame_bytes, el->frame_bytes);
+                (void)hipMemRelease(h);
+                lk.lock();
+                el->state[f] = F_UNMAPPED;
+                el->mapped_frames--;
+                el->mapped_free--;
+                el->done.notify_all();
+                continue;
+            }
+        }
+        el->seen = gen;
+        el->idle = true;
+        el->done.notify_all();
+        el->work.wait(lk, [&] { return el->stop || el->changes != el->seen; });
+    }
+}
+
+// A model has acquired frame f (already popped from the copy of the stack): make sure memory backs it
+// before the call returns.  Called with the lock held.
+static int elastic_acquire(Elastic &el, uint32_t f, std::unique_lock<std::mutex> &lk) {
+    while (el.state[f] == F_MAPPING || el.state[f] == F_UNMAPPING) el.done.wait(lk);
+    if (el.state[f] == F_MAPPED) {
+        el.mapped_free--;
         return PKV_OK;
     }
-    if (p.mapped[f]) return PKV_E_INTERNAL;
     if (g_fail_map_after >= 0 && g_fail_map_after-- == 0) {
         snprintf(g_errbuf, sizeof g_errbuf, "frame %u: mapping refused (pkv_debug_fail_frame_map)", f);
         return PKV_E_NOMEM;
     }
-    hipMemGenericAllocationHandle_t h;
-    if (!p.spare.empty()) {
-        h = p.spare.back();
-        p.spare.pop_back();
-    } else {
-        const hipMemAllocationProp prop = device_memory_prop();
-        hipError_t e = hipMemCreate(&h, p.frame_bytes, &prop, 0);
-        if (e != hipSuccess) { fail_hip(e, "hipMemCreate(frame)"); return PKV_E_NOMEM; }
-    }
-    void *at = p.base + (size_t)f * p.frame_bytes;
-    hipError_t e = hipMemMap(at, p.frame_bytes, 0, h, 0);
-    if (e == hipSuccess) {
-        hipMemAccessDesc acc = {};
-        acc.location = device_memory_prop().location;
-        acc.flags = hipMemAccessFlagsProtReadWrite;
-        e = hipMemSetAccess(at, p.frame_bytes, &acc, 1);
-        if (e != hipSuccess) (void)hipMemUnmap(at, p.frame_bytes);
-    }
+    hipMemGenericAllocationHandle_t h{};
+    el.state[f] = F_MAPPING;
+    lk.unlock();
+    hipError_t e = frame_create(el, &h);
+    int rc = PKV_OK;
     if (e != hipSuccess) {
+        fail_hip(e, "hipMemCreate(frame)");
+        rc = PKV_E_NOMEM;
+    } else if ((e = frame_map(el, f, h)) != hipSuccess) {
         (void)hipMemRelease(h);
         fail_hip(e, "hipMemMap(frame)");
-        return PKV_E_DEVICE;
+        rc = PKV_E_DEVICE;
     }
-    p.handle[f] = h;
-    p.mapped[f] = 1;
-    p.mapped_frames++;
-    return PKV_OK;
+    lk.lock();
+    if (rc == PKV_OK) {
+        el.handle[f] = h;
+        el.state[f] = F_MAPPED;
+        el.mapped_frames++;
+    } else {
+        el.state[f] = F_UNMAPPED;
+    }
+    el.done.notify_all();
+    return rc;
 }
 
-static int elastic_unmap(Pool &p, uint32_t f) {
-    if (f >= (uint64_t)p.n_frames || !p.mapped[f]) return PKV_E_INTERNAL;
-    if (p.idle[f]) {
-        p.idle[f] = 0;
-        p.n_idle--;
-    }
-    hipError_t e = hipMemUnmap(p.base + (size_t)f * p.frame_bytes, p.frame_bytes);
-    if (e != hipSuccess) return fail_hip(e, "hipMemUnmap(frame)");
-    if (p.spare.size() + (size_t)p.n_idle < p.spare_cap) p.spare.push_back(p.handle[f]);
-    else (void)hipMemRelease(p.handle[f]);
-    p.mapped[f] = 0;
-    p.mapped_frames--;
-    return PKV_OK;
+// wait until the pre-allocation thread has dealt with every change made so far (it rests early only if
+// the driver has no memory for the buffer)
+static void elastic_settle(Elastic &el) {
+    std::unique_lock<std::mutex> lk(el.mu);
+    el.work.notify_all();
+    el.done.wait(lk, [&] { return el.idle && el.seen == el.changes; });
 }
 
-// a deflate gave frame f back: leave it mapped where it is while the buffer has room (an inflate
-// that takes it again — the free stack hands the latest frames out first — then costs nothing),
-// else unmap it
-static int elastic_give_back(Pool &p, uint32_t f) {
-    if (f >= (uint64_t)p.n_frames || !p.mapped[f] || p.idle[f]) return PKV_E_INTERNAL;
-    if (p.spare.size() + (size_t)p.n_idle < p.spare_cap) {
-        p.idle[f] = 1;
-        p.n_idle++;
-        p.idle_fifo.push_back(f);
-        return PKV_OK;
-    }
-    return elastic_unmap(p, f);
+// callers, with the lock held, after any change of the stack copy or of the target
+static void elastic_changed(Elastic &el) {
+    ++el.changes;
+    el.work.notify_one();
 }
 
-// shrink the buffer to its cap: spare handles first, then the idle frames that have waited longest
-static int elastic_trim(Pool &p) {
-    while (p.spare.size() + (size_t)p.n_idle > p.spare_cap && !p.spare.empty()) {
-        (void)hipMemRelease(p.spare.back());
-        p.spare.pop_back();
+static void elastic_shutdown(Pool &p) {
+    Elastic *el = p.el;
+    if (!el) return;
+    {
+        std::lock_guard<std::mutex> g(el->mu);
+        el->stop = true;
     }
-    size_t head = 0;
-    while ((size_t)p.n_idle > p.spare_cap && head < p.idle_fifo.size()) {
-        const uint32_t f = p.idle_fifo[head++];
-        if (!p.idle[f]) continue;              // taken again meanwhile
-        const size_t cap = p.spare_cap;
-        p.spare_cap = 0;                        // really release it
-        const int rc = elastic_unmap(p, f);
-        p.spare_cap = cap;
-        if (rc) return rc;
-    }
-    // drop the stale prefix of the queue
-    std::vector<uint32_t> rest;
-    for (size_t i = head; i < p.idle_fifo.size(); ++i)
-        if (p.idle[p.idle_fifo[i]]) rest.push_back(p.idle_fifo[i]);
-    p.idle_fifo.swap(rest);
-    return PKV_OK;
+    el->work.notify_all();
+    if (el->worker.joinable()) el->worker.join();
+    for (size_t f = 0; f < el->state.size(); ++f)
+        if (el->state[f] == F_MAPPED) {
+            (void)hipMemUnmap(el->base + f * el->frame_bytes, el->frame_bytes);
+            (void)hipMemRelease(el->handle[f]);
+        }
+    delete el;
+    p.el = nullptr;
 }
 
 int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes) {
@@ -788,9 +871,32 @@ int pool_create_elastic(size_t bytes, int page_tokens, size_t frame_bytes) {
     }
     Pool &p = g_pools[id];
     p.elastic = true;
-    p.handle.assign((size_t)n_frames, hipMemGenericAllocationHandle_t{});
-    p.mapped.assign((size_t)n_frames, 0);
-    p.idle.assign((size_t)n_frames, 0);
+    Elastic *el = new Elastic;
+    (void)hipGetDevice(&el->device);
+    el->base = p.base;
+    el->frame_bytes = frame_bytes;
+    el->state.assign((size_t)n_frames, F_UNMAPPED);
+    el->handle.assign((size_t)n_frames, hipMemGenericAllocationHandle_t{});
+    el->stack.resize((size_t)n_frames);
+    for (int64_t i = 0; i < n_frames; ++i) el->stack[(size_t)i] = (uint32_t)(n_frames - 1 - i);   // frame 0 on top
+    p.el = el;
+    el->worker = std::thread(elastic_worker, el);
+    static bool at_exit = false;
+    if (!at_exit) {                      // a process that ends with elastic pools alive: stop their threads before the runtime goes
+        at_exit = true;
+        atexit([] {
+            for (int i = 0; i < PKV_MAX_POOLS; ++i) {
+                Elastic *e = g_pools[i].live ? g_pools[i].el : nullptr;
+                if (!e) continue;
+                {
+                    std::lock_guard<std::mutex> g(e->mu);
+                    e->stop = true;
+                }
+                e->work.notify_all();
+                if (e->worker.joinable()) e->worker.join();
+            }
+        });
+    }
     return id;
 }
 
@@ -798,18 +904,25 @@ int pool_set_prealloc(int pool, long frames) {
     Pool *p = get_pool(pool);
     if (!p) return PKV_E_HANDLE;
     if (!p->elastic || frames < 0 || frames > p->n_frames) return PKV_E_ARG;
-    HIP_TRY(hipStreamSynchronize(g_stream));
-    p->spare_cap = (size_t)frames;
-    const int rc = elastic_trim(*p);
-    if (rc) return rc;
-    const hipMemAllocationProp prop = device_memory_prop();
-    while (p->spare.size() + (size_t)p->n_idle < p->spare_cap) {
-        hipMemGenericAllocationHandle_t h;
-        hipError_t e = hipMemCreate(&h, p->frame_bytes, &prop, 0);
-        if (e != hipSuccess) { fail_hip(e, "hipMemCreate(spare)"); return PKV_E_NOMEM; }
-        p->spare.push_back(h);
+    Elastic &el = *p->el;
+    {
+        std::lock_guard<std::mutex> g(el.mu);
+        el.target = (size_t)frames;
+        el.low_water = 0;
+        elastic_changed(el);
     }
-    return (int)(p->spare.size() + (size_t)p->n_idle);
+    elastic_settle(el);
+    std::lock_guard<std::mutex> g(el.mu);
+    return (int)el.mapped_free;
+}
+
+int pool_prealloc_wait(int pool) {
+    Pool *p = get_pool(pool);
+    if (!p) return PKV_E_HANDLE;
+    if (!p->elastic) return 0;
+    elastic_settle(*p->el);
+    std::lock_guard<std::mutex> g(p->el->mu);
+    return (int)p->el->mapped_free;
 }
 
 int pool_create(size_t bytes, int page_tokens) {
@@ -825,11 +938,10 @@ int pool_destroy(int pool) {
     (void)hipFree(p->dev.owner); (void)hipFree(p->dev.free_stack); (void)hipFree(p->dev.pos); (void)hipFree(p->dev.n_free);
     if (p->own_base) (void)hipFree(p->base);
     if (p->elastic) {
-        p->spare_cap = 0;
-        for (int64_t f = 0; f < p->n_frames; ++f)
-            if (p->mapped[(size_t)f]) (void)elastic_unmap(*p, (uint32_t)f);
-        for (auto h : p->spare) (void)hipMemRelease(h);
-        (void)hipMemAddressFree(p->base, (size_t)p->n_frames * p->frame_bytes);
+        const size_t range = (size_t)p->n_frames * p->frame_bytes;
+        uint8_t *base = p->base;
+        elastic_shutdown(*p);
+        (void)hipMemAddressFree(base, range);
     }
     *p = Pool{};
     if (g_last_pool == pool) g_last_pool = -1;
@@ -856,6 +968,12 @@ int pool_seed_free_order(int pool, const uint32_t *perm, size_t n) {
     if (e == hipSuccess) e = hipStreamSynchronize(g_stream);
     (void)hipFree(dperm);
     if (e != hipSuccess) return fail_hip(e, "pool_seed_free_order");
+    if (p->elastic) {                   // the host's copy of the free stack follows: perm[0] on top
+        std::lock_guard<std::mutex> g(p->el->mu);
+        for (size_t i = 0; i < n; ++i) p->el->stack[n - 1 - i] = perm[i];
+        p->el->low_water = 0;
+        elastic_changed(*p->el);
+    }
     return PKV_OK;
 }
 
@@ -1029,42 +1147,60 @@ long balloon_resize(int model, long pages) {
     const int64_t n_free_before = p.n_free;
     p.n_free -= r - before;
     m->owned = r;
+    Elastic &el = *p.el;
     if (r > before) {
-        // the kernel chose the frames (top of the free stack); back them with memory before anyone
-        // can place a block there: they are the new tail of the model's frame list
-        std::vector<uint32_t> got((size_t)(r - before));
-        hipError_t e = hipMemcpy(got.data(), m->dev.frames + before, got.size() * sizeof(uint32_t), hipMemcpyDeviceToHost);
+        // the kernel chose the frames (the top of the free stack, topmost first: they are the new tail of the
+        // model's frame list); memory must back them before anyone can place a block there.  Those that
+        // waited in the buffer have it already.
+        const size_t k = (size_t)(r - before);
+        std::vector<uint32_t> got(k);
+        hipError_t e = hipMemcpy(got.data(), m->dev.frames + before, k * sizeof(uint32_t), hipMemcpyDeviceToHost);
         int fail = e == hipSuccess ? PKV_OK : fail_hip(e, "balloon_resize: reading the acquired frames");
+        std::unique_lock<std::mutex> lk(el.mu);
         size_t backed = 0;
-        for (; fail == PKV_OK && backed < got.size(); ++backed) {
-            fail = elastic_map(p, got[backed]);
-            if (fail) break;
+        if (fail == PKV_OK) {
+            for (size_t i = 0; i < k; ++i) {
+                if (el.stack.empty() || el.stack.back() != got[i]) return PKV_E_INTERNAL;     // the copy of the stack is off
+                el.stack.pop_back();
+            }
+            for (; backed < k; ++backed)
+                if ((fail = elastic_acquire(el, got[backed], lk)) != PKV_OK) break;
+            if (fail == PKV_OK) {
+                elastic_changed(el);
+                return (long)r;
+            }
         }
-        if (fail == PKV_OK) return (long)r;
-        // No memory for a frame (or the list could not be read): undo the whole inflate, or kernels
-        // could be pointed at an address nothing backs.  The frames just taken are the model's newest
-        // and hold no block, so a deflate to the old size hands back exactly them, in the order that
-        // restores the free stack; those already backed go the way of any frame given back.
+        // No memory for a frame (or the list could not be read): undo the whole inflate, or kernels could
+        // be pointed at an address nothing backs.  The frames just taken are the model's newest and hold
+        // no block, so a deflate to the old size hands back exactly them, in the order that restores the
+        // free stack (the newest first, so the one taken first ends on top again).
+        lk.unlock();
         const int64_t back = wait_ticket(enqueue_resize(*m, before));
         if (back >= 0) {
             p.n_free -= back - m->owned;
             m->owned = back;
         }
-        for (size_t j = 0; j < backed; ++j) (void)elastic_give_back(p, got[j]);
+        lk.lock();
+        if (e == hipSuccess && back == before) {
+            if (el.stack.size() < el.low_water) el.low_water = el.stack.size();      // mapped frames arrive from here up
+            for (size_t i = k; i-- > 0;) el.stack.push_back(got[i]);
+            el.mapped_free += (int64_t)backed;         // those that got their memory keep it, as free frames of the buffer
+            elastic_changed(el);
+        }
         return back == before ? fail : PKV_E_INTERNAL;
     }
-    if (r < before) {
-        // the frames given back are the new top of the free stack; nothing refers to them any more
-        // (they held no block) and the stream is idle (the call above waited for its result)
-        std::vector<uint32_t> gone((size_t)(before - r));
-        HIP_TRY(hipMemcpy(gone.data(), p.dev.free_stack + n_free_before, gone.size() * sizeof(uint32_t), hipMemcpyDeviceToHost));
-        // top of the stack first: those are the frames the next inflate takes, so they are the
-        // ones worth leaving mapped while the buffer has room
-        for (auto it = gone.rbegin(); it != gone.rend(); ++it) {
-            const int rc2 = elastic_give_back(p, *it);
-            if (rc2) return rc2;
-        }
-    }
+    // a deflate: the frames given back are the new top of the free stack, in the order the kernel pushed them.
+    // They keep their memory for now (nothing is unmapped inside this call): the top ones are the buffer, the
+    // pre-allocation thread takes the memory of those that lie deeper.  Nothing refers to them any more: they
+    // held no block, and the work enqueued before the deflate has ended (the call above waited for its kernel).
+    const size_t k = (size_t)(before - r);
+    std::vector<uint32_t> gone(k);
+    HIP_TRY(hipMemcpy(gone.data(), p.dev.free_stack + n_free_before, k * sizeof(uint32_t), hipMemcpyDeviceToHost));
+    std::lock_guard<std::mutex> g(el.mu);
+    if (el.stack.size() < el.low_water) el.low_water = el.stack.size();              // mapped frames arrive from here up
+    for (size_t j = 0; j < k; ++j) el.stack.push_back(gone[j]);
+    el.mapped_free += (int64_t)k;
+    elastic_changed(el);
     return (long)r;
 }
 
@@ -1644,9 +1780,12 @@ int pool_stats(int pool, pkv_stats *out) {
         out->owned[id] = cnt[0];
         out->used_blocks[id] = cnt[0] * m.slots - cnt[1];
     }
-    out->mapped_bytes = p->elastic ? p->mapped_frames * (int64_t)p->frame_bytes : p->n_frames * (int64_t)p->frame_bytes;
-    out->spare_frames = (int64_t)p->spare.size();
-    out->idle_frames = p->n_idle;
+    out->mapped_bytes = p->n_frames * (int64_t)p->frame_bytes;
+    if (p->elastic) {
+        std::lock_guard<std::mutex> g(p->el->mu);
+        out->mapped_bytes = p->el->mapped_frames * (int64_t)p->frame_bytes;
+        out->idle_frames = p->el->mapped_free;
+    }
     return PKV_OK;
 }
 

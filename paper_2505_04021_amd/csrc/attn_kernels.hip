@@ -777,11 +777,11 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     gend = gend < W ? gend : W;
     PKV_STAMP(1);
 
-    // --- the first piece: the segment that contains gbeg
-    Piece cur;
-    {
+    // --- which segment holds line position x: the lane whose sequences span x walks them (from
+    // registers for batches that fit there)
+    auto locate = [&](uint32_t x, int &seq, int &P, int &L) {
         const uint32_t lo = (uint32_t)(incl - my_sum) * Hkv, hi = (uint32_t)incl * Hkv;
-        const unsigned long long own = __ballot(lo <= gbeg && gbeg < hi);
+        const unsigned long long own = __ballot(lo <= x && x < hi);
         const int owner = __ffsll(own) - 1;
         int fs = 0, fp = incl - my_sum, fl = 0;     // sequence, pages before it, its context length
         if (K <= LINE_REGS) {
@@ -791,7 +791,7 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                 if (!found && Lc[k] >= 0) {
                     const int np = (Lc[k] + T - 1) / T;
                     const int pl = planned(d, np);
-                    if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl;
+                    if ((uint32_t)(fp + pl) * Hkv <= x) fp += pl;
                     else { fs = lane * K + k; fl = Lc[k]; found = true; }
                 }
             }
@@ -802,21 +802,29 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                     const int L1 = ctx_clamped(d, sq);
                     const int np = (L1 + T - 1) / T;
                     const int pl = planned(d, np);
-                    if ((uint32_t)(fp + pl) * Hkv <= gbeg) fp += pl; else { fs = sq; fl = L1; break; }
+                    if ((uint32_t)(fp + pl) * Hkv <= x) fp += pl; else { fs = sq; fl = L1; break; }
                 }
             }
         }
-        cur.seq = __builtin_amdgcn_readfirstlane(__shfl(fs, owner));
-        cur.P = __builtin_amdgcn_readfirstlane(__shfl(fp, owner));
-        cur.L = __builtin_amdgcn_readfirstlane(__shfl(fl, owner));
-        cur.n_pages = (cur.L + T - 1) / T;
-        cur.pl = planned(d, cur.n_pages);
-        cur.kvh = (int)((gbeg - (uint32_t)cur.P * Hkv) / (uint32_t)cur.pl);
-        piece_clip(cur, d, gbeg, gend);
-        // a share may begin in the allowance behind a segment's last page: nothing to do there
-        if (cur.pb >= cur.pe) cur = piece_next(cur, d, gbeg, gend);
-        if (!cur.valid) return;
-    }
+        seq = __builtin_amdgcn_readfirstlane(__shfl(fs, owner));
+        P = __builtin_amdgcn_readfirstlane(__shfl(fp, owner));
+        L = __builtin_amdgcn_readfirstlane(__shfl(fl, owner));
+    };
+    auto piece_at = [&](uint32_t x) {
+        Piece pc;
+        locate(x, pc.seq, pc.P, pc.L);
+        pc.n_pages = (pc.L + T - 1) / T;
+        pc.pl = planned(d, pc.n_pages);
+        pc.kvh = (int)((x - (uint32_t)pc.P * Hkv) / (uint32_t)pc.pl);
+        piece_clip(pc, d, gbeg, gend);
+        return pc;
+    };
+
+    // --- the first piece: the segment that contains gbeg
+    Piece cur = piece_at(gbeg);
+    // a share may begin in the allowance behind a segment's last page: nothing to do there
+    if (cur.pb >= cur.pe) cur = piece_next(cur, d, gbeg, gend);
+    if (!cur.valid) return;
 
     uint32_t bad = 0;
     const int pf = partial_floats(g, D);

@@ -6,6 +6,7 @@
 // built with hidden visibility: only what the public header declares is exported
 #pragma GCC visibility push(default)
 #include "../../include/prism_kv.h"
+#include "../../include/prism_kv_tuning.h"
 #pragma GCC visibility pop
 
 #define PKV_MAX_POOLS 8

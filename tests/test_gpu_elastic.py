@@ -1,7 +1,8 @@
 """GPU tests of elastic pools: a pool whose frames are backed by device memory only while a model
 owns them (HIP virtual memory management behind balloon_resize).  The bookkeeping state and the
 attention results must be what they are with an ordinary pool — the oracle knows no difference —
-and the memory mapped must be exactly the frames that are owned."""
+and, once the pre-allocation thread has caught up, the memory mapped must be exactly the frames that
+are owned plus the buffer on top of the free stack."""
 import numpy as np
 import pytest
 
@@ -36,8 +37,12 @@ def gpu():
     return PrismKV()
 
 
-def mapped_matches_owned(gpu, pool, frame_bytes):
+def mapped_matches_owned(gpu, pool, frame_bytes, buffer=0):
+    """After the pre-allocation thread has caught up: memory backs the owned frames and the `buffer`
+    frames on top of the free stack (as many as there are), nothing else."""
+    held = gpu.pool_prealloc_wait(pool)
     st = gpu.pool_stats(pool)
+    assert held == st["idle_frames"] == min(buffer, st["n_free"]), (held, buffer, st["idle_frames"], st["n_free"])
     assert st["mapped_bytes"] == (st["n_frames"] - st["n_free"] + st["idle_frames"]) * frame_bytes, st
     return st
 
@@ -89,35 +94,69 @@ def test_frames_are_mapped_while_owned(gpu, oracle):
             be.seq_release(m, s)
         assert be.balloon_resize(m, 0) == 0 and be.balloon_resize(mm, 0) == 0
         assert be.model_unregister(m) == 0 and be.model_unregister(mm) == 0
-    assert gpu.pool_stats(pools[0])["mapped_bytes"] == 0
+    assert mapped_matches_owned(gpu, pools[0], fb)["mapped_bytes"] == 0
     for be, pool in zip(bes, pools):
         assert be.pool_destroy(pool) == 0
 
 
 def test_prealloc_buffer(gpu):
+    """The buffer is the top n frames of the free stack kept mapped: inflates within it map nothing,
+    deflates unmap nothing, and the library's thread restores the rule behind the calls."""
     fb = 2 << 20
     pool = gpu.pool_create_elastic(32 * fb, 16, fb)
     assert pool >= 0
-    assert gpu.pool_set_prealloc(pool, 6) == 6
-    m = gpu.model_register(pool, 32, 8, 128, BF16, 2, 64)
-    assert gpu.balloon_resize(m, 4) == 4
-    st = gpu.pool_stats(pool)
-    assert st["spare_frames"] == 2 and st["mapped_bytes"] == 4 * fb
-    assert gpu.balloon_resize(m, 10) == 10                   # 2 from the buffer, 4 from the driver
-    assert gpu.pool_stats(pool)["spare_frames"] == 0
-    assert gpu.balloon_resize(m, 1) == 1                     # 9 come back: 6 stay mapped in place, 3 are released
-    st = gpu.pool_stats(pool)
-    assert st["idle_frames"] == 6 and st["spare_frames"] == 0 and st["mapped_bytes"] == 7 * fb
-    assert gpu.balloon_resize(m, 5) == 5                     # the free stack hands the latest frames out first,
-    st = gpu.pool_stats(pool)                                # and those are the ones that were left mapped
-    assert st["idle_frames"] == 2 and st["mapped_bytes"] == 7 * fb
-    assert gpu.pool_set_prealloc(pool, 0) == 0               # trim: only what is owned stays mapped
-    st = gpu.pool_stats(pool)
-    assert st["idle_frames"] == 0 and st["spare_frames"] == 0 and st["mapped_bytes"] == 5 * fb
-    assert gpu.balloon_resize(m, 0) == 0 and gpu.model_unregister(m) == 0
     assert gpu.pool_stats(pool)["mapped_bytes"] == 0
+    assert gpu.pool_set_prealloc(pool, 6) == 6
+    assert gpu.pool_stats(pool)["mapped_bytes"] == 6 * fb              # nobody owns a frame yet; six are ready
+    m = gpu.model_register(pool, 32, 8, 128, BF16, 2, 64)
+    assert gpu.balloon_resize(m, 4) == 4                     # all four were ready
+    st = mapped_matches_owned(gpu, pool, fb, 6)              # ... and the thread has made six ready again
+    assert st["mapped_bytes"] == 10 * fb
+    assert gpu.balloon_resize(m, 14) == 14                   # 6 from the buffer, 4 mapped by the call itself
+    assert mapped_matches_owned(gpu, pool, fb, 6)["mapped_bytes"] == 20 * fb
+    assert gpu.balloon_resize(m, 1) == 1                     # 13 come back with their memory ...
+    st = gpu.pool_stats(pool)
+    assert st["mapped_bytes"] >= 7 * fb                      # (the thread may already be taking it from the deeper ones)
+    assert mapped_matches_owned(gpu, pool, fb, 6)["mapped_bytes"] == 7 * fb       # ... of which the top six keep it
+    assert gpu.balloon_resize(m, 5) == 5                     # the free stack hands the latest frames out first:
+    assert mapped_matches_owned(gpu, pool, fb, 6)["mapped_bytes"] == 11 * fb      # those that were left mapped
+    assert gpu.pool_set_prealloc(pool, 0) == 0               # no buffer: only what is owned stays mapped
+    assert mapped_matches_owned(gpu, pool, fb, 0)["mapped_bytes"] == 5 * fb
+    assert gpu.pool_set_prealloc(pool, 32) == 27             # the whole free stack
+    assert mapped_matches_owned(gpu, pool, fb, 32)["mapped_bytes"] == 32 * fb
+    assert gpu.pool_set_prealloc(pool, 2) == 2
+    assert gpu.balloon_resize(m, 0) == 0 and gpu.model_unregister(m) == 0
+    assert mapped_matches_owned(gpu, pool, fb, 2)["mapped_bytes"] == 2 * fb
     assert gpu.pool_destroy(pool) == 0
     assert gpu.pool_create_elastic(32 * fb, 16, fb + 512) < 0          # not a multiple of the granularity
+
+
+def test_a_cold_inflate_and_any_deflate_stay_off_the_driver(gpu):
+    """With a buffer of 176 frames (one admission of the bursty workload) a model that has never held a
+    frame inflates by 176, and deflates by 176, without a single mapping call on its path: both return in
+    a time that no 176 driver calls would fit into."""
+    import time
+    fb = 2 << 20
+    pool = gpu.pool_create_elastic(2048 * fb, 16, fb)
+    assert pool >= 0 and gpu.pool_set_prealloc(pool, 176) == 176
+    a = gpu.model_register(pool, 32, 8, 128, BF16, 2, 64)
+    b = gpu.model_register(pool, 32, 8, 64, BF16, 2, 64)
+    t_inf, t_def = [], []
+    for m in (a, b, a, b):
+        t0 = time.perf_counter()
+        assert gpu.balloon_resize(m, 176) == 176
+        t1 = time.perf_counter()
+        gpu.pool_prealloc_wait(pool)                  # the thread refills the buffer for the next one
+        t2 = time.perf_counter()
+        assert gpu.balloon_resize(m, 0) == 0
+        t3 = time.perf_counter()
+        gpu.pool_prealloc_wait(pool)
+        t_inf.append((t1 - t0) * 1e6)
+        t_def.append((t3 - t2) * 1e6)
+        assert mapped_matches_owned(gpu, pool, fb, 176)["mapped_bytes"] == 176 * fb
+    print(f"inflate by 176 frames {t_inf} us, deflate {t_def} us")
+    assert max(t_inf) < 1000 and max(t_def) < 1000    # 176 mappings take ~7 ms, 176 unmappings ~44 ms
+    assert gpu.model_unregister(a) == 0 and gpu.model_unregister(b) == 0 and gpu.pool_destroy(pool) == 0
 
 
 @pytest.mark.parametrize("cfg_id", [3, 5])
@@ -135,7 +174,8 @@ def test_dynamic_scenarios_on_an_elastic_pool(gpu, oracle, cfg_id):
             ro.step(t)
             assert rg.log == ro.log
             assert_same_state(gpu, oracle, rg.pool, ro.pool, f"step {t}")
-            mapped_matches_owned(gpu, rg.pool, cfg.frame_bytes)
+            if t % 3 == 0:          # (other steps go on while the thread is still at work)
+                mapped_matches_owned(gpu, rg.pool, cfg.frame_bytes, 16)
             if t % 7 == 0:
                 for mi in rg.active_models():
                     q = rg.queries(t, mi)

@@ -14,11 +14,23 @@ def _lib():
     return ctypes.CDLL(build.LIB)
 
 
-def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "prism_kv.h")).read()
+def declared_in(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     text = text[text.index("extern \"C\""):]
-    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+    return set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"}
+
+
+def declared_symbols():
+    """The serving boundary (prism_kv.h) and the measurement / test hooks (prism_kv_tuning.h)."""
+    return sorted(declared_in("prism_kv.h") | declared_in("prism_kv_tuning.h"))
+
+
+def test_serving_header_holds_no_knobs():
+    serving = declared_in("prism_kv.h")
+    assert not [n for n in serving if n.startswith(("pkv_set_", "pkv_debug_", "pkv_tune", "pkv_timing", "pkv_get_xcd"))
+                and n != "pkv_set_stream" and n != "pkv_set_layer"]
+    assert {"pool_create", "model_register", "balloon_resize", "decode_attention"} <= serving
 
 
 def test_every_declared_symbol_is_exported():
