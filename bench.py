@@ -355,14 +355,22 @@ def per_step_times(torch, step, n):
     return [evs[i].elapsed_time(evs[i + 1]) * 1e3 for i in range(n)]
 
 
-def timed_decode(gpu, torch, step, bytes_of_step, steps, warmup, condition_ms):
+LAUNCHES = [0]      # decode launches this process has issued (profiles slice their kernel trace by it)
+
+
+def timed_decode(gpu, torch, step_fn, bytes_of_step, steps, warmup, condition_ms):
     """The timing protocol of a decode workload: conditioning, warm-up, `steps` timed steps between two
     events on the library's stream (and the host's clock around them), then the same steps once more
     with an event behind each for the spread."""
+    def step(i):
+        LAUNCHES[0] += 1
+        step_fn(i)
+
     n_cond = condition(torch, step, condition_ms) if condition_ms > 0 else 0
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
+    first_timed = LAUNCHES[0]
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record()
@@ -375,7 +383,7 @@ def timed_decode(gpu, torch, step, bytes_of_step, steps, warmup, condition_ms):
     total = sum(bytes_of_step(i) for i in range(steps))
     dist = percentiles(per_step_times(torch, step, min(steps, 200)))
     return {"wall_s": wall, "dev_ms": dev_ms, "bytes": total, "n_cond": n_cond, "dist": dist,
-            "form": gpu.last_kernel_form()}
+            "form": gpu.last_kernel_form(), "timed_launches": [first_timed, first_timed + steps]}
 
 
 def decode_summary(t, steps):
@@ -449,6 +457,7 @@ def bursty_leg(gpu, torch, size, steps, warmup, frame_bytes=0):
                                                 [ctxs[mi] for mi in act], [outs[mi] for mi in act])
             assert rc == 0, (rc, gpu.last_error())
             forms[gpu.last_kernel_form()] += 1
+            LAUNCHES[0] += 1
         while tickets and tickets[0][0] < t:          # the previous steps' calls: done long ago
             res = gpu.ticket_result(tickets.pop(0)[1])
             assert res >= 0, res
@@ -458,6 +467,7 @@ def bursty_leg(gpu, torch, size, steps, warmup, frame_bytes=0):
     torch.cuda.synchronize()
     gpu.timing_enable(1)
     forms[0] = forms[1] = 0
+    first_timed = LAUNCHES[0]
     t0 = time.perf_counter()
     for t in range(warmup, total):
         step(t)
@@ -482,7 +492,7 @@ def bursty_leg(gpu, torch, size, steps, warmup, frame_bytes=0):
            "attention_avg_launch_us": round(attn_ms / max(n_rec, 1) * 1e3, 2), "attention_kv_gbps": round(attn_gbps, 1),
            "attention_frac_of_hbm_peak": round(attn_gbps / HBM_PEAK_GBPS, 4),
            "whole_step_over_attention": round((wall * 1e3 / steps) / (attn_ms / max(n_rec, 1)), 3) if n_rec else None,
-           "launches_by_kernel": dict(zip(KERNEL_FORM_NAME, forms)),
+           "launches_by_kernel": dict(zip(KERNEL_FORM_NAME, forms)), "timed_launches": [first_timed, LAUNCHES[0]],
            "ideal_us_at_hbm_peak": round(kv / max(launches, 1) / HBM_PEAK_GBPS / 1e3, 1),
            "kind": "attention: an event pair around every decode launch (each pair adds about 2 us); whole step: host clock "
                    "over all steps, enqueue-only bookkeeping included"}
@@ -506,7 +516,7 @@ def bursty_run(gpu, torch, args):
                      "achieved": leg["attention_kv_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": leg["attention_frac_of_hbm_peak"], "traffic": profiled_traffic("k_attention_deep", leg["workload"], args.size),
                      "avg_launch_us": leg["attention_avg_launch_us"], "launches": leg["decode_launches"],
-                     "launches_by_kernel": leg["launches_by_kernel"]},
+                     "timed_launches": leg["timed_launches"], "launches_by_kernel": leg["launches_by_kernel"]},
         "bursty": leg,
     }
     print(json.dumps(result), flush=True)
@@ -607,6 +617,7 @@ def main():
                      "traffic": None if args.frame_bytes or args.layers > 1 else profiled_traffic(kernel, reps[0].cfg.name, args.size),
                      "traffic_kind": "stored figure of the committed rocprofv3 counter summary of this workload, not read in this run",
                      "avg_launch_us": round(attn_avg_ms * 1e3, 2), "launches": args.steps,
+                     "timed_launches": t["timed_launches"],
                      "bracketed_single_launch_us": round(br_ms / max(n_rec, 1) * 1e3, 2)},
     }
     result["read_ceiling_gbps"] = {"stream": round(gpu.stream_read_probe(4 << 30, 0, 10), 1),

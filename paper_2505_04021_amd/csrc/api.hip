@@ -139,7 +139,6 @@ long g_next_ticket = 0;
 uint32_t *g_err = nullptr;         // device error flags
 uint32_t g_host_flags = 0;         // the same flags, raised by the host (an enqueue-only call refused before any kernel ran)
 void *g_safe = nullptr;            // 16 KiB of zeros: what kernels read instead of a block they must not touch
-uint64_t *g_trace = nullptr;        // time-stamp buffer of instrumented builds
 int g_items = 0, g_min_share = 0, g_seg_cost = -1;
 int g_deep_mode = -1;                // which form of the attention kernel: -1 = by the launch, 0 = two waves per SIMD, 1 = one
 bool g_deep_now = false;             // the form chosen for the launch being prepared
@@ -318,7 +317,6 @@ void fill_desc_core(AttnDesc &d, Model &m, int batch, const void *q, const int32
     d.out = out;
     d.err = g_err;
     d.safe = g_safe;
-    d.trace = g_trace;
     d.frame_bytes = p.frame_bytes;
     d.block_bytes = m.block_bytes;
     d.slots_div = fastdiv_make((uint32_t)m.slots);
@@ -624,13 +622,6 @@ int pkv_stream_read_probe(size_t bytes, size_t granule_bytes, int iters, double 
     return PKV_OK;
 }
 
-#if defined(PKV_TRACE)
-// instrumented builds only: per work-group time stamps of the last attention launch
-int pkv_trace_buffer(void *dev_buf) {
-    g_trace = (uint64_t *)dev_buf;
-    return PKV_OK;
-}
-#endif
 
 int pkv_debug_fail_frame_map(int after) {
     if (after < -1) return PKV_E_ARG;
@@ -1625,7 +1616,6 @@ int prefill_attention(int model, int batch, const void *q, const int32_t *q_lens
     d.vmap = m->vmap;
     d.cols = tile * m->g;
     d.scale_log2 = (float)(1.4426950408889634 / sqrt((double)m->D));
-    d.trace = g_trace;
     if (any_split) {
         const size_t need = rows.size() * m->Hkv * (PKV_PREFILL_TILES * 16) * (size_t)(m->D + 4);
         if (need > m->pf_ws_floats) {

@@ -72,16 +72,10 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi) {
 // 4 e4m3 codes in one word -> 4 bf16 in two words (exact): gfx950's packed conversion with a
 // scale of one, two codes per instruction (checked against the fp32 route on all 2^16 code pairs)
 __device__ __forceinline__ u32x2 fp8x4_to_bf16x4(uint32_t w) {
-#if defined(PKV_CVT_VIA_F32)
-    f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
-    f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
-    return mk2(pack_bf16_trunc(a[0], a[1]), pack_bf16_trunc(b[0], b[1]));
-#else
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
     bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true);
     return mk2(*reinterpret_cast<uint32_t *>(&a), *reinterpret_cast<uint32_t *>(&b));
-#endif
 }
 
 template <int D, int DT>
@@ -233,12 +227,9 @@ __device__ __forceinline__ u32x2 v_half(const PageRegs<D, DT> &r, int jt) {
 // probability (8 bits, error 2^-9) is already 32 times finer than the V it multiplies, and the
 // second product is left out (measured error then ~4e-3 of a row's largest output against a bar of
 // 2e-2; 16 % less time).
-#ifndef PKV_E4M3_PREFILL_P_TERMS
-#define PKV_E4M3_PREFILL_P_TERMS 1
-#endif
 template <int DT, bool PREFILL>
 __device__ __forceinline__ constexpr bool p_has_lo() {
-    return DT == PKV_BF16 || !PREFILL || PKV_E4M3_PREFILL_P_TERMS == 2;
+    return DT == PKV_BF16 || !PREFILL;
 }
 
 // bf16 hi + lo of four probabilities: 16 significant bits reach the matrix unit
@@ -421,21 +412,13 @@ __device__ __forceinline__ void pair_accumulate_ops(State<D, DT> &st, const u32x
 // Floats per split-K partial: g rows of D accumulators, then g maxima, then g sums.
 __host__ __device__ inline int partial_floats(int g, int D) { return g * (D + 2); }
 
-#ifndef PKV_FLIGHT_KIB
-#define PKV_FLIGHT_KIB 16
-#endif
-#ifndef PKV_PRIO
-#define PKV_PRIO 1
-#endif
-#ifndef PKV_WAVES
-#define PKV_WAVES 2
-#endif
+constexpr int FLIGHT_KIB_2WAVES = 16;      // bytes in flight per wave, two waves per SIMD
 // Page pairs resident per wave: one in use, the rest in flight.  The memory system
 // serves waves roughly in proportion to the bytes they have outstanding, so every
-// shape keeps the same number of bytes in flight (PKV_FLIGHT_KIB), small pages through
+// shape keeps the same number of bytes in flight (FLIGHT_KIB_2WAVES), small pages through
 // a deeper ring; otherwise waves of a small-page model would fall behind the others in
 // a grouped launch.
-template <int D, int DT, int FLIGHT_KIB = PKV_FLIGHT_KIB>
+template <int D, int DT, int FLIGHT_KIB = FLIGHT_KIB_2WAVES>
 struct Ring {
     static constexpr int PAIR_BYTES = 4 * Tile<D, DT>::TILE_BYTES;        // K and V tiles of two pages
     static constexpr int N = 1 + (FLIGHT_KIB * 1024 + PAIR_BYTES - 1) / PAIR_BYTES;
@@ -444,9 +427,7 @@ struct Ring {
 // the registers the second wave would have had).  Fewer, longer shares: measured faster for bf16
 // caches from middle-sized launches on (the host chooses), about equal on small ones, and no good
 // for e4m3 caches, whose conversion arithmetic wants a second wave to hide behind.
-#ifndef PKV_DEEP_FLIGHT_KIB
-#define PKV_DEEP_FLIGHT_KIB 32
-#endif
+constexpr int FLIGHT_KIB_1WAVE = 32;       // one wave per SIMD
 constexpr int MAX_PIECES = 64;   // pieces of one (sequence, kv head) the merge stages in LDS
 
 // A row of a launch.  In a decode step it is a sequence with its one new query token.  In a
@@ -686,30 +667,17 @@ struct Cut {
     }
 };
 
-#if defined(PKV_TRACE)
-#define PKV_STAMP(slot) do { if (threadIdx.x == 0 && d.trace) d.trace[(size_t)(blockIdx.x) * 16 + (slot)] = wall_clock64(); } while (0)
-#else
-#define PKV_STAMP(slot) do { } while (0)
-#endif
 
 // CACHED: the partials and arrival counters sit in ordinary (cached) device memory instead of
 // uncached memory.  The L2 caches of the eight XCDs are not coherent with each other for such
 // memory, so the hand-over of a partial follows the memory model by the book: partial stores,
 // release fence, arrival atomic (agent scope) on the writer's side; arrival atomic, acquire fence,
 // partial loads on the merger's side.
-template <int D, int DT, int FLIGHT_KIB = PKV_FLIGHT_KIB, bool CACHED = false>
+template <int D, int DT, int FLIGHT_KIB = FLIGHT_KIB_2WAVES, bool CACHED = false>
 __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, int item, float *s_m, float *s_l) {
     using TL = Tile<D, DT>;
     const int lane = threadIdx.x;
-#if PKV_PRIO
     __builtin_amdgcn_s_setprio(3);      // from the first instruction: a wave still setting up must not wait behind streaming ones
-#endif
-    PKV_STAMP(0);
-#if defined(PKV_TRACE)
-    if (threadIdx.x == 0 && d.trace)      // where the wave runs: HW_ID in the low word, XCC_ID above
-        d.trace[(size_t)blockIdx.x * 16 + 6] = (uint64_t)__builtin_amdgcn_s_getreg(63492) |
-                                              ((uint64_t)__builtin_amdgcn_s_getreg(63508) << 32);
-#endif
     const int G = lane >> 4, n = lane & 15;
     const int g = d.cols, Hkv = d.Hkv, B = d.batch;   // g: columns in use, (query tokens of a row) x (heads of a kv head)
     const Column col = column_of(d, n);
@@ -775,7 +743,6 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     uint32_t gend = cut.begin((uint32_t)item + 1);
     if (gbeg >= W) return;
     gend = gend < W ? gend : W;
-    PKV_STAMP(1);
 
     // --- which segment holds line position x: the lane whose sequences span x walks them (from
     // registers for batches that fit there)
@@ -852,8 +819,6 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     load_q<D>(qf, d, ri_c, cur.kvh, lane, col);
 
     State<D, DT> st;
-    PKV_STAMP(2);
-#if PKV_PRIO
     // Instruction issue favours the older wave of a SIMD, and at two waves per SIMD the
     // younger one can starve for tens of microseconds before it gets its turn.  A wave
     // therefore starts at the highest priority and steps down as its share proceeds, so
@@ -861,11 +826,6 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     const uint32_t prio_total = gend - gbeg + 1;
     uint32_t prio_done = 0;
     int prio_lvl = 0;
-#endif
-    int trace_first = 1;
-#if defined(PKV_TRACE)
-    uint64_t trace_issue = 0, trace_proc = 0, trace_steps = 0, trace_ids = 0;
-#endif
     while (cur.valid) {
         const Piece nxt = piece_next(cur, d, gbeg, gend);
         const RowInfo ri_n = nxt.valid ? row_info_uniform(d, nxt.seq) : ri_c;
@@ -888,13 +848,6 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
             const bool last_turn = t0 + RING >= n_pairs;
 #pragma unroll
             for (int r = 0; r < RING; ++r) {
-#if defined(PKV_TRACE)
-                const uint64_t tr0 = __builtin_readcyclecounter();
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                const uint64_t trA = __builtin_readcyclecounter();
-                trace_ids += trA - tr0;
-#endif
-#if PKV_PRIO
                 {
                     const int lvl = (int)(prio_done * 4u / prio_total) & 3;
                     if (lvl != prio_lvl) {
@@ -904,7 +857,6 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                         else __builtin_amdgcn_s_setprio(0);
                     }
                 }
-#endif
                 // request: position RING-1 of this turn (r == 0), else position r-1 of the next
                 // turn, which belongs to the next piece when this is the piece's last turn
                 {
@@ -928,28 +880,14 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
                     }
                     pre = fetch_ids(d, row, page);
                 }
-#if defined(PKV_TRACE)
-                const uint64_t tr1 = __builtin_readcyclecounter();
-#endif
                 const int i = 2 * (t0 + r);
                 if (i < n_live) {
                     const int pa = cur.pb + i;                                  // absolute page of the pair's first half
                     const int va = pa == cur.n_pages - 1 ? last_valid : T;
                     const int vb = i + 1 < n_live ? (pa + 1 == cur.n_pages - 1 ? last_valid : T) : 0;
                     process_pair<D, DT, false>(st, ring[r], qf, d.scale_log2, va, vb, G);
-#if PKV_PRIO
                     prio_done += 2;
-#endif
                 }
-#if defined(PKV_TRACE)
-                if (trace_first) { trace_first = 0; PKV_STAMP(3); }
-                {
-                    const uint64_t tr2 = __builtin_readcyclecounter();
-                    trace_issue += tr1 - tr0;
-                    trace_proc += tr2 - tr1;
-                    trace_steps += 1;
-                }
-#endif
             }
         }
 
@@ -1008,20 +946,11 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
     }
 
     // --- merges this wave owes: it arrived last at a segment shared with other waves
-    (void)trace_first;
-    PKV_STAMP(4);
     if (w.stat && lane == 0) {          // tuning launches only: when did this XCD's waves finish streaming
         const unsigned xcd = blockIdx.x & 7u;
         atomicAdd(reinterpret_cast<unsigned long long *>(w.stat) + 2 * xcd, (unsigned long long)(wall_clock64() - t_begin));
         atomicAdd(reinterpret_cast<unsigned long long *>(w.stat) + 2 * xcd + 1, 1ull);
     }
-#if defined(PKV_TRACE)
-    if (threadIdx.x == 0 && d.trace) {
-        d.trace[(size_t)blockIdx.x * 16 + 7] = trace_steps | (trace_issue << 16);
-        d.trace[(size_t)blockIdx.x * 16 + 8] = trace_proc;
-        d.trace[(size_t)blockIdx.x * 16 + 9] = trace_ids;
-    }
-#endif
     asm volatile("" ::: "memory");
     if (pend_a.valid) {
         const uint32_t arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)pend_a.arrived);
@@ -1041,10 +970,9 @@ __device__ __forceinline__ void attn_wave(const AttnDesc &d, const AttnTune &w, 
         }
     }
     if (bad && lane == 0) atomicOr(d.err, 1u);
-    PKV_STAMP(5);
 }
 
-__global__ __launch_bounds__(64, PKV_WAVES) void k_attention(const AttnGroup grp) {
+__global__ __launch_bounds__(64, 2) void k_attention(const AttnGroup grp) {
     __shared__ float s_m[MAX_PIECES * 16], s_l[MAX_PIECES * 16];
     const int gi = blockIdx.x;
     int mi = 0;
@@ -1070,22 +998,22 @@ __global__ __launch_bounds__(64, 1) void k_attention_deep(const AttnGroup grp) {
     const AttnDesc &d = grp.m[mi];
     const int item = gi - d.item_begin;
     // bf16 caches only (the host never sends another kind here)
-    if (d.D == 128) attn_wave<128, PKV_BF16, PKV_DEEP_FLIGHT_KIB>(d, grp.tune, item, s_m, s_l);
-    else attn_wave<64, PKV_BF16, PKV_DEEP_FLIGHT_KIB>(d, grp.tune, item, s_m, s_l);
+    if (d.D == 128) attn_wave<128, PKV_BF16, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
+    else attn_wave<64, PKV_BF16, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
 }
 
 // The decode kernel for callers that may not allocate: the same code with its split-K partials and
 // arrival counters in the library's file-scope scratch array (ordinary cached memory).
-__global__ __launch_bounds__(64, PKV_WAVES) void k_attention_static(const AttnGroup grp) {
+__global__ __launch_bounds__(64, 2) void k_attention_static(const AttnGroup grp) {
     __shared__ float s_m[MAX_PIECES * 16], s_l[MAX_PIECES * 16];
     const AttnDesc &d = grp.m[0];
     const int item = blockIdx.x;
     if (d.dtype == PKV_BF16) {
-        if (d.D == 128) attn_wave<128, PKV_BF16, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
-        else attn_wave<64, PKV_BF16, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
+        if (d.D == 128) attn_wave<128, PKV_BF16, FLIGHT_KIB_2WAVES, true>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_BF16, FLIGHT_KIB_2WAVES, true>(d, grp.tune, item, s_m, s_l);
     } else {
-        if (d.D == 128) attn_wave<128, PKV_E4M3, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
-        else attn_wave<64, PKV_E4M3, PKV_FLIGHT_KIB, true>(d, grp.tune, item, s_m, s_l);
+        if (d.D == 128) attn_wave<128, PKV_E4M3, FLIGHT_KIB_2WAVES, true>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_E4M3, FLIGHT_KIB_2WAVES, true>(d, grp.tune, item, s_m, s_l);
     }
 }
 
@@ -1227,9 +1155,6 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         else if (ahead == 1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(TL::NL) : "memory");
         else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     };
-#if defined(PKV_TRACE)
-    uint64_t tr_read = 0, tr_math = 0, tr_sync = 0, tr_steps = 0;
-#endif
     // Operand registers of the pair being worked on.  The K tiles are read from LDS one step
     // ahead, right after the scores of the current pair have been issued (the registers are free
     // from then on), so that a step starts its matrix work without waiting for LDS; the V tiles
@@ -1288,9 +1213,6 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     // from buf_next, and sends the pair NBUF - 1 ahead into the buffer that pair p - 1 occupied
     auto step = [&](int p, const uint8_t *buf, const uint8_t *buf_next, uint8_t *refill) {
         const int pa = 2 * p;
-#if defined(PKV_TRACE)
-        const uint64_t tr0 = __builtin_readcyclecounter();
-#endif
         bool mine[NT];
         bool any_mine = false, all_mine = true;
 #pragma unroll
@@ -1329,9 +1251,6 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
                 if (h == 0) { r.a.sk = sk; r.a.sv = sv; } else { r.b.sk = sk; r.b.sv = sv; }
             }
         }
-#if defined(PKV_TRACE)
-        const uint64_t tr1 = __builtin_readcyclecounter();
-#endif
         if (fast) {
             // the common case in one straight line: the score matrices of every tile, the operand
             // reads, the softmax of every tile, the accumulation of every tile
@@ -1367,21 +1286,11 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
             __builtin_amdgcn_sched_barrier(0);
             if (next_mine) read_k(buf_next);
         }
-#if defined(PKV_TRACE)
-        const uint64_t tr2 = __builtin_readcyclecounter();
-#endif
         // pair p + 2 must have landed before anybody reads its K tiles in the next step; the pair
         // requested in this step may still travel
         const int newest = p + PF_BUFS - 1 < p_end - 1 ? p + PF_BUFS - 1 : p_end - 1;
         landed(newest - (p + 2));
         __builtin_amdgcn_s_barrier();      // every read of this step's buffer has been consumed by then
-#if defined(PKV_TRACE)
-        const uint64_t tr3 = __builtin_readcyclecounter();
-        tr_read += tr1 - tr0;
-        tr_math += tr2 - tr1;
-        tr_sync += tr3 - tr2;
-        tr_steps += 1;
-#endif
     };
 
     // prologue: the first NBUF - 1 pairs are requested, the first two must have landed
@@ -1429,12 +1338,6 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         }
     }
     if (bad && lane == 0) atomicOr(d.err, 1u);
-#if defined(PKV_TRACE)
-    if (lane == 0 && d.trace && blockIdx.x < 4096) {
-        uint64_t *t = d.trace + ((size_t)blockIdx.x * 4 + w) * 4;
-        t[0] = tr_read; t[1] = tr_math; t[2] = tr_sync; t[3] = tr_steps;
-    }
-#endif
 }
 
 // Joins the parts of a group whose context was walked by several work-groups of k_prefill: one

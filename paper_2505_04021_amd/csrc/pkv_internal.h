@@ -90,7 +90,6 @@ struct AttnDesc {
     uint32_t *cnt;              // [B][Hkv] arrival counters of the split-K merge, zero between launches
     uint32_t *err;              // device error flags
     const void *safe;           // 16 KiB of zeros owned by the library: stands in for blocks that must not be read
-    uint64_t *trace;            // NULL, or [grid][16] time stamps and counters (instrumented builds only)
     uint64_t frame_bytes, block_bytes;
     FastDiv slots_div;
     uint32_t max_block_id;      // n_frames * slots
