@@ -328,6 +328,24 @@ __device__ __forceinline__ void pair_qk(const PairRegs<D, DT> &r, const bf16x8 *
     sb = qk_page<D, DT>(r.b, qf);
 }
 
+// The same for two tiles of queries at once (bf16 caches): four independent accumulation chains (two
+// pages x two tiles), written round-robin so that no matrix instruction waits for the one before it.
+template <int D>
+__device__ __forceinline__ void pair_qk2(const PairRegs<D, PKV_BF16> &r, const bf16x8 *q0, const bf16x8 *q1, f32x4 *sa, f32x4 *sb) {
+    using TL = Tile<D, PKV_BF16>;
+    f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, b0 = a0, a1 = a0, b1 = a0;
+#pragma unroll
+    for (int j = 0; j < TL::NK; ++j) {
+        u32x4 ka = r.a.k[j], kb = r.b.k[j];
+        const bf16x8 kav = *reinterpret_cast<bf16x8 *>(&ka), kbv = *reinterpret_cast<bf16x8 *>(&kb);
+        a0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kav, q0[j], a0, 0, 0, 0);
+        b0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kbv, q0[j], b0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kav, q1[j], a1, 0, 0, 0);
+        b1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kbv, q1[j], b1, 0, 0, 0);
+    }
+    sa[0] = a0; sb[0] = b0; sa[1] = a1; sb[1] = b1;
+}
+
 template <int D, int DT>
 __device__ __forceinline__ void pair_softmax(State<D, DT> &st, const PairRegs<D, DT> &r, f32x4 sa, f32x4 sb, float scale_log2,
                                              bf16x8 &phv, bf16x8 &plv) {
@@ -1180,22 +1198,37 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
     // bf16: the two pages' halves of an accumulation operand are read side by side into the four
     // registers of that operand (8-byte reads), so that no register moves are needed to join them
     u32x4 vop[DT == PKV_BF16 ? TL::NV : 1];
+    // bf16: one LDS instruction per operand (ds_read2st64_b64: two 8-byte reads, 512-byte strides, into
+    // four consecutive registers).  Left to itself the compiler fetches 16 bytes at a time and shuffles
+    // the halves into place with 32 register moves per step.  The reads are issued here and waited for
+    // in read_v_wait (the compiler does not count them; LDS returns in order, so its own waits stay safe).
     auto read_v = [&](const uint8_t *buf) {
-        const uint8_t *src = buf + lane * 16;
-        if (DT == PKV_BF16) {
+        if constexpr (DT == PKV_BF16) {
+            const uint32_t at = (uint32_t)(size_t)(__attribute__((address_space(3))) const uint8_t *)buf + (uint32_t)lane * 16u;
 #pragma unroll
             for (int jt = 0; jt < TL::NV; ++jt) {
-                const int off = (jt >> 1) * 1024 + (jt & 1) * 8;
-                const u32x2 x = *reinterpret_cast<const u32x2 *>(src + 1 * TL::TILE_BYTES + off);
-                const u32x2 y = *reinterpret_cast<const u32x2 *>(src + 3 * TL::TILE_BYTES + off);
-                vop[DT == PKV_BF16 ? jt : 0] = mk4(x.x, x.y, y.x, y.y);
+                constexpr int T512 = TL::TILE_BYTES / 512;
+                const int o0 = T512 + 2 * (jt >> 1), o1 = 3 * T512 + 2 * (jt >> 1);
+                const uint32_t a = at + (jt & 1) * 8u;
+                asm volatile("ds_read2st64_b64 %0, %1 offset0:%2 offset1:%3" : "=v"(vop[jt]) : "v"(a), "n"(o0), "n"(o1) : "memory");
             }
         } else {
+            const uint8_t *src = buf + lane * 16;
 #pragma unroll
             for (int j = 0; j < TL::NL; ++j) {
                 r.a.v[j] = *reinterpret_cast<const u32x4 *>(src + 1 * TL::TILE_BYTES + j * 1024);
                 r.b.v[j] = *reinterpret_cast<const u32x4 *>(src + 3 * TL::TILE_BYTES + j * 1024);
             }
+        }
+    };
+    auto read_v_wait = [&]() {
+        if constexpr (DT == PKV_BF16) {
+            static_assert(DT != PKV_BF16 || TL::NV == 8 || TL::NV == 4, "operand tiles of head dims 128 and 64");
+            if constexpr (TL::NV == 8)
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vop[0]), "+v"(vop[1]), "+v"(vop[2]), "+v"(vop[3]), "+v"(vop[TL::NV - 4]),
+                             "+v"(vop[TL::NV - 3]), "+v"(vop[TL::NV - 2]), "+v"(vop[TL::NV - 1])::"memory");
+            else
+                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(vop[0]), "+v"(vop[1]), "+v"(vop[2]), "+v"(vop[3])::"memory");
         }
     };
     // the per-page form of the V tiles that the masked path works on
@@ -1256,8 +1289,12 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
             // reads, the softmax of every tile, the accumulation of every tile
             f32x4 sa[NT], sb[NT];
             bf16x8 phv[NT], plv[NT];
+            if constexpr (DT == PKV_BF16 && NT == 2) {
+                pair_qk2<D>(r, qf[0], qf[1], sa, sb);
+            } else {
 #pragma unroll
-            for (int u = 0; u < NT; ++u) pair_qk<D, DT>(r, qf[u], sa[u], sb[u]);
+                for (int u = 0; u < NT; ++u) pair_qk<D, DT>(r, qf[u], sa[u], sb[u]);
+            }
             __builtin_amdgcn_sched_barrier(0);        // the K registers are rewritten below: not before their last use is issued
             read_v(buf);
             if (next_mine) read_k(buf_next);
@@ -1265,6 +1302,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < NT; ++u) pair_softmax<D, DT>(st[u], r, sa[u], sb[u], d.scale_log2, phv[u], plv[u]);
+            read_v_wait();
 #pragma unroll
             for (int u = 0; u < NT; ++u) {
                 if (DT == PKV_BF16) pair_accumulate_ops<D, DT>(st[u], vop, phv[u], plv[u]);
@@ -1273,6 +1311,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         } else {
             if (any_mine) {
                 read_v(buf);
+                read_v_wait();
                 v_per_page();
             }
 #pragma unroll
