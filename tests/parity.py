@@ -18,6 +18,15 @@ def row_rel_err(gpu, orc):
     return float((num / den).max()) if num.size else 0.0
 
 
+def elementwise_rel_err(gpu, orc):
+    """Secondary measure: |gpu - orc| / max(|orc|, 1e-3 * ||orc_row||_inf) per element, maximum over all
+    elements (the floor keeps elements that cancel to almost nothing from dominating).  Reported, not gated."""
+    o = orc.astype(np.float64)
+    floor = 1e-3 * np.maximum(np.abs(o).max(axis=-1, keepdims=True), 1e-6)
+    e = np.abs(gpu.astype(np.float64) - o) / np.maximum(np.abs(o), floor)
+    return float(e.max()) if e.size else 0.0
+
+
 def assert_same_state(gpu_be, orc_be, gpu_pool, orc_pool, what=""):
     a, b = gpu_be.pool_export_state(gpu_pool), orc_be.pool_export_state(orc_pool)
     if not np.array_equal(a, b):

@@ -11,7 +11,7 @@ replayed in full and compared bit for bit, attention on the sampled sequences' r
 import numpy as np
 import pytest
 
-from parity import TOL, row_rel_err
+from parity import TOL, elementwise_rel_err, row_rel_err
 from workloads.scenarios import Runner, make_config
 
 pytestmark = pytest.mark.gpu
@@ -80,15 +80,17 @@ def test_full_size_whole_batch(gpu, oracle, cfg_id):
         assert rg.log == ro.log
         assert np.array_equal(gpu.pool_export_state(rg.pool), oracle.pool_export_state(ro.pool))
         outs = grouped_decode(gpu, rg, 0)
-        worst, rows = 0.0, 0
+        worst, worst_elem, rows = 0.0, 0.0, 0
         for mi in rg.active_models():
             rc, ref = oracle.decode_attention(ro.models[mi], ro.queries(0, mi), ro.ctx[mi])
             assert rc == 0
             err = row_rel_err(outs[mi], ref)
             assert err <= TOL[cfg.models[mi].dtype], (cfg_id, mi, err)
             worst, rows = max(worst, err), rows + ref.shape[0] * ref.shape[1]
+            worst_elem = max(worst_elem, elementwise_rel_err(outs[mi], ref))
         assert gpu.device_errors() == 0
-        print(f"cfg {cfg_id}: {rows} output rows, worst rel err {worst:.2e}, kernel form {gpu.last_kernel_form()}")
+        print(f"cfg {cfg_id}: {rows} output rows, worst rel err per row {worst:.2e}, per element (floored) {worst_elem:.2e}, "
+              f"kernel form {gpu.last_kernel_form()}")
     finally:
         rg.teardown()
         ro.teardown()
