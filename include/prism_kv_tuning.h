@@ -38,24 +38,30 @@ int pkv_set_split(int items, int min_share);
  * many short sequences then gets fewer pages than one inside a long sequence. */
 int pkv_set_segment_cost(int pages);
 /* Which form of the decode kernel a launch uses: 0 = two waves per SIMD (2048 work items),
- * 1 = one wave per SIMD with twice the bytes in flight (1024 work items; bf16 caches only,
- * other launches keep form 0), -1 = the library decides by the launch (form 1 for bf16 caches
- * unless the launch is small: fewer than 10 pages per work item of form 0). */
+ * 1 = one wave per SIMD, one page pair in flight per wave, and only as many work items as keep
+ * the memory system busy (512, 768 or 1024, by the page sizes and cache types of the launch),
+ * -1 = the library decides by the launch: form 1 unless the launch is small (fewer than 10 240
+ * page units) or its pages are so small that 1024 such waves could not saturate the memory
+ * (e4m3 caches with 64-wide heads). */
 int pkv_set_kernel_form(int form);
 /* The form (0 or 1) of the most recent decode attention launch of this process. */
 int pkv_last_kernel_form(void);
+/* The work items (waves) of that launch, all its models together. */
+int pkv_last_launch_items(void);
 /* Cost model that shares the waves out among the models of a grouped launch: a page
  * costs per_mille/1000 + 0.1 per KiB of its K and V tile (-1 = the default: 800 in kernel
- * form 0, 4500 in form 1). */
+ * form 0, 1600 for bf16 pages in form 1). */
 int pkv_set_page_cost(int per_mille);
 /* The eight XCDs of the chip do not get the same memory bandwidth, and work-groups are
  * dealt to them in turn; so each block of eight consecutive attention work items is
  * cut in proportion to eight weights rather than evenly.  The library finds the weights
- * by itself: the first launches of a process that fill the chip (512 work items or more)
+ * by itself: the first launches of a process that fill the chip (256 work items or more)
  * also record how long each XCD's waves streamed, the sums travel to the host behind the
  * launch, and a later launch that finds them there moves the weights toward equal times
  * (24 updates, the first 8 coarse; nothing ever waits, and launches under stream capture
- * are left alone).  pkv_tune_xcd(n) restarts that for n more updates (0 = stop: the
+ * are left alone).  After those, every eighth such launch is still measured and moves the
+ * weights by a tenth of the way, so that they follow the load (what the XCDs differ by
+ * depends on it).  pkv_tune_xcd(n) restarts all that with n quick updates (0 = stop: the
  * weights stay as they are).  pkv_set_xcd_weights sets them by hand and stops the tuning
  * (w: 8 positive floats, host memory, copied; NULL = all equal; they are scaled to mean 1
  * and clamped to [0.75, 1.25]); pkv_get_xcd_weights copies the current ones to w[8].  Weights change where

@@ -42,6 +42,7 @@ def _load():
         "pkv_set_segment_cost": (i, [i]),
         "pkv_set_kernel_form": (i, [i]),
         "pkv_last_kernel_form": (i, []),
+        "pkv_last_launch_items": (i, []),
         "pkv_stream_read_probe": (i, [sz, sz, i, C.POINTER(C.c_double)]),
         "pkv_timing_enable": (i, [i]),
         "pkv_timing_read": (l, [C.POINTER(C.c_double)]),
@@ -90,7 +91,7 @@ def _load():
 
 
 EXPORTS = ["pkv_set_stream", "pkv_last_error", "pkv_device_errors", "pkv_set_split", "pkv_set_page_cost", "pkv_debug_fastdiv", "pkv_debug_fail_frame_map",
-           "pkv_set_xcd_weights", "pkv_get_xcd_weights", "pkv_tune_xcd", "pkv_set_segment_cost", "pkv_set_kernel_form", "pkv_last_kernel_form",
+           "pkv_set_xcd_weights", "pkv_get_xcd_weights", "pkv_tune_xcd", "pkv_set_segment_cost", "pkv_set_kernel_form", "pkv_last_kernel_form", "pkv_last_launch_items",
            "pkv_timing_enable", "pkv_timing_read", "pkv_stream_read_probe",
            "pool_create", "pool_create_ex", "pool_create_elastic", "pool_set_prealloc", "pool_prealloc_wait", "pool_destroy", "pool_seed_free_order", "model_register",
            "model_register_ex", "model_register_layers", "pkv_set_layer", "model_unregister", "balloon_resize", "seq_reserve", "seq_reserve_batch",
@@ -191,6 +192,9 @@ class PrismKV:
 
     def last_kernel_form(self):
         return self.lib.pkv_last_kernel_form()
+
+    def last_launch_items(self):
+        return self.lib.pkv_last_launch_items()
 
     def set_segment_cost(self, pages=-1):
         return self.lib.pkv_set_segment_cost(int(pages))

@@ -149,10 +149,16 @@ float g_xcd_w[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
 // that fills the chip lets its waves add their streaming times to per-XCD sums on the device (running
 // totals, never cleared); a copy of the totals travels to pinned host memory behind the launch, and a
 // later launch that finds such a copy complete turns the difference to the previous copy into the
-// next step of the weights.
+// next step of the weights.  What the XCDs differ by depends on the load (a launch that saturates the
+// memory wants every second XCD some 7 % below the others, one whose waves are half bound by their own
+// arithmetic wants equal shares), so after the updates a process starts with the weights keep
+// following the launches, slowly: every kSlowTuneEvery-th launch that fills the chip is measured and
+// moves them by a tenth of the way.
 constexpr int kAutoTuneUpdates = 24;        // weight updates a process starts with (coarse ones first)
+constexpr int kSlowTuneEvery = 8;
+constexpr double kSlowTuneGain = 0.1;
 constexpr int kTuneSlots = 4;
-constexpr int kMinTuneItems = 512;          // smaller launches do not fill the chip: their times say little
+constexpr int kMinTuneItems = 256;          // smaller launches do not fill the chip: their times say little
 uint64_t *g_xcd_stat = nullptr;             // device: [8][2] running sums of streaming time and wave counts
 uint64_t *g_tune_host = nullptr;            // pinned: [kTuneSlots][16] copies of the totals
 hipEvent_t g_tune_ev[kTuneSlots];
@@ -161,6 +167,8 @@ long g_tune_version[kTuneSlots];            // which set of weights the launch b
 uint64_t g_tune_last[16];                   // the totals of the last copy looked at
 long g_xcd_version = 0;                     // counts changes of the weights
 int g_tune_left = kAutoTuneUpdates, g_tune_done = 0, g_tune_measured = 0;
+bool g_tune_follow = true;                  // keep following the launches once the first updates are done
+long g_tune_tick = 0;
 constexpr int kMaxTuneMeasured = 4096;      // give up measuring if the updates never come (launches too alike in time)
 constexpr float kXcdWeightMin = 0.75f, kXcdWeightMax = 1.25f;
 double g_page_cost = -1.0;           // fixed cost of a page relative to 0.1 per KiB (< 0: the default of the kernel form)
@@ -255,12 +263,33 @@ void free_model_dev(Model &m) {
     m.ws_floats = m.cnt_cap = 0;
 }
 
-// Work items (waves) per attention launch: what the chip holds at once (256 CUs x 4 SIMDs
-// x 2 resident waves of this kernel), so every wave starts at once and takes one equal
-// share of the pages.  More, smaller items were measured to be slower: an item that
-// starts while the memory system is saturated pays ~10 us before its first page arrives.
-// Each model of a grouped launch gets items in proportion to the KV bytes it will read.
+// Work items (waves) of an attention launch, and which form of the kernel runs them.
+//
+// The ordinary form has two waves per SIMD, and a launch of it gets what the chip holds at once (256
+// CUs x 4 SIMDs x 2 = 2048 items): every wave starts at once and takes one equal share of the pages.
+// More, smaller items were measured to be slower: an item that starts while the memory system is
+// saturated pays ~10 us before its first page arrives.
+//
+// The second form has one wave per SIMD, and only as many waves as it takes to keep the memory system
+// busy.  A wave alone on its SIMD turns pages over at a rate of its own, set by the load - MFMA -
+// softmax - MFMA chain and not by what it has in flight (deep_page_us below: 18.6 GB/s per wave for
+// bf16 pages of 8 KiB, 12 GB/s for 4 KiB ones, 7 and 4 GB/s for e4m3 pages of 4 and 2 KiB); past the
+// point where the waves together can take about 1.3 times what the memory delivers (6.6 TB/s), every
+// further wave only lengthens the queues in front of the memory channels, and the launch gets slower:
+// the two-model workload takes 92.6 us with 512 waves, 95-96 with 768, 97.4 with 1024 (and 98.9 with
+// 1024 waves that keep 32 KiB in flight each instead of one page pair, 100.9 in the ordinary form).
+// Whole CUs' worth of waves only (multiples of 256: with 640 or 896 some CUs hold a wave more than
+// others and their waves fall behind: 99.7 / 98.4 us).  Lognormal row lengths, one model, 0.2-2.5 GB
+// per launch, ordinary form -> second form: bf16, 128-wide heads 512 waves, 2-17 % faster (more on
+// smaller launches); bf16, 64-wide heads 768 waves, 3-13 %; e4m3, 128-wide heads 1024 waves (all the
+// form has), 1-12 %; e4m3 with 64-wide heads would need some 2000 such waves and stays with the
+// ordinary form (123 against 155 us for 620 MB).  Launches of fewer than 10 240 page units are left to
+// the ordinary form as well (within a microsecond either way, mostly in its favour).
 constexpr int kDefaultItems = 2048;
+constexpr int kDeepMaxItems = 1024, kDeepMinItems = 512, kItemGrain = 256;
+constexpr double kDeepMinUnits = 10240.0;
+constexpr double kMemBytesPerUs = 6.6e6;       // what the memory system delivers to this kernel at its best
+constexpr double kDeepCapacity = 1.3;          // waves' own rate over the memory's, where more waves stop paying
 // Smallest share of a wave, in pages.  It only binds in launches too small to give every wave slot a
 // share; there the last wave of a (sequence, kv head) merges one partial per piece, one after the
 // other, and many small pieces cost more than they gain in parallelism: an eighth of a mean row,
@@ -268,27 +297,29 @@ constexpr int kDefaultItems = 2048;
 // 28.2 / 20.4; 16 of 4096 with one kv head: 41.6 / 26.9; rows of 8-16 pages are best left at 4).
 constexpr int kDefaultMinShare = 4, kMaxAutoMinShare = 16;
 constexpr int kDefaultSegCost = 6;
-// The kernel's second form (one wave per SIMD, twice the bytes in flight, half the work items) is the
-// faster one for bf16 caches from middle-sized launches on: 2-10 % over shapes from 16 sequences of
-// 2048 tokens (8 page units per work item of the ordinary form) to 16 sequences of 32768 tokens (128
-// units), short rows or long; below that the two forms differ by little and in either direction, and
-// the ordinary form stays.  A wave of the second form has nobody to hide its per-page arithmetic behind, so in the cost
-// model that shares the waves out among the models of a launch the fixed part of a page weighs more
-// (two-model workload, 128- and 64-wide heads: 101.8 us with the ordinary form's 0.8, 97.1-97.5 with
-// 4.5-10, against 98.5 in the ordinary form).
-constexpr int kDeepItems = 1024;
-constexpr double kDeepUnitsPerItem = 10.0;
-constexpr double kPageCost = 0.8, kDeepPageCost = 4.5;
+// Fixed part of a page's cost relative to 0.1 per KiB, in the model that shares the waves of a grouped
+// launch out among its models.  Two-model workload (128- and 64-wide heads), second form, 512 waves:
+// 95.0 us at 0.8, 92.9 at 1.2, 92.6 at 1.6, 93.4 at 2.0, 94.4 at 2.4, 95.2 at 3.2.
+constexpr double kPageCost = 0.8, kDeepPageCost = 1.6;
+int g_plan_items = kDefaultItems;     // items of the launch being prepared, all models together
+int g_last_items = 0;                 // items of the most recent launch
+
+// Time (us) a wave of the second form, alone on its SIMD, spends on one page.
+double deep_page_us(const Model &m) {
+    const double page_kib = (double)m.layer_bytes / m.Hkv / 1024.0;
+    if (m.dtype == PKV_BF16) return 0.179 * ((g_page_cost >= 0.0 ? g_page_cost : kDeepPageCost) + 0.1 * page_kib);
+    return 0.395 + 0.04 * page_kib;
+}
 
 // Expected cost of a model's pages, used to share the waves out among the models of a
 // grouped launch.  A wave spends a fixed time per page (the load - MFMA - softmax - MFMA
-// chain) plus a time per byte; measured on MI355X the two are about equal for a 8 KiB
-// page, so a model of small pages needs more waves than its bytes alone suggest.
+// chain) plus a time per byte, so a model of small pages needs more waves than its bytes
+// alone suggest.
 double est_bytes(const Model &m, bool own, int batch, int row_stride) {
     const double blocks = own ? (double)m.used_blocks : (double)batch * row_stride;
+    if (g_deep_now) return blocks * m.Hkv * deep_page_us(m);
     const double page_kib = (double)m.layer_bytes / m.Hkv / 1024.0;
-    const double fixed = g_page_cost >= 0.0 ? g_page_cost : (g_deep_now ? kDeepPageCost : kPageCost);
-    return blocks * m.Hkv * (fixed + 0.1 * page_kib);
+    return blocks * m.Hkv * ((g_page_cost >= 0.0 ? g_page_cost : kPageCost) + 0.1 * page_kib);
 }
 
 // page units (pages plus the allowance per segment) of a model's part of a launch, as far as the host knows
@@ -297,8 +328,28 @@ double launch_units(const Model &m, bool own, int batch, int row_stride) {
     return ((own ? (double)m.used_blocks : (double)batch * row_stride) + (double)batch * (seg + 1)) * m.Hkv;
 }
 
-void choose_form(bool all_bf16, double units) {
-    g_deep_now = all_bf16 && (g_deep_mode == 1 || (g_deep_mode < 0 && g_items == 0 && units / kDefaultItems >= kDeepUnitsPerItem));
+// What the host knows of a launch before it is cut: page units, their time in waves of the second form,
+// and the bytes they stand for.
+struct LaunchLoad {
+    double units = 0.0, wave_us = 0.0, bytes = 0.0;
+    void add(const Model &m, bool own, int batch, int row_stride) {
+        const double u = launch_units(m, own, batch, row_stride);
+        units += u;
+        wave_us += u * deep_page_us(m);
+        bytes += (own ? (double)m.used_blocks : (double)batch * row_stride) * (double)m.layer_bytes;
+    }
+};
+
+// Chooses the form and the number of items of the launch being prepared.
+void plan_launch(const LaunchLoad &l) {
+    // waves of the second form that together take kDeepCapacity times what the memory delivers
+    const double want = l.bytes > 0.0 ? kDeepCapacity * l.wave_us / (l.bytes / kMemBytesPerUs) : 0.0;
+    int n = (int)(want / kItemGrain + 0.5) * kItemGrain;
+    const bool fits = n <= kDeepMaxItems + kItemGrain;          // 1280 wanted: 1024 still beat the ordinary form
+    n = n < kDeepMinItems ? kDeepMinItems : (n > kDeepMaxItems ? kDeepMaxItems : n);
+    if (g_deep_mode >= 0) g_deep_now = g_deep_mode == 1;
+    else g_deep_now = g_items == 0 && fits && l.units >= kDeepMinUnits;
+    g_plan_items = g_items > 0 ? g_items : (g_deep_now ? n : kDefaultItems);
 }
 
 // Everything of a launch descriptor except its split-K workspace.
@@ -339,7 +390,7 @@ void fill_desc_core(AttnDesc &d, Model &m, int batch, const void *q, const int32
     const double units = units_hint > 0.0 ? units_hint
                                           : ((own ? (double)m.used_blocks : (double)batch * d.row_stride) +
                                              (double)batch * (d.seg_cost + 1)) * m.Hkv;
-    double items = (g_items > 0 ? g_items : (g_deep_now ? kDeepItems : kDefaultItems)) * share_of_launch;
+    double items = g_plan_items * share_of_launch;
     if (items > units / d.min_share) items = units / d.min_share;
     d.n_items = items < 1.0 ? 1 : (int)items;                // never more than the slots in total
     if (d.n_items >= 8) d.n_items &= ~7;                     // whole blocks of eight: one item per XCD
@@ -475,7 +526,7 @@ static void tune_apply(const uint64_t *tot, bool same_weights) {
     uint64_t d[16];
     for (int i = 0; i < 16; ++i) d[i] = tot[i] - g_tune_last[i];
     for (int i = 0; i < 16; ++i) g_tune_last[i] = tot[i];
-    if (!same_weights || g_tune_left <= 0) return;      // measured with weights that have changed since
+    if (!same_weights || (g_tune_left <= 0 && !g_tune_follow)) return;      // measured with weights that have changed since
     double t[8], mean = 0.0;
     for (int i = 0; i < 8; ++i) {
         if (d[2 * i + 1] < 8) return;                    // too few waves on this XCD to judge
@@ -485,11 +536,14 @@ static void tune_apply(const uint64_t *tot, bool same_weights) {
     if (!(mean > 0.0)) return;
     // a wave's time is its share over its XCD's rate: move each weight part of the way to where the
     // times would be equal, and let the next launches correct the rest
-    const double gain = g_tune_done < 8 ? 0.5 : 0.2;      // coarse first, then averaging out the noise
+    // coarse first, then averaging out the noise, then following slowly
+    const double gain = g_tune_left <= 0 ? kSlowTuneGain : (g_tune_done < 8 ? 0.5 : 0.2);
     for (int i = 0; i < 8; ++i) g_xcd_w[i] = (float)(g_xcd_w[i] * pow(mean / t[i], gain));
     normalise_xcd_weights(g_xcd_w);
-    ++g_tune_done;
-    --g_tune_left;
+    if (g_tune_left > 0) {
+        ++g_tune_done;
+        --g_tune_left;
+    }
     ++g_xcd_version;
 }
 
@@ -513,13 +567,16 @@ static int launch_attention(AttnGroup &grp) {
             g_tune_busy[i] = false;
             tune_apply(g_tune_host + 16 * i, g_tune_version[i] == g_xcd_version);
         }
-    bool measure = g_tune_left > 0 && g_tune_measured < kMaxTuneMeasured && g_xcd_stat != nullptr;
+    bool measure = g_xcd_stat != nullptr &&
+                   ((g_tune_left > 0 && g_tune_measured < kMaxTuneMeasured) || (g_tune_left <= 0 && g_tune_follow));
     int items = 0, slot = -1;
     for (int i = 0; i < grp.n; ++i) {
         items += grp.m[i].n_items;
         measure = measure && grp.m[i].weighted;
     }
+    g_last_items = items;
     measure = measure && items >= kMinTuneItems;
+    if (measure && g_tune_left <= 0) measure = ++g_tune_tick % kSlowTuneEvery == 0;
     if (measure) {
         hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
         if (hipStreamIsCapturing(g_stream, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) measure = false;
@@ -549,6 +606,7 @@ int pkv_set_xcd_weights(const float *w) {
     for (int i = 0; i < 8; ++i) g_xcd_w[i] = v[i];
     ++g_xcd_version;
     g_tune_left = 0;              // weights set by hand stay until pkv_tune_xcd asks for tuning again
+    g_tune_follow = false;
     return PKV_OK;
 }
 
@@ -563,6 +621,7 @@ int pkv_tune_xcd(int updates) {
     int rc = lib_init();
     if (rc) return rc;
     g_tune_left = updates;
+    g_tune_follow = updates > 0;
     g_tune_done = 0;
     g_tune_measured = 0;
     return PKV_OK;
@@ -588,6 +647,8 @@ int pkv_set_kernel_form(int form) {
 }
 
 int pkv_last_kernel_form(void) { return g_deep_now ? 1 : 0; }
+
+int pkv_last_launch_items(void) { return g_last_items; }
 
 int pkv_set_segment_cost(int pages) {
     if (pages < -1 || pages > 256) return PKV_E_ARG;
@@ -1501,7 +1562,9 @@ int decode_attention_ex(int model, int batch, const void *q, const int32_t *bloc
     }
     AttnGroup grp;
     grp.n = 1;
-    choose_form(m->dtype == PKV_BF16, launch_units(*m, block_table == nullptr, batch, row_stride));
+    LaunchLoad load;
+    load.add(*m, block_table == nullptr, batch, row_stride);
+    plan_launch(load);
     int rc = fill_desc(grp.m[0], *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
     if (rc) return rc;
 
@@ -1533,6 +1596,7 @@ int decode_attention_static(int model, int batch, const void *q, const int32_t *
     AttnGroup grp;
     grp.n = 1;
     g_deep_now = false;                   // the ordinary kernel form, every cache type
+    g_plan_items = g_items > 0 ? g_items : kDefaultItems;
     AttnDesc &d = grp.m[0];
     fill_desc_core(d, *m, batch, q, block_table, row_stride, ctx_lens, out, 1.0);
     // the partials of the work items must fit what is left of the array behind the counters: fewer,
@@ -1647,8 +1711,8 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
     AttnGroup grp;
     grp.n = 0;
     int items = 0, pool = -1;
-    double total_bytes = 0.0, units = 0.0;
-    bool all_bf16 = true;
+    double total_bytes = 0.0;
+    LaunchLoad load;
     for (int i = 0; i < n_models; ++i) {
         Model *m = get_model(models[i]);
         if (!m) return PKV_E_HANDLE;
@@ -1660,10 +1724,9 @@ int decode_attention_multi(int n_models, const int *models, const int *batches, 
         if (batches[i] == 0) continue;
         if (!q[i] || !ctx_lens[i] || !out[i]) return PKV_E_ARG;
         if (((uintptr_t)q[i] & 15) || ((uintptr_t)out[i] & 15)) return PKV_E_ARG;
-        all_bf16 &= m->dtype == PKV_BF16;
-        units += launch_units(*m, true, batches[i], 0);
+        load.add(*m, true, batches[i], 0);
     }
-    choose_form(all_bf16, units);
+    plan_launch(load);
     for (int i = 0; i < n_models; ++i)              // (the cost of a page depends on the form)
         if (batches[i] > 0) total_bytes += est_bytes(*get_model(models[i]), true, batches[i], 0) + 1.0;
     for (int i = 0; i < n_models; ++i) {

@@ -431,21 +431,22 @@ __device__ __forceinline__ void pair_accumulate_ops(State<D, DT> &st, const u32x
 __host__ __device__ inline int partial_floats(int g, int D) { return g * (D + 2); }
 
 constexpr int FLIGHT_KIB_2WAVES = 16;      // bytes in flight per wave, two waves per SIMD
-// Page pairs resident per wave: one in use, the rest in flight.  The memory system
-// serves waves roughly in proportion to the bytes they have outstanding, so every
-// shape keeps the same number of bytes in flight (FLIGHT_KIB_2WAVES), small pages through
-// a deeper ring; otherwise waves of a small-page model would fall behind the others in
+// Page pairs resident per wave: one in use, the rest in flight.  In the form with two waves per
+// SIMD every shape keeps the same number of bytes in flight (FLIGHT_KIB_2WAVES), small pages
+// through a deeper ring; otherwise waves of a small-page model would fall behind the others in
 // a grouped launch.
 template <int D, int DT, int FLIGHT_KIB = FLIGHT_KIB_2WAVES>
 struct Ring {
     static constexpr int PAIR_BYTES = 4 * Tile<D, DT>::TILE_BYTES;        // K and V tiles of two pages
     static constexpr int N = 1 + (FLIGHT_KIB * 1024 + PAIR_BYTES - 1) / PAIR_BYTES;
 };
-// The second form of the kernel: one wave per SIMD with twice the bytes in flight (its ring lives in
-// the registers the second wave would have had).  Fewer, longer shares: measured faster for bf16
-// caches from middle-sized launches on (the host chooses), about equal on small ones, and no good
-// for e4m3 caches, whose conversion arithmetic wants a second wave to hide behind.
-constexpr int FLIGHT_KIB_1WAVE = 32;       // one wave per SIMD
+// The second form of the kernel: one wave per SIMD, the host launching only as many waves as it
+// takes to keep the memory system busy (512 for bf16 pages of 8 KiB).  A wave alone on its SIMD
+// turns a page pair over in 0.7-1.1 us whatever it has in flight, so one pair in use and one
+// travelling is all the ring needs (8 KiB covers a pair of every shape but bf16 with 128-wide
+// heads, whose pair of 16 KiB is the one in flight anyway); more bytes outstanding only lengthen
+// the queues in front of the memory channels, and the launch as a whole gets slower.
+constexpr int FLIGHT_KIB_1WAVE = 8;
 constexpr int MAX_PIECES = 64;   // pieces of one (sequence, kv head) the merge stages in LDS
 
 // A row of a launch.  In a decode step it is a sequence with its one new query token.  In a
@@ -1015,9 +1016,13 @@ __global__ __launch_bounds__(64, 1) void k_attention_deep(const AttnGroup grp) {
         if (gi >= grp.m[i].item_begin) mi = i;
     const AttnDesc &d = grp.m[mi];
     const int item = gi - d.item_begin;
-    // bf16 caches only (the host never sends another kind here)
-    if (d.D == 128) attn_wave<128, PKV_BF16, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
-    else attn_wave<64, PKV_BF16, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
+    if (d.dtype == PKV_BF16) {
+        if (d.D == 128) attn_wave<128, PKV_BF16, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_BF16, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
+    } else {
+        if (d.D == 128) attn_wave<128, PKV_E4M3, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
+        else attn_wave<64, PKV_E4M3, FLIGHT_KIB_1WAVE>(d, grp.tune, item, s_m, s_l);
+    }
 }
 
 // The decode kernel for callers that may not allocate: the same code with its split-K partials and

@@ -121,7 +121,7 @@ def test_edge_lengths_and_shapes(gpu, oracle, hq, hkv, d, dtype):
         assert gpu.set_segment_cost(seg) == 0
         assert gpu.set_xcd_weights(w) == 0
         err = p.check()
-    # the kernel's other form (one wave per SIMD, deeper ring; e4m3 models keep the ordinary form)
+    # the kernel's other form (one wave per SIMD)
     assert gpu.set_kernel_form(1) == 0
     for items, share, seg, w in ((0, 0, -1, None), (100000, 1, 2, None), (37, 3, 7, UNEVEN), (8, 5, 0, None), (1, 1, -1, None)):
         assert gpu.set_split(items, share) == 0
@@ -307,47 +307,52 @@ def test_xcd_weights_api_and_tuning(gpu, oracle):
 
 
 def test_kernel_form_choice(gpu):
-    """Which form of the decode kernel a launch gets: the ordinary one for small launches and for
-    e4m3 caches (also when the other is asked for), the one-wave-per-SIMD form for bf16 launches
-    of 10 page units per work item or more, or when forced."""
-    pool = gpu.pool_create(1 << 30, 16, 2 << 20)
+    """Which form of the decode kernel a launch gets and how many work items: the ordinary form (2048
+    items at most) for small launches and for pages too small for 1024 lone waves to saturate the
+    memory (e4m3, 64-wide heads); otherwise one wave per SIMD with 512 (bf16, 128-wide heads), 768
+    (bf16, 64-wide) or 1024 (e4m3, 128-wide) items; either form when forced, with equal results."""
+    pool = gpu.pool_create(2 << 30, 16, 2 << 20)
     assert pool >= 0
-    big = gpu.model_register(pool, 32, 8, 128, BF16, 64, 128)
-    q8 = gpu.model_register(pool, 32, 8, 128, E4M3, 4, 16)
-    assert min(big, q8) >= 0
+    shapes = {"b128": (128, BF16), "b64": (64, BF16), "e128": (128, E4M3), "e64": (64, E4M3)}
+    ms = {k: gpu.model_register(pool, 32, 8, d, dt, 64, 128) for k, (d, dt) in shapes.items()}
+    assert min(ms.values()) >= 0
     try:
-        assert gpu.balloon_resize(big, 400) == 400 and gpu.balloon_resize(q8, 2) == 2
-        q = gen.queries((77, 1), 64, 32, 128)
+        for m in ms.values():
+            assert gpu.balloon_resize(m, 200) == 200
 
-        def form_after(model, n_seq, tokens):
-            for s in range(64 if model == big else 4):
-                gpu.seq_release(model, s)
+        def launch(key, n_seq, tokens, form=-1):
+            d, dt = shapes[key]
+            m = ms[key]
+            gpu.seq_release_batch(m, np.arange(64, dtype=np.int32))
             ctx = np.full(n_seq, tokens, dtype=np.int32)
-            assert gpu.seq_reserve_batch(model, list(range(n_seq)), ctx) >= 0
-            kv = gen.seq_kv((77, 2), tokens, 8, 128, BF16 if model == big else E4M3, 16)
+            assert gpu.seq_reserve_batch(m, list(range(n_seq)), ctx) >= 0
+            kv = gen.seq_kv((77, 2), tokens, 8, d, dt, 16)
             for s in range(n_seq):                      # defined values, whatever they are
-                assert gpu.kv_write(model, s, 0, kv["k"], kv["v"], kv.get("k_scale"), kv.get("v_scale")) == tokens
-            rc, out = gpu.decode_attention(model, q[:n_seq], ctx)
+                assert gpu.kv_write(m, s, 0, kv["k"], kv["v"], kv.get("k_scale"), kv.get("v_scale")) == tokens
+            assert gpu.set_kernel_form(form) == 0
+            rc, out = gpu.decode_attention(m, gen.queries((77, 1), n_seq, 32, d), ctx)
             assert rc == 0 and np.isfinite(out).all()
-            return gpu.last_kernel_form()
+            return gpu.last_kernel_form(), gpu.last_launch_items(), out
 
-        assert gpu.set_kernel_form(-1) == 0
-        assert form_after(big, 4, 256) == 0             # 4 x 16 pages x 8 heads: a small launch
-        assert form_after(big, 64, 1600) == 1           # 64 x (100 + 7) x 8 / 2048 = 26.8 units per item
-        assert form_after(big, 64, 400) == 0            # 64 x (25 + 7) x 8 / 2048 = 8
-        assert form_after(big, 64, 600) == 1            # 64 x (38 + 7) x 8 / 2048 = 11.25
-        assert form_after(q8, 4, 200) == 0
-        assert gpu.set_kernel_form(1) == 0
-        assert form_after(big, 4, 256) == 1
-        assert form_after(q8, 4, 200) == 0              # e4m3 caches keep the ordinary form
-        assert gpu.set_kernel_form(0) == 0
-        assert form_after(big, 64, 1600) == 0
+        assert launch("b128", 4, 256)[:2] == (0, 184)          # 4 x (16 + 7) x 8 = 736 units in shares of 4 pages or more
+        assert launch("b128", 64, 1600)[:2] == (1, 512)
+        assert launch("b128", 64, 400)[:2] == (1, 512)         # 64 x (25 + 7) x 8 = 16384 units
+        assert launch("b128", 64, 190)[0] == 0                 # 64 x (12 + 7) x 8 = 9728 units: small
+        assert launch("b64", 64, 1600)[:2] == (1, 768)
+        assert launch("e128", 64, 1600)[:2] == (1, 1024)
+        assert launch("e64", 64, 1600)[:2] == (0, 2048)
+        assert launch("e128", 4, 200)[0] == 0
+        for key in shapes:                                      # forced either way: same numbers
+            f1, n1, out1 = launch(key, 48, 1100, form=1)
+            f0, n0, out0 = launch(key, 48, 1100, form=0)
+            assert (f1, f0, n0) == (1, 0, 2048) and n1 in (512, 768, 1024)
+            assert row_rel_err(out1, out0) <= 2e-5, key
+        assert launch("b128", 4, 256, form=1)[0] == 1
         assert gpu.set_kernel_form(2) == -1 and gpu.set_kernel_form(-2) == -1
         assert gpu.device_errors() == 0
     finally:
         gpu.set_kernel_form(-1)
-        for m, n in ((big, 64), (q8, 4)):
-            for s in range(n):
-                gpu.seq_release(m, s)
+        for m in ms.values():
+            gpu.seq_release_batch(m, np.arange(64, dtype=np.int32))
             assert gpu.balloon_resize(m, 0) == 0 and gpu.model_unregister(m) == 0
         assert gpu.pool_destroy(pool) == 0

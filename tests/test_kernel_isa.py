@@ -41,7 +41,7 @@ def kernel_body(asm, mangled_part):
     return insn, labels, meta
 
 
-def innermost_mfma_loops(insn, labels, min_mfma=30):
+def innermost_mfma_loops(insn, labels, min_mfma=20):
     mf = [i for i, t in enumerate(insn) if t.startswith("v_mfma")]
     loops = []
     for i, t in enumerate(insn):
@@ -55,15 +55,14 @@ def innermost_mfma_loops(insn, labels, min_mfma=30):
 
 def test_streaming_loops_keep_exact_load_counts():
     asm = device_assembly()
-    # the ordinary form (bf16 / e4m3 x head dim 128 / 64, two waves per SIMD) and the form with one
-    # wave per SIMD and a deeper ring (bf16 x head dim 128 / 64)
-    for name, n_loops, max_vgpr in (("11k_attentionE", 4, 256), ("16k_attention_deepE", 2, 512)):
+    # both forms (two waves per SIMD / one wave per SIMD), each with bf16 / e4m3 x head dim 128 / 64
+    for name, n_loops, max_vgpr in (("11k_attentionE", 4, 256), ("16k_attention_deepE", 4, 512)):
         insn, labels, _ = kernel_body(asm, name)
         loops = innermost_mfma_loops(insn, labels)
         assert len(loops) == n_loops, (name, loops)
         for a, b in loops:
             seg = insn[a:b]
-            assert sum(t.startswith("buffer_load_dwordx4") for t in seg) >= 16
+            assert sum(t.startswith("buffer_load_dwordx4") for t in seg) >= 12
             full = [t for t in seg if t.startswith("s_waitcnt") and re.search(r"vmcnt\(0\)", t)]
             assert not full, f"{name} loop {a}..{b} drains vector memory: {full[:3]}"
             assert not any(t.startswith("scratch_") for t in seg), f"{name} loop {a}..{b} spills to scratch"
