@@ -51,7 +51,7 @@ def parse_args():
     ap.add_argument("--condition-ms", type=int, default=1000,
                     help="untimed launches for this long before the warm-up, so that the clocks have settled (0 = none)")
     ap.add_argument("--kernel-form", type=int, default=-1, choices=[-1, 0, 1],
-                    help="decode kernel: 0 = two waves per SIMD, 1 = one wave with a deeper ring, -1 = chosen by the launch")
+                    help="decode kernel: 0 = two waves per SIMD, 1 = one wave per SIMD and as many waves as keep the memory busy, -1 = chosen by the launch")
     ap.add_argument("--tune", type=int, default=24,
                     help="weight updates the library's own tuning of the per-XCD shares may make (24 = what a process starts with; 0 = equal weights)")
     ap.add_argument("--no-legs", dest="legs", action="store_false", help="skip the secondary workloads (cfg 1, 3, 4, 5, cfg 2 on 64 KiB frames)")
@@ -383,7 +383,7 @@ def timed_decode(gpu, torch, step_fn, bytes_of_step, steps, warmup, condition_ms
     total = sum(bytes_of_step(i) for i in range(steps))
     dist = percentiles(per_step_times(torch, step, min(steps, 200)))
     return {"wall_s": wall, "dev_ms": dev_ms, "bytes": total, "n_cond": n_cond, "dist": dist,
-            "form": gpu.last_kernel_form(), "timed_launches": [first_timed, first_timed + steps]}
+            "form": gpu.last_kernel_form(), "items": gpu.last_launch_items(), "timed_launches": [first_timed, first_timed + steps]}
 
 
 def decode_summary(t, steps):
@@ -392,7 +392,7 @@ def decode_summary(t, steps):
     gbps = t["bytes"] / (t["dev_ms"] * 1e-3) / 1e9
     return {"step_us": round(us, 2), "step_us_wall": round(t["wall_s"] * 1e6 / steps, 2), "step_us_spread": t["dist"],
             "kv_gbps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-            "kernel": KERNEL_FORM_NAME[t["form"]], "steps": steps}
+            "kernel": KERNEL_FORM_NAME[t["form"]], "work_items": t["items"], "steps": steps}
 
 
 def static_leg(gpu, torch, cfg_id, steps, warmup, condition_ms, replicas, frame_bytes=0):
@@ -603,7 +603,7 @@ def main():
         "config": {"workload": reps[0].cfg.name, "cfg": args.config, "size": args.size,
                    "frame_bytes": reps[0].cfg.frame_bytes, "layers": args.layers,
                    "replicas_rotated": len(reps), "kv_bytes_per_step": int(np.mean(kv_per_rep)),
-                   "work_items": args.items or "auto", "xcd_weight_updates_allowed": args.tune,
+                   "work_items": t["items"], "work_items_chosen_by": "--items" if args.items else "the library, per launch", "xcd_weight_updates_allowed": args.tune,
                    "conditioning_launches": t["n_cond"],
                    "xcd_weights": [round(x, 3) for x in gpu.get_xcd_weights()],
                    "xcd_weights_found_by": "the library itself, during the conditioning and warm-up launches (no tuning call)"},
