@@ -183,16 +183,36 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
     __shared__ uint32_t s_ent[PKV_MAX_BATCH_OPS];   // entry i: sequence << 20 | row length before the entry
     __shared__ int s_fail;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // Everything the kernel will read is asked for here, before the first answer is needed: the list
+    // (host memory, the longest trip), the rows' lengths, the counters and the lane's own frame of the
+    // first pass of the placement.  The call then costs one such trip instead of five in a row.
+    constexpr int CHUNKS = PKV_MAX_BATCH_OPS / NT, PRE_WORDS = 4;
+    int o_seq[CHUNKS], o_ctx[CHUNKS];
+#pragma unroll
+    for (int c = 0; c < CHUNKS; ++c) {
+        const int i = c * NT + tid;
+        o_seq[c] = i < n ? ops[i] : 0;
+        o_ctx[c] = i < n ? ops[n + i] : 0;
+    }
+    const int64_t owned = m.counters[0], spare = m.counters[1];
+    const int wpf = m.wpf, slots = m.slots;
+    uint32_t pre_bits[PRE_WORDS];
+#pragma unroll
+    for (int w = 0; w < PRE_WORDS; ++w) pre_bits[w] = (tid < owned && w < wpf) ? m.bits[(int64_t)tid * wpf + w] : 0u;
+    const uint32_t pre_frame = tid < owned ? m.frames[tid] : 0u;
     for (int s = tid; s < m.max_seqs; s += NT) s_cur[s] = m.row_len[s];
     if (tid == 0) s_fail = 0x7fffffff;
     __syncthreads();
     const int T = m.page_tokens;
     int total = 0;
-    for (int c0 = 0; c0 < n; c0 += NT) {
+    for (int c0 = 0, ci = 0; c0 < n; c0 += NT, ++ci) {
         const int i = c0 + tid;
         int seq = -1, want = 0;
         if (i < n) {
-            const int s_ = ops[i], c = ops[n + i];
+            int s_ = 0, c = 0;
+#pragma unroll
+            for (int k = 0; k < CHUNKS; ++k)              // (static indices: the lists stay in registers)
+                if (k == ci) { s_ = o_seq[k]; c = o_ctx[k]; }
             if (s_ < 0 || s_ >= m.max_seqs || c < 0) {
                 atomicMin(&s_fail, i * 2);                       // the first refused entry decides the code
             } else {
@@ -233,28 +253,35 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
     __syncthreads();
     int status = 0;
     if (s_fail != 0x7fffffff) status = (s_fail & 1) ? PKV_E_RANGE : PKV_E_ARG;
-    else if ((int64_t)total > m.counters[1]) status = PKV_E_BALLOON;
+    else if ((int64_t)total > spare) status = PKV_E_BALLOON;
     if (status != 0 || total == 0) {
         if (tid == 0) book_finish(res, err, status);
         return;
     }
-    const int64_t owned = m.counters[0];
-    const int wpf = m.wpf, slots = m.slots;
     int running = 0;
     for (int64_t base = 0; base < owned && running < total; base += NT) {
         const int64_t i = base + tid;
+        const bool pre = base == 0 && wpf <= PRE_WORDS;      // this pass's words are already here
         int zeros = 0;
         if (i < owned) {
             for (int w = 0; w < wpf; ++w) {
                 const int nb = slots - 32 * w;
                 const uint32_t valid = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                zeros += __popc(~m.bits[i * wpf + w] & valid);
+                uint32_t word = 0u;
+                if (pre) {
+#pragma unroll
+                    for (int k = 0; k < PRE_WORDS; ++k)
+                        if (k == w) word = pre_bits[k];
+                } else {
+                    word = m.bits[i * wpf + w];
+                }
+                zeros += __popc(~word & valid);
             }
         }
         int chunk_total;
         int r = running + block_excl_scan(zeros, chunk_total, s_wave);
         if (zeros && r < total) {
-            const uint32_t f = m.frames[i];
+            const uint32_t f = base == 0 ? pre_frame : m.frames[i];
             int lo = 0, hi = n;                      // last entry with s_start <= r
             while (hi - lo > 1) {
                 const int mid = (lo + hi) >> 1;
@@ -263,7 +290,14 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
             for (int w = 0; w < wpf && r < total; ++w) {
                 const int nb = slots - 32 * w;
                 const uint32_t valid = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                uint32_t word = m.bits[i * wpf + w];
+                uint32_t word = 0u;
+                if (pre) {
+#pragma unroll
+                    for (int k = 0; k < PRE_WORDS; ++k)
+                        if (k == w) word = pre_bits[k];
+                } else {
+                    word = m.bits[i * wpf + w];
+                }
                 uint32_t freeb = ~word & valid;
                 while (freeb && r < total) {
                     const int b = __ffs(freeb) - 1;
@@ -283,7 +317,7 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
     __syncthreads();
     for (int s = tid; s < m.max_seqs; s += NT) m.row_len[s] = s_cur[s];
     if (tid == 0) {
-        m.counters[1] -= total;
+        m.counters[1] = spare - total;
         book_finish(res, err, total);
     }
 }
@@ -317,17 +351,35 @@ __global__ __launch_bounds__(NT) void k_release(PoolDev p, ModelDev m, int n, co
     }
     if (tid == 0) s_start[n] = total;
     __syncthreads();
-    for (int x = tid; x < total; x += NT) {
-        int lo = 0, hi = n;                              // last entry with s_start <= x
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (s_start[mid] <= x) lo = mid; else hi = mid;
+    // Every block costs two dependent reads (its id in the row, then the list position of its frame)
+    // before its bit can be cleared; a lane takes RELEASE_BATCH blocks at a time and issues each kind of
+    // read for all of them before it needs the first answer, so a pass costs two memory round trips.
+    constexpr int RELEASE_BATCH = 8;
+    for (int x0 = 0; x0 < total; x0 += NT * RELEASE_BATCH) {
+        uint32_t id[RELEASE_BATCH];
+        int64_t at[RELEASE_BATCH];
+#pragma unroll
+        for (int u = 0; u < RELEASE_BATCH; ++u) {
+            const int x = x0 + u * NT + tid;
+            id[u] = 0xffffffffu;
+            if (x < total) {
+                int lo = 0, hi = n;                      // last entry with s_start <= x
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_start[mid] <= x) lo = mid; else hi = mid;
+                }
+                id[u] = (uint32_t)m.rows[(int64_t)s_seq[lo] * m.max_blocks + (x - s_start[lo])];
+            }
         }
-        const int seq = s_seq[lo], b = x - s_start[lo];
-        const uint32_t id = (uint32_t)m.rows[(int64_t)seq * m.max_blocks + b];
-        const uint32_t f = id / (uint32_t)m.slots, s = id % (uint32_t)m.slots;
-        const int64_t at = p.pos[f];
-        atomicAnd(&m.bits[at * m.wpf + (s >> 5)], ~(1u << (s & 31)));
+#pragma unroll
+        for (int u = 0; u < RELEASE_BATCH; ++u)
+            at[u] = id[u] != 0xffffffffu ? p.pos[id[u] / (uint32_t)m.slots] : 0;
+#pragma unroll
+        for (int u = 0; u < RELEASE_BATCH; ++u)
+            if (id[u] != 0xffffffffu) {
+                const uint32_t sl = id[u] % (uint32_t)m.slots;
+                atomicAnd(&m.bits[at[u] * m.wpf + (sl >> 5)], ~(1u << (sl & 31)));
+            }
     }
     __syncthreads();
     for (int i = tid; i < n; i += NT)
