@@ -241,6 +241,21 @@ __device__ __forceinline__ void split_p(const float *p, u32x2 &hi, u32x2 &lo) {
     lo = mk2(pack_bf16_rne(l0, l1), pack_bf16_rne(l2, l3));
 }
 
+// Largest of three in one instruction.  Written out because the compiler puts a quieting instruction in
+// front of every matrix-unit result that it takes a maximum of.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// How far (in powers of two) a column's maximum may run ahead of the reference point of its
+// exponentials before a softmax step moves that point and rescales the column's sums.  The reference
+// point need not be the true maximum, only near it: results are the same up to rounding (probabilities
+// up to 2^kRescaleSlack instead of 1, numerator and denominator alike), and the 32 multiplications of a
+// rescale become rare.
+constexpr float kRescaleSlack = 8.f;
+
 // One online-softmax step over the 32 tokens of a page pair.  valid_a is 1..16,
 // valid_b 0..16 (0: the pair has no second page; its registers hold zeros).
 // TAIL: 0 = whether the pair needs masks is decided at run time inside (one code path with
@@ -271,7 +286,9 @@ __device__ __forceinline__ void process_pair(State<D, DT> &st, const PairRegs<D,
     float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
     mx = rows_max(mx);
     const float m_new = fmaxf(st.m, mx);
-    if (__any(m_new > st.m)) {            // wave-uniform: rescale only when some column's max moved
+    // wave-uniform: the reference point of the exponentials moves, and the sums are rescaled, only when some
+    // column's maximum has run ahead of it by more than kRescaleSlack (probabilities stay below 2^kRescaleSlack)
+    if (__any(m_new > st.m + kRescaleSlack)) {
         // a column that has seen no token yet (prefill tiles only) has m = -inf on both sides
         const float alpha = CAUSAL && TAIL != 1 && m_new == -INFINITY ? 1.0f : __builtin_amdgcn_exp2f(st.m - m_new);
         st.l *= alpha;
@@ -369,11 +386,14 @@ __device__ __forceinline__ void pair_softmax(State<D, DT> &st, const PairRegs<D,
             s[i] = sa[i];
             s[4 + i] = sb[i];
         }
-        mx = scale_log2 * fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+        mx = scale_log2 * max3(max3(s[0], s[1], s[2]), max3(s[3], s[4], s[5]), max3(s[6], s[7], s[0]));
     }
+    // The reference point of the exponentials need not be the true maximum, only near it: it moves (and
+    // the sums are rescaled) when some column's maximum has grown by more than kRescaleSlack, so that
+    // probabilities stay below 2^kRescaleSlack.  Wave-uniform.
     mx = rows_max(mx);
     const float m_new = fmaxf(st.m, mx);
-    if (__any(m_new > st.m)) {
+    if (__any(m_new > st.m + kRescaleSlack)) {
         const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
         st.l *= alpha;
 #pragma unroll
