@@ -146,3 +146,52 @@ def test_few_queries_in_front_of_long_contexts(gpu, oracle, hq, hkv, d, dtype):
         assert err <= TOL[dtype], (shrink, err)
     assert gpu.device_errors() == 0
     t.close()
+
+
+@pytest.mark.parametrize("d,dtype", [(128, BF16), (64, BF16), (128, E4M3)])
+def test_scores_that_rise_and_fall_along_the_context(gpu, oracle, d, dtype):
+    """Keys along a fixed direction with a length that grows (or shrinks) with the token's position: the
+    logits of a query head ramp up or down along the context, depending on the sign of its component in
+    that direction, by a little per page pair in one sequence (the running maximum creeps: the reference
+    point of the exponentials lags behind it by design and is moved only now and then), by more than the
+    allowed lag per pair in another (it moves in every step), and not at all in a third.  Decode and
+    chunked prefill against the oracle."""
+    import torch
+    hq, hkv = 16, 4
+    ctx = [1500, 700, 900, 333]
+    slope = [0.1, 0.6, 0.0, -0.3]                       # growth of a key's length per token
+    t = Twin(gpu, oracle, hq, hkv, d, dtype, ctx, max_blocks=96)
+    g = gen.generator(91, d, dtype)
+    e = torch.randn((hkv, d), generator=g)
+    e = e / e.norm(dim=-1, keepdim=True)
+    for s, (c, sl) in enumerate(zip(ctx, slope)):
+        pos = torch.arange(c, dtype=torch.float32)
+        length = (sl * pos if sl >= 0 else -sl * (c - pos))[:, None, None]
+        k = length * e[None] * (d ** 0.5) / 4 + 0.05 * torch.randn((c, hkv, d), generator=g)
+        v = torch.randn((c, hkv, d), generator=g)
+        if dtype == BF16:
+            kb, vb, ks, vs = gen.to_bf16_bits(k), gen.to_bf16_bits(v), None, None
+        else:
+            (kb, ks), (vb, vs) = gen.quantise_e4m3(k, 16), gen.quantise_e4m3(v, 16)
+        for be, m in zip(t.be, t.models):
+            assert be.kv_write(m, s, 0, kb, vb, ks, vs) == c
+    # decode: one query per sequence; prefill: the last 40 tokens of every sequence as a chunk
+    q = gen.queries((92, d), len(ctx), hq, d)
+    cl = np.array(ctx, dtype=np.int32)
+    for form in (0, 1):
+        assert gpu.set_kernel_form(form) == 0
+        rc_g, out_g = gpu.decode_attention(t.models[0], q, cl)
+        rc_o, out_o = oracle.decode_attention(t.models[1], q, cl)
+        assert rc_g == 0 and rc_o == 0
+        err = row_rel_err(out_g, out_o)
+        assert err <= TOL[dtype], (form, err)
+    gpu.set_kernel_form(-1)
+    qlen = [40] * len(ctx)
+    qp = gen.queries((93, d), sum(qlen), hq, d)
+    rc_g, out_g = gpu.prefill_attention(t.models[0], qp, qlen, ctx)
+    rc_o, out_o = oracle.prefill_attention(t.models[1], qp, qlen, ctx)
+    assert rc_g == 0 and rc_o == 0
+    err = row_rel_err(out_g, out_o)
+    assert err <= TOL[dtype], err
+    assert gpu.device_errors() == 0
+    t.close()
