@@ -75,6 +75,7 @@ struct Model {
     int64_t owned = 0;                      // shadow of the device counter
     int64_t used_blocks = 0;
     std::vector<int32_t> row_len;           // shadow
+    std::vector<int32_t> list_max;          // scratch of enqueue_reserve, all zero between calls
     // The shadows follow the calls as if each had succeeded in full.  After an enqueue-only bookkeeping
     // call nobody has looked at the outcome yet: the shadows are then estimates (good for sizing a
     // launch) until reconcile() has read the device's own counts back.
@@ -133,7 +134,7 @@ struct Ticket {
     hipStream_t stream = nullptr;
 };
 BookResult *g_res = nullptr;       // pinned host, [kTickets]
-int32_t *g_ops = nullptr;          // pinned host, [kTickets][2 * PKV_MAX_BATCH_OPS]
+int32_t *g_ops = nullptr;          // pinned host, [kTickets][3 * PKV_MAX_BATCH_OPS]
 Ticket g_tickets[kTickets];
 long g_next_ticket = 0;
 uint32_t *g_err = nullptr;         // device error flags
@@ -194,7 +195,7 @@ int lib_init() {
     if (g_res) return PKV_OK;
     HIP_TRY(hipHostMalloc((void **)&g_res, sizeof(BookResult) * kTickets, hipHostMallocDefault));
     for (int i = 0; i < kTickets; ++i) g_res[i].value = 0;
-    HIP_TRY(hipHostMalloc((void **)&g_ops, sizeof(int32_t) * 2 * PKV_MAX_BATCH_OPS * kTickets, hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc((void **)&g_ops, sizeof(int32_t) * 3 * PKV_MAX_BATCH_OPS * kTickets, hipHostMallocDefault));
     HIP_TRY(hipMalloc((void **)&g_err, sizeof(uint32_t)));
     HIP_TRY(hipMemset(g_err, 0, sizeof(uint32_t)));
     HIP_TRY(hipMalloc(&g_safe, 16384));
@@ -220,7 +221,7 @@ int take_ticket() {
     return slot;
 }
 
-int32_t *ticket_ops(int slot) { return g_ops + (size_t)slot * 2 * PKV_MAX_BATCH_OPS; }
+int32_t *ticket_ops(int slot) { return g_ops + (size_t)slot * 3 * PKV_MAX_BATCH_OPS; }
 int ticket_handle(int slot) { return (int)(g_tickets[slot].id & 0x7fffffff); }
 
 // a call that was refused before anything was enqueued still gets a (finished) ticket
@@ -1292,6 +1293,18 @@ static int enqueue_reserve(Model &m, int n, const int32_t *seqs, const int32_t *
     int32_t *ops = ticket_ops(slot);
     memcpy(ops, seqs, sizeof(int32_t) * n);
     memcpy(ops + n, ctx_lens, sizeof(int32_t) * n);
+    // What an entry's row holds before it, as far as the list alone decides: the largest want among the
+    // earlier entries of the same sequence (the list has passed check_reserve_list).  The kernel takes the
+    // larger of this and the row's length on the device, which leaves it nothing to order among entries.
+    int32_t *earlier = ops + 2 * n;
+    if (m.list_max.size() < (size_t)m.dev.max_seqs) m.list_max.assign((size_t)m.dev.max_seqs, 0);
+    for (int i = 0; i < n; ++i) {
+        const int want = (int)(((int64_t)ctx_lens[i] + p.T - 1) / p.T);
+        int32_t &seen = m.list_max[(size_t)seqs[i]];
+        earlier[i] = seen;
+        if (want > seen) seen = want;
+    }
+    for (int i = 0; i < n; ++i) m.list_max[(size_t)seqs[i]] = 0;
     hipError_t e = pkv_launch_reserve(p.dev, m.dev, n, ops, &g_res[slot], sticky ? g_err : nullptr, g_stream);
     if (e != hipSuccess) g_res[slot].value = fail_hip(e, "seq_reserve_batch launch");
     return slot;

@@ -124,7 +124,8 @@ struct AttnGroup {
 hipError_t pkv_launch_pool_init(const PoolDev &p, const uint32_t *perm_dev, hipStream_t s);
 // Bookkeeping kernels: the result goes to *res (pinned host memory); a refused call also sets bit 2 of *err.
 hipError_t pkv_launch_resize(const PoolDev &p, const ModelDev &m, int64_t target, BookResult *res, uint32_t *err, hipStream_t s);
-// ops: pinned host memory, n sequence ids then n context lengths (n <= PKV_MAX_BATCH_OPS)
+// ops: pinned host memory, n sequence ids, n context lengths, then per entry the largest want (blocks) among
+// the earlier entries of its sequence in the list (n <= PKV_MAX_BATCH_OPS)
 hipError_t pkv_launch_reserve(const PoolDev &p, const ModelDev &m, int n, const int32_t *ops, BookResult *res, uint32_t *err,
                               hipStream_t s);
 // ops: pinned host memory, n sequence ids (n <= PKV_MAX_SEQS)

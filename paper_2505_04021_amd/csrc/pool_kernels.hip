@@ -15,6 +15,11 @@ namespace {
 constexpr int NT = PKV_BOOK_THREADS;
 constexpr int NW = NT / 64;
 
+// Work-group barrier for exchanges through LDS only: it waits for this wave's LDS traffic, not for its
+// global stores to be acknowledged (__syncthreads does, and a store's round trip costs about as much as
+// everything else such a kernel does between two barriers).
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Exclusive prefix sum of one int per lane over the work-group; `total` is uniform.
 __device__ inline int block_excl_scan(int v, int &total, int *s_wave) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -175,71 +180,74 @@ __global__ __launch_bounds__(NT) void k_resize(PoolDev p, ModelDev m, int64_t ta
 // times (the growth rounds of an admission in one call): entry i then needs what its
 // row lacks after the earlier entries, i.e. its want minus the largest want among the
 // earlier entries of the same sequence (and the row's length before the call).
-// ops: host (pinned) memory, n sequence ids then n context lengths.
+// ops: host (pinned) memory, n sequence ids, then n context lengths, then for each entry the largest want
+// (in blocks) among the earlier entries of its sequence in this list, 0 if there is none.
 __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, const int32_t *ops, BookResult *res, uint32_t *err) {
     __shared__ int s_wave[NW];
     __shared__ int s_cur[PKV_MAX_SEQS];             // row length after the entries walked so far
     __shared__ int s_start[PKV_MAX_BATCH_OPS + 1];  // first rank of entry i
     __shared__ uint32_t s_ent[PKV_MAX_BATCH_OPS];   // entry i: sequence << 20 | row length before the entry
+    __shared__ uint32_t s_free[NT], s_fid[NT];      // placement: free bits of frame j's current word, its frame id
+    __shared__ int s_rank[NT];                      // placement: rank of the first free slot of that word
     __shared__ int s_fail;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x;
     // Everything the kernel will read is asked for here, before the first answer is needed: the list
     // (host memory, the longest trip), the rows' lengths, the counters and the lane's own frame of the
     // first pass of the placement.  The call then costs one such trip instead of five in a row.
     constexpr int CHUNKS = PKV_MAX_BATCH_OPS / NT, PRE_WORDS = 4;
-    int o_seq[CHUNKS], o_ctx[CHUNKS];
+    int o_seq[CHUNKS], o_ctx[CHUNKS], o_ear[CHUNKS];
 #pragma unroll
     for (int c = 0; c < CHUNKS; ++c) {
         const int i = c * NT + tid;
         o_seq[c] = i < n ? ops[i] : 0;
         o_ctx[c] = i < n ? ops[n + i] : 0;
+        o_ear[c] = i < n ? ops[2 * n + i] : 0;
     }
     const int64_t owned = m.counters[0], spare = m.counters[1];
     const int wpf = m.wpf, slots = m.slots;
     uint32_t pre_bits[PRE_WORDS];
 #pragma unroll
-    for (int w = 0; w < PRE_WORDS; ++w) pre_bits[w] = (tid < owned && w < wpf) ? m.bits[(int64_t)tid * wpf + w] : 0u;
-    const uint32_t pre_frame = tid < owned ? m.frames[tid] : 0u;
+    // (list positions the model does not own yet are read too, and never looked at: the address then does
+    // not wait for the count of owned frames to arrive)
+    for (int w = 0; w < PRE_WORDS; ++w) pre_bits[w] = (tid < p.n_frames && w < wpf) ? m.bits[(int64_t)tid * wpf + w] : 0u;
+    const uint32_t pre_frame = tid < p.n_frames ? m.frames[tid] : 0u;
     for (int s = tid; s < m.max_seqs; s += NT) s_cur[s] = m.row_len[s];
     if (tid == 0) s_fail = 0x7fffffff;
     __syncthreads();
     const int T = m.page_tokens;
-    int total = 0;
-    for (int c0 = 0, ci = 0; c0 < n; c0 += NT, ++ci) {
-        const int i = c0 + tid;
-        int seq = -1, want = 0;
-        if (i < n) {
-            int s_ = 0, c = 0;
+    // Row length before an entry = the larger of the row's length when the call began and the largest want
+    // among the earlier entries of its sequence.  The second is a property of the list alone and comes
+    // with it; the first is read here, for every entry, before any entry's want reaches s_cur.
+    int e_seq[CHUNKS], e_want[CHUNKS], e_prev[CHUNKS];
 #pragma unroll
-            for (int k = 0; k < CHUNKS; ++k)              // (static indices: the lists stay in registers)
-                if (k == ci) { s_ = o_seq[k]; c = o_ctx[k]; }
-            if (s_ < 0 || s_ >= m.max_seqs || c < 0) {
+    for (int c = 0; c < CHUNKS; ++c) {
+        const int i = c * NT + tid;
+        e_seq[c] = -1;
+        e_want[c] = e_prev[c] = 0;
+        if (i < n) {
+            const int s_ = o_seq[c], cl = o_ctx[c];
+            if (s_ < 0 || s_ >= m.max_seqs || cl < 0) {
                 atomicMin(&s_fail, i * 2);                       // the first refused entry decides the code
             } else {
-                const int64_t w = ((int64_t)c + T - 1) / T;
+                const int64_t w = ((int64_t)cl + T - 1) / T;
                 if (w > m.max_blocks) atomicMin(&s_fail, i * 2 + 1);
-                else { seq = s_; want = (int)w; }
+                else {
+                    e_seq[c] = s_;
+                    e_want[c] = (int)w;
+                    const int before = s_cur[s_];
+                    e_prev[c] = before > o_ear[c] ? before : o_ear[c];
+                }
             }
         }
-        // Row length before each entry = the largest want among the earlier entries of its sequence, or
-        // the row's length when the call began.  First every wave looks, for its own 64 entries at once,
-        // at the earlier entries of the same wave through lane reads; then the waves go one after the
-        // other: each reads what the earlier waves (and chunks) left in s_cur and leaves its own wants.
-        int prev = 0;
+    }
+    __syncthreads();
+    int total = 0;
 #pragma unroll
-        for (int k = 0; k < 63; ++k) {
-            const int sk = __builtin_amdgcn_readlane(seq, k), wk = __builtin_amdgcn_readlane(want, k);
-            if (k < lane && sk == seq && wk > prev) prev = wk;
-        }
-        const int live_waves = ((n - c0 < NT ? n - c0 : NT) + 63) >> 6;
-        for (int w = 0; w < live_waves; ++w) {
-            if (w == wave && seq >= 0) {
-                const int before = s_cur[seq];
-                prev = before > prev ? before : prev;
-                atomicMax(&s_cur[seq], want);
-            }
-            __syncthreads();
-        }
+    for (int c = 0; c < CHUNKS; ++c) {
+        const int c0 = c * NT, i = c0 + tid;
+        if (c0 >= n) break;                                      // uniform
+        const int seq = e_seq[c], want = e_want[c], prev = e_prev[c];
+        if (seq >= 0) atomicMax(&s_cur[seq], want);              // the row's length after the call
         const int need = (seq >= 0 && want > prev) ? want - prev : 0;
         int chunk_total;
         const int excl = block_excl_scan(need, chunk_total, s_wave);
@@ -258,58 +266,86 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
         if (tid == 0) book_finish(res, err, status);
         return;
     }
+    // Placement.  Free slots are ranked in frame-list order, ascending slot inside a frame; rank r goes to
+    // the entry e with s_start[e] <= r < s_start[e + 1].  A lane per frame counts the frame's free slots (a
+    // prefix sum gives the rank of its first one) and publishes one 32-slot word at a time; then a lane per
+    // (frame, slot) of that word takes over: a free slot knows its rank from the bits below it, finds its
+    // entry by binary search and writes the row.  The frame's lane sets the bits that were taken.
     int running = 0;
     for (int64_t base = 0; base < owned && running < total; base += NT) {
         const int64_t i = base + tid;
         const bool pre = base == 0 && wpf <= PRE_WORDS;      // this pass's words are already here
+        auto word_of = [&](int w) {
+            uint32_t word = 0u;
+            if (pre) {
+#pragma unroll
+                for (int k = 0; k < PRE_WORDS; ++k)
+                    if (k == w) word = pre_bits[k];
+            } else {
+                word = m.bits[i * wpf + w];
+            }
+            return word;
+        };
+        auto valid_of = [&](int w) {
+            const int nb = slots - 32 * w;
+            return nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
+        };
         int zeros = 0;
-        if (i < owned) {
-            for (int w = 0; w < wpf; ++w) {
-                const int nb = slots - 32 * w;
-                const uint32_t valid = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                uint32_t word = 0u;
-                if (pre) {
-#pragma unroll
-                    for (int k = 0; k < PRE_WORDS; ++k)
-                        if (k == w) word = pre_bits[k];
-                } else {
-                    word = m.bits[i * wpf + w];
-                }
-                zeros += __popc(~word & valid);
-            }
-        }
+        if (i < owned)
+            for (int w = 0; w < wpf; ++w) zeros += __popc(~word_of(w) & valid_of(w));
         int chunk_total;
-        int r = running + block_excl_scan(zeros, chunk_total, s_wave);
-        if (zeros && r < total) {
-            const uint32_t f = base == 0 ? pre_frame : m.frames[i];
-            int lo = 0, hi = n;                      // last entry with s_start <= r
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (s_start[mid] <= r) lo = mid; else hi = mid;
+        int rank0 = running + block_excl_scan(zeros, chunk_total, s_wave);    // rank of this frame's first free slot
+        const uint32_t f = i < owned ? (base == 0 ? pre_frame : m.frames[i]) : 0u;
+        const int nf = (int)(owned - base < NT ? owned - base : NT);
+        for (int w = 0; w < wpf; ++w) {
+            const bool mine = i < owned && zeros && rank0 < total;
+            const uint32_t word = mine ? word_of(w) : 0u;
+            const uint32_t freeb = mine ? ~word & valid_of(w) : 0u;
+            s_free[tid] = freeb;
+            s_rank[tid] = rank0;
+            s_fid[tid] = f;
+            lds_barrier();
+            for (int idx = tid; idx < nf * 32; idx += NT) {
+                const int j = idx >> 5, bit = idx & 31;
+                const uint32_t fr = s_free[j];
+                if (!((fr >> bit) & 1u)) continue;
+                const int r = s_rank[j] + __popc(fr & ((1u << bit) - 1u));
+                if (r >= total) continue;
+                // last entry with s_start <= r: three pivots a step (their reads travel together), then halves
+                int lo = 0, hi = n;
+                while (hi - lo > 3) {
+                    const int q = (hi - lo) >> 2;
+                    const int m1 = lo + q, m2 = m1 + q, m3 = m2 + q;
+                    const int a1 = s_start[m1], a2 = s_start[m2], a3 = s_start[m3];
+                    if (a3 <= r) lo = m3;
+                    else if (a2 <= r) { lo = m2; hi = m3; }
+                    else if (a1 <= r) { lo = m1; hi = m2; }
+                    else hi = m1;
+                }
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (s_start[mid] <= r) lo = mid; else hi = mid;
+                }
+                const uint32_t ent = s_ent[lo];
+                m.rows[(int64_t)(ent >> 20) * m.max_blocks + (ent & 0xfffffu) + (r - s_start[lo])] =
+                    (int32_t)(s_fid[j] * (uint32_t)slots + (uint32_t)(32 * w + bit));
             }
-            for (int w = 0; w < wpf && r < total; ++w) {
-                const int nb = slots - 32 * w;
-                const uint32_t valid = nb >= 32 ? 0xffffffffu : ((1u << nb) - 1u);
-                uint32_t word = 0u;
-                if (pre) {
-#pragma unroll
-                    for (int k = 0; k < PRE_WORDS; ++k)
-                        if (k == w) word = pre_bits[k];
-                } else {
-                    word = m.bits[i * wpf + w];
+            lds_barrier();
+            if (freeb) {
+                const int c = __popc(freeb);
+                int take = total - rank0;
+                take = take > c ? c : take;
+                uint32_t mask = freeb;                   // the lowest `take` free bits
+                if (take < c) {
+                    mask = 0u;
+                    uint32_t rest = freeb;
+                    for (int k = 0; k < take; ++k) {
+                        mask |= rest & (0u - rest);
+                        rest &= rest - 1u;
+                    }
                 }
-                uint32_t freeb = ~word & valid;
-                while (freeb && r < total) {
-                    const int b = __ffs(freeb) - 1;
-                    freeb &= freeb - 1;
-                    while (s_start[lo + 1] <= r) ++lo;   // ranks rise by one: walk forward
-                    const uint32_t ent = s_ent[lo];
-                    m.rows[(int64_t)(ent >> 20) * m.max_blocks + (ent & 0xfffffu) + (r - s_start[lo])] =
-                        (int32_t)(f * (uint32_t)slots + (uint32_t)(32 * w + b));
-                    word |= 1u << b;
-                    ++r;
-                }
-                m.bits[i * wpf + w] = word;
+                m.bits[i * wpf + w] = word | mask;
+                rank0 += c;
             }
         }
         running += chunk_total;
@@ -322,6 +358,8 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
     }
 }
 
+constexpr int RELEASE_WIN = 6144;      // words of a model's slot bitmap that k_release collects in LDS at a time
+
 // release (batched): clear the slot bits of every block of the listed rows; the same state as single
 // releases in order (a sequence listed twice is empty the second time).
 // ops: host (pinned) memory, n sequence ids, checked by the host.
@@ -329,6 +367,7 @@ __global__ __launch_bounds__(NT) void k_release(PoolDev p, ModelDev m, int n, co
     __shared__ int s_wave[NW];
     __shared__ int s_start[PKV_MAX_SEQS + 1];
     __shared__ int s_seq[PKV_MAX_SEQS];
+    __shared__ uint32_t s_win[RELEASE_WIN];
     const int tid = threadIdx.x;
     for (int i = tid; i < n; i += NT) {
         const int s_ = ops[i];
@@ -354,32 +393,48 @@ __global__ __launch_bounds__(NT) void k_release(PoolDev p, ModelDev m, int n, co
     // Every block costs two dependent reads (its id in the row, then the list position of its frame)
     // before its bit can be cleared; a lane takes RELEASE_BATCH blocks at a time and issues each kind of
     // read for all of them before it needs the first answer, so a pass costs two memory round trips.
+    // The bits to clear are collected in LDS, a window of WIN words of the model's slot bitmap at a
+    // time (one window covers the bitmap of all but very large models), and each word that lost bits is
+    // then rewritten once by one lane: thirty atomics on the same word in memory cost more than the
+    // rest of the kernel.
     constexpr int RELEASE_BATCH = 8;
-    for (int x0 = 0; x0 < total; x0 += NT * RELEASE_BATCH) {
-        uint32_t id[RELEASE_BATCH];
-        int64_t at[RELEASE_BATCH];
+    const int64_t words_total = m.counters[0] * m.wpf;
+    for (int64_t win0 = 0; win0 < words_total && total > 0; win0 += RELEASE_WIN) {
+        for (int i = tid; i < RELEASE_WIN; i += NT) s_win[i] = 0u;
+        lds_barrier();
+        for (int x0 = 0; x0 < total; x0 += NT * RELEASE_BATCH) {
+            uint32_t id[RELEASE_BATCH];
+            int64_t at[RELEASE_BATCH];
 #pragma unroll
-        for (int u = 0; u < RELEASE_BATCH; ++u) {
-            const int x = x0 + u * NT + tid;
-            id[u] = 0xffffffffu;
-            if (x < total) {
-                int lo = 0, hi = n;                      // last entry with s_start <= x
-                while (hi - lo > 1) {
-                    const int mid = (lo + hi) >> 1;
-                    if (s_start[mid] <= x) lo = mid; else hi = mid;
+            for (int u = 0; u < RELEASE_BATCH; ++u) {
+                const int x = x0 + u * NT + tid;
+                id[u] = 0xffffffffu;
+                if (x < total) {
+                    int lo = 0, hi = n;                      // last entry with s_start <= x
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        if (s_start[mid] <= x) lo = mid; else hi = mid;
+                    }
+                    id[u] = (uint32_t)m.rows[(int64_t)s_seq[lo] * m.max_blocks + (x - s_start[lo])];
                 }
-                id[u] = (uint32_t)m.rows[(int64_t)s_seq[lo] * m.max_blocks + (x - s_start[lo])];
             }
+#pragma unroll
+            for (int u = 0; u < RELEASE_BATCH; ++u)
+                at[u] = id[u] != 0xffffffffu ? p.pos[id[u] / (uint32_t)m.slots] : 0;
+#pragma unroll
+            for (int u = 0; u < RELEASE_BATCH; ++u)
+                if (id[u] != 0xffffffffu) {
+                    const uint32_t sl = id[u] % (uint32_t)m.slots;
+                    const int64_t word = at[u] * m.wpf + (sl >> 5) - win0;
+                    if (word >= 0 && word < RELEASE_WIN) atomicOr(&s_win[word], 1u << (sl & 31));
+                }
         }
-#pragma unroll
-        for (int u = 0; u < RELEASE_BATCH; ++u)
-            at[u] = id[u] != 0xffffffffu ? p.pos[id[u] / (uint32_t)m.slots] : 0;
-#pragma unroll
-        for (int u = 0; u < RELEASE_BATCH; ++u)
-            if (id[u] != 0xffffffffu) {
-                const uint32_t sl = id[u] % (uint32_t)m.slots;
-                atomicAnd(&m.bits[at[u] * m.wpf + (sl >> 5)], ~(1u << (sl & 31)));
-            }
+        lds_barrier();
+        for (int i = tid; i < RELEASE_WIN && win0 + i < words_total; i += NT) {
+            const uint32_t gone = s_win[i];
+            if (gone) m.bits[win0 + i] &= ~gone;
+        }
+        lds_barrier();
     }
     __syncthreads();
     for (int i = tid; i < n; i += NT)

@@ -259,6 +259,44 @@ def test_balloon_exhaustion_and_clamp(gpu, oracle):
         assert be.pool_destroy(pool) == 0
 
 
+def test_bookkeeping_over_many_frames(gpu, oracle):
+    """A model that owns thousands of frames (one block per frame, a slot bitmap of 8000 words: more than the
+    release kernel collects in LDS at a time) and reserve lists in which sequences come back many times:
+    return values and state images equal to the oracle's after every call."""
+    rng = np.random.default_rng(5)
+    n_seq, rounds = 50, 22
+    ctx = rng.integers(16 * 100, 16 * 170, n_seq)
+    seqs, wants = [], []
+    for r in range(rounds):                                  # growth rounds of 8 blocks, sequences shuffled
+        live = np.nonzero(ctx > r * 128)[0]
+        live = live[rng.permutation(len(live))]
+        seqs += list(live)
+        wants += list(np.minimum(ctx[live], (r + 1) * 128))
+    half = [int(x) for x in rng.permutation(n_seq)[: n_seq // 2]]
+    res, pools = [], []
+    for be in (gpu, oracle):
+        pool = be.pool_create(512 << 20, 16, 64 << 10)       # 8192 frames of 64 KiB
+        assert be.pool_seed_free_order(pool, gen.free_order(8192, gen.generator(44))) == 0
+        a = be.model_register(pool, 32, 8, 128, BF16, n_seq, 176)    # 64 KiB blocks: one slot per frame
+        pools.append((be, pool, a))
+        r = [be.balloon_resize(a, 8000)]
+        for lo in range(0, len(seqs), 4096):
+            r.append(be.seq_reserve_batch(a, seqs[lo:lo + 4096], wants[lo:lo + 4096]))
+        res.append(r)
+    assert res[0] == res[1] and res[0][1] > 6144, res
+    check_invariants(parse(assert_same_state(gpu, oracle, pools[0][1], pools[1][1], "after the reserves")))
+    for step, batch in enumerate((half, half[:3] + [s for s in range(n_seq) if s not in half])):
+        out = [be.seq_release_batch(a, batch) for be, _, a in pools]
+        assert out[0] == out[1], (step, out)
+        check_invariants(parse(assert_same_state(gpu, oracle, pools[0][1], pools[1][1], f"after release {step}")))
+        if step == 0:                                        # the freed frames are found and given back
+            out = [be.balloon_resize(a, 0) for be, _, a in pools]
+            assert out[0] == out[1] and 0 < out[0] < 8000, out
+            assert_same_state(gpu, oracle, pools[0][1], pools[1][1], "after the deflate")
+    for be, pool, a in pools:
+        assert be.balloon_resize(a, 0) == 0 and be.model_unregister(a) == 0 and be.pool_destroy(pool) == 0
+
+
 def test_bookkeeping_is_deterministic(gpu, oracle):
     """The same scenario twice on the GPU gives byte-identical state images."""
     cfg = make_config(3, "small")
