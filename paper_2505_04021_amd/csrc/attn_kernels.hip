@@ -1284,10 +1284,19 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
         const int vb = pa + 1 < n_pages ? (pa + 1 == n_pages - 1 ? last_valid : T) : 0;
         const bool pair_tail = va < T || vb < T || (pa + 2) * T > causal_from;       // wave-uniform
         const bool fast = all_mine && !pair_tail;
-        // Every wave has finished with pair p - 1 (barrier): its buffer takes the pair NBUF - 1 ahead.
-        // All waves of a CU reach this point together and the requests queue up behind each other;
-        // on the common path they are therefore issued further down, behind the first matrix
-        // instructions, which then run while the wave waits for its turn.
+        // The step's meeting point.  Before it, the wave's own requests for every pair up to p + 1 have
+        // landed (the one for p + 2 may still travel); behind it, every wave's have, and every wave has
+        // finished with pair p - 1: pair p + 1's K tiles may be read, and the buffer of pair p - 1 takes
+        // the pair NBUF - 1 ahead.  A step needs neither for its score matrices (their K operands were
+        // read a step ago), so on the common path the waves meet behind those: a wave that is ahead works
+        // instead of waiting, and the requests, which would otherwise queue up behind each other where all
+        // waves of a CU arrive together, are issued while the matrix instructions run.
+        auto meet = [&]() {
+            const int newest = p + PF_BUFS - 2 < p_end - 1 ? p + PF_BUFS - 2 : p_end - 1;
+            landed(newest - (p + 1));
+            __builtin_amdgcn_s_barrier();
+        };
+        if (!fast) meet();
         if (!fast && p + PF_BUFS - 1 < p_end) fetch(p + PF_BUFS - 1, refill);
         if (DT == PKV_E4M3 && any_mine) {
             const int last = d.row_stride - 1;
@@ -1321,6 +1330,7 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
                 for (int u = 0; u < NT; ++u) pair_qk<D, DT>(r, qf[u], sa[u], sb[u]);
             }
             __builtin_amdgcn_sched_barrier(0);        // the K registers are rewritten below: not before their last use is issued
+            meet();
             read_v(buf);
             if (next_mine) read_k(buf_next);
             if (p + PF_BUFS - 1 < p_end) fetch(p + PF_BUFS - 1, refill);
@@ -1350,11 +1360,6 @@ __device__ __forceinline__ void prefill_group(const AttnDesc &d, uint8_t *lds0, 
             __builtin_amdgcn_sched_barrier(0);
             if (next_mine) read_k(buf_next);
         }
-        // pair p + 2 must have landed before anybody reads its K tiles in the next step; the pair
-        // requested in this step may still travel
-        const int newest = p + PF_BUFS - 1 < p_end - 1 ? p + PF_BUFS - 1 : p_end - 1;
-        landed(newest - (p + 2));
-        __builtin_amdgcn_s_barrier();      // every read of this step's buffer has been consumed by then
     };
 
     // prologue: the first NBUF - 1 pairs are requested, the first two must have landed
