@@ -195,3 +195,24 @@ def test_scores_that_rise_and_fall_along_the_context(gpu, oracle, d, dtype):
     assert err <= TOL[dtype], err
     assert gpu.device_errors() == 0
     t.close()
+
+
+@pytest.mark.parametrize("dtype", [BF16, E4M3])
+def test_prefill_at_the_size_the_bench_times(gpu, oracle, dtype):
+    """The chunk of bench.py's prefill leg — 512 new tokens behind 2048 cached ones, 32 q heads, 8 kv heads,
+    128-wide heads, every group of 32 query tokens on the mask-free path for most of its context — for
+    three sequences (the bench has eight of the same kind), every output row against the oracle."""
+    from parity import elementwise_rel_err
+    hq, hkv, d, prefix, chunk = 32, 8, 128, 2048, 512
+    ctx = [prefix + chunk] * 3
+    qlen = [chunk] * 3
+    t = Twin(gpu, oracle, hq, hkv, d, dtype, ctx, max_blocks=(prefix + chunk) // 16, pool_bytes=256 << 20)
+    q = gen.queries((23, dtype), sum(qlen), hq, d)
+    rc_o, out_o = oracle.prefill_attention(t.models[1], q, qlen, ctx)
+    rc_g, out_g = gpu.prefill_attention(t.models[0], q, qlen, ctx)
+    assert rc_o == 0 and rc_g == 0
+    err = row_rel_err(out_g, out_o)
+    print(f"dtype {dtype}: worst row error {err:.3e}, floored per-element error {elementwise_rel_err(out_g, out_o):.3e}")
+    assert err <= TOL[dtype], err
+    assert gpu.device_errors() == 0
+    t.close()
