@@ -155,6 +155,74 @@ __device__ __forceinline__ void append_row_e4m3(uint8_t *tile, float *scale_p, i
     }
 }
 
+// Several consecutive K or V rows of one page of an e4m3 model (slots slot0 .. slot0 + n - 1), with the
+// same outcome, bit for bit, as append_row_e4m3 called for each in turn.  What those calls exchange
+// through memory — the block's scale, the codes of the slots before — is held on chip here: the new rows
+// and the codes the page already holds are fetched in one go, the rows are then taken in order (the scale
+// rule is sequential by definition) with the page's codes in LDS, and codes and scale are written once.
+// A lane only ever touches its own columns (lane and lane + 64), so the LDS arrays need no barrier.
+template <bool IS_V>
+__device__ __forceinline__ void append_rows_e4m3(uint8_t *tile, float *scale_p, int slot0, int n, int D, const uint16_t *x_bf16,
+                                                 size_t row_stride, int lane, float (*sx)[128], uint8_t (*sc)[128]) {
+    auto off = [&](int t, int dd) { return IS_V ? v_elem_off<PKV_E4M3>(t, dd) : k_elem_off<PKV_E4M3>(t, dd); };
+    for (int t = 0; t < n; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int dd = lane + 64 * i;
+            if (dd < D) sx[slot0 + t][dd] = bf16_bits_to_float(x_bf16[(size_t)t * row_stride + dd]);
+        }
+    float scale = 1.0f;
+    if (slot0 > 0) {
+        scale = *scale_p;
+        for (int t = 0; t < slot0; ++t)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int dd = lane + 64 * i;
+                if (dd < D) sc[t][dd] = tile[off(t, dd)];
+            }
+    }
+    int first_changed = slot0;                       // slots below it still hold what memory holds
+    for (int slot = slot0; slot < slot0 + n; ++slot) {
+        float x[2];
+        float amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int dd = lane + 64 * i;
+            x[i] = dd < D ? sx[slot][dd] : 0.f;
+            amax = fmaxf(amax, fabsf(x[i]));
+        }
+        amax = wave_max(amax);
+        const float cand = __fdiv_rn(amax, 448.0f);
+        if (slot == 0) {
+            scale = amax > 0.f ? cand : 1.0f;
+        } else if (cand > scale) {
+            for (int t = 0; t < slot; ++t)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int dd = lane + 64 * i;
+                    if (dd < D) {
+                        const float v = __fmul_rn(e4m3_decode(sc[t][dd]), scale);
+                        sc[t][dd] = (uint8_t)e4m3_encode(__fdiv_rn(v, cand));
+                    }
+                }
+            scale = cand;
+            first_changed = 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int dd = lane + 64 * i;
+            if (dd < D) sc[slot][dd] = (uint8_t)e4m3_encode(__fdiv_rn(x[i], scale));
+        }
+    }
+    if (lane == 0) *scale_p = scale;
+    for (int t = first_changed; t < slot0 + n; ++t)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int dd = lane + 64 * i;
+            if (dd < D) tile[off(t, dd)] = sc[t][dd];
+        }
+}
+
 // kv_append: one wave per (sequence, kv head).  Without a chunk list it writes the token with
 // index ctx_lens[seq] - 1 from row `seq` of k_new / v_new (bf16 [batch][Hkv][D]).  With one
 // (d.vmap: per unit {first row of the sequence's new tokens, their number, sequence, which of the
@@ -204,14 +272,55 @@ __global__ __launch_bounds__(64) void k_kv_append(AttnDesc d, const uint16_t *k_
         const size_t tile = (size_t)PKV_T * D * 2;
         uint16_t *kt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile);
         uint16_t *vt = reinterpret_cast<uint16_t *>(blk + (size_t)h * 2 * tile + tile);
-        const int n_el = (hi - lo) * D;
+        const size_t row0 = ((size_t)(first_row + (lo - tok0)) * d.Hkv + h) * D, stride = (size_t)d.Hkv * D;
+        const int s0 = lo % PKV_T, n = hi - lo;
+        if (n >= 4 && ((reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new)) & 15) == 0) {
+            // Several tokens of a chunk: whole 16-byte units.  A K unit is eight consecutive elements of
+            // one token's row, as in the source; a V unit holds four consecutive tokens of one element
+            // (8 bytes each for elements d and d + 16), gathered from four source rows.  Token groups the
+            // chunk covers only in part go element by element.
+            const int c8 = D >> 3;
+            for (int e = lane; e < n * c8; e += 64) {
+                const int t = e / c8, c = e - t * c8;
+                *reinterpret_cast<uint4 *>(kt + k_elem_off<PKV_BF16>(s0 + t, 8 * c)) =
+                    *reinterpret_cast<const uint4 *>(k_new + row0 + (size_t)t * stride + 8 * c);
+            }
+            for (int e = lane; e < 4 * D; e += 64) {
+                const int G = e / D, dd = e - G * D;
+                const int t_lo = 4 * G - s0;                       // the group's first token, counted from lo
+                if (t_lo >= 0 && t_lo + 4 <= n) {
+                    const uint16_t *src = v_new + row0 + (size_t)t_lo * stride + dd;
+                    const uint32_t a = src[0], b = src[stride], c = src[2 * stride], f = src[3 * stride];
+                    *reinterpret_cast<uint2 *>(vt + v_elem_off<PKV_BF16>(4 * G, dd)) = make_uint2(a | (b << 16), c | (f << 16));
+                } else {
+                    for (int k = 0; k < 4; ++k) {
+                        const int t = t_lo + k;
+                        if (t >= 0 && t < n) vt[v_elem_off<PKV_BF16>(4 * G + k, dd)] = v_new[row0 + (size_t)t * stride + dd];
+                    }
+                }
+            }
+            return;
+        }
+        const int n_el = n * D;
 #pragma unroll 4
         for (int e = lane; e < n_el; e += 64) {
-            const int t = e / D, dd = e - t * D, tok = lo + t;
-            const size_t src = ((size_t)(first_row + (tok - tok0)) * d.Hkv + h) * D + dd;
-            kt[k_elem_off<PKV_BF16>(tok % PKV_T, dd)] = k_new[src];
-            vt[v_elem_off<PKV_BF16>(tok % PKV_T, dd)] = v_new[src];
+            const int t = e / D, dd = e - t * D;
+            const size_t src = row0 + (size_t)t * stride + dd;
+            kt[k_elem_off<PKV_BF16>(s0 + t, dd)] = k_new[src];
+            vt[v_elem_off<PKV_BF16>(s0 + t, dd)] = v_new[src];
         }
+        return;
+    }
+    if (hi - lo > 1) {
+        // several tokens of a chunk in this page: in order, as single appends would, but in one pass
+        __shared__ float sx[PKV_T][128];
+        __shared__ uint8_t sc[PKV_T][128];
+        float *hdr = reinterpret_cast<float *>(blk);
+        const size_t tile = (size_t)PKV_T * D;
+        uint8_t *kt = blk + PKV_FP8_HEADER + (size_t)h * 2 * tile, *vt = kt + tile;
+        const size_t src = ((size_t)(first_row + (lo - tok0)) * d.Hkv + h) * D, stride = (size_t)d.Hkv * D;
+        append_rows_e4m3<false>(kt, hdr + h, lo % PKV_T, hi - lo, D, k_new + src, stride, lane, sx, sc);
+        append_rows_e4m3<true>(vt, hdr + d.Hkv + h, lo % PKV_T, hi - lo, D, v_new + src, stride, lane, sx, sc);
         return;
     }
     for (int tok = lo; tok < hi; ++tok) {
