@@ -184,7 +184,7 @@ __global__ __launch_bounds__(NT) void k_resize(PoolDev p, ModelDev m, int64_t ta
 // (in blocks) among the earlier entries of its sequence in this list, 0 if there is none.
 __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, const int32_t *ops, BookResult *res, uint32_t *err) {
     __shared__ int s_wave[NW];
-    __shared__ int s_cur[PKV_MAX_SEQS];             // row length after the entries walked so far
+    __shared__ int s_cur[PKV_MAX_SEQS];             // row lengths: as the call finds them, then with its wants
     __shared__ int s_start[PKV_MAX_BATCH_OPS + 1];  // first rank of entry i
     __shared__ uint32_t s_ent[PKV_MAX_BATCH_OPS];   // entry i: sequence << 20 | row length before the entry
     __shared__ uint32_t s_free[NT], s_fid[NT];      // placement: free bits of frame j's current word, its frame id
@@ -206,9 +206,9 @@ __global__ __launch_bounds__(NT) void k_reserve(PoolDev p, ModelDev m, int n, co
     const int64_t owned = m.counters[0], spare = m.counters[1];
     const int wpf = m.wpf, slots = m.slots;
     uint32_t pre_bits[PRE_WORDS];
-#pragma unroll
     // (list positions the model does not own yet are read too, and never looked at: the address then does
     // not wait for the count of owned frames to arrive)
+#pragma unroll
     for (int w = 0; w < PRE_WORDS; ++w) pre_bits[w] = (tid < p.n_frames && w < wpf) ? m.bits[(int64_t)tid * wpf + w] : 0u;
     const uint32_t pre_frame = tid < p.n_frames ? m.frames[tid] : 0u;
     for (int s = tid; s < m.max_seqs; s += NT) s_cur[s] = m.row_len[s];
