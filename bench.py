@@ -218,22 +218,23 @@ def append_latency(gpu, torch, rep, inputs):
     return res
 
 
-def prefill_leg(gpu, torch, condition_ms=1000):
+def prefill_leg(gpu, torch, condition_ms=1000, dtype=0):
     """Chunked prefill on one model of the headline workload's shape (32 q heads, 8 kv heads, head dim
-    128, bf16 cache): 8 sequences with 2048 cached tokens each take a chunk of 512.  Reports device time
-    per call and the rate of useful attention flops (4 * D * heads * visible (query, key) pairs)."""
+    128; dtype 0: bf16 cache, 1: e4m3 cache): 8 sequences with 2048 cached tokens each take a chunk of 512.
+    Reports device time per call and the rate of useful attention flops (4 * D * heads * visible (query,
+    key) pairs)."""
     import numpy as np
     from workloads import gen
     hq, hkv, d, B, prefix, chunk = 32, 8, 128, 8, 2048, 512
     pool = gpu.pool_create(8 << 30, 16, 2 << 20)
     assert pool >= 0 and gpu.pool_seed_free_order(pool, gen.free_order((8 << 30) // (2 << 20), gen.generator(5))) == 0
-    m = gpu.model_register(pool, hq, hkv, d, 0, B, 1024)
+    m = gpu.model_register(pool, hq, hkv, d, dtype, B, 1024)
     ctx = prefix + chunk
     assert m >= 0 and gpu.balloon_resize(m, 1024) == 1024
     assert gpu.seq_reserve_batch(m, list(range(B)), [ctx] * B) >= 0
     for s in range(B):
-        kv = gen.seq_kv((3, s), ctx, hkv, d, 0, 16)
-        assert gpu.kv_write(m, s, 0, kv["k"], kv["v"]) == ctx
+        kv = gen.seq_kv((3, s), ctx, hkv, d, dtype, 16)
+        assert gpu.kv_write(m, s, 0, kv["k"], kv["v"], kv["k_scale"], kv["v_scale"]) == ctx
     g = torch.Generator(device="cpu"); g.manual_seed(1)
     q = torch.randn((B * chunk, hq, d), generator=g).to(torch.bfloat16).view(torch.int16).cuda()
     out = torch.empty((B * chunk, hq, d), dtype=torch.float32, device="cuda")
@@ -269,7 +270,8 @@ def prefill_leg(gpu, torch, condition_ms=1000):
         gpu.seq_release(m, s)
     gpu.balloon_resize(m, 0); gpu.model_unregister(m); gpu.pool_destroy(pool)
     tf = flops / ms / 1e9
-    return {"workload": "8 sequences x (2048 cached + 512 new tokens), 32 q heads / 8 kv heads / head dim 128, bf16 cache",
+    return {"workload": "8 sequences x (2048 cached + 512 new tokens), 32 q heads / 8 kv heads / head dim 128, "
+                        + ("bf16" if dtype == 0 else "e4m3") + " cache",
             "us_per_call": round(ms * 1e3, 1), "useful_tflops": round(tf, 1), "gflop_per_call": round(flops / 1e9, 1),
             "kv_append_chunk_us": round(append_us, 1),
             "roofline": {"bound": "mfma", "achieved": round(tf, 1), "peak": 2500.0, "unit": "TFLOP/s", "frac": round(tf / 2500.0, 4)}}
@@ -627,6 +629,8 @@ def main():
         result["balloon_resize"] = balloon_latency(gpu, torch)
         result["kv_append"] = append_latency(gpu, torch, reps[0], inputs[0])
         result["prefill_attention"] = prefill_leg(gpu, torch, min(args.condition_ms, 1000))
+        e4 = prefill_leg(gpu, torch, min(args.condition_ms, 500), dtype=1)
+        result["prefill_attention"]["e4m3_cache"] = {k: e4[k] for k in ("us_per_call", "useful_tflops", "kv_append_chunk_us")}
         result["policies"] = policy_leg()
     if args.cpu_seconds > 0:
         result["cpu_baseline"] = cpu_baseline(reps[0], args.cpu_seconds)
